@@ -1,0 +1,171 @@
+/*
+ * liblgc — per-node compression hot path of Learned Gradient Compression (LGC)
+ * for AMD MI355X (gfx950).  C ABI; no C++ or framework types cross it.
+ *
+ * The calls follow the state and the steps of the paper's Alg. 1 / Alg. 2
+ * (per-node loop of the parameter-server and ring-allreduce variants):
+ *
+ *   g       fresh gradient of this iteration            (grad Loss)
+ *   v       accumulated gradient / residual             (g_acc, g_l)
+ *   u       momentum buffer of the momentum correction  (Sec. V-A, last paragraph)
+ *   vals    the selected values g~ in ascending index order, idx their positions
+ *   latent  E_c(g~), rec = D_c(latent)                   (Sec. IV)
+ *   dense   the averaged reconstructed gradient          (Sec. V-B)
+ *
+ * Conventions (all entry points)
+ *  - Every data pointer is a DEVICE pointer owned by the caller, fp32 or uint32,
+ *    contiguous.  The library keeps no pointer after a call returns (the
+ *    autoencoder handle copies its weights when it is created).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work: they never synchronise the stream and never read
+ *    results back to the host.  Outputs are valid once the stream has drained.
+ *  - Several simulated nodes are handled in one call: `batch` nodes whose
+ *    arrays start `stride` ELEMENTS apart (node b uses base + b*stride;
+ *    stride >= n).  batch = 1 is the single-node form.
+ *  - A context owns only scratch memory.  One context serves one stream at a
+ *    time and is not thread-safe; calls on one context that overlap race.
+ *  - Argument errors are detected on the host before anything is launched and
+ *    reported as LGC_EINVAL (null pointer, n == 0, n >= 2^31, k > n, k, n or
+ *    batch beyond what the context was created for, stride < n, pointers not
+ *    4-byte aligned).  k == 0 is valid: nothing is selected.
+ *  - No exceptions cross the boundary.  lgc_last_error gives a message for the
+ *    last failing call on that context (or, with NULL, of the calling thread).
+ */
+#ifndef LGC_H
+#define LGC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lgc_ctx lgc_ctx; /* opaque: scratch for selection and autoencoder */
+typedef struct lgc_ae lgc_ae;   /* opaque: autoencoder description + device copy of its weights */
+
+typedef enum {
+    LGC_OK = 0,
+    LGC_EINVAL = 1,  /* bad argument; nothing was launched */
+    LGC_ENOMEM = 2,  /* host or device allocation failed */
+    LGC_EHIP = 3,    /* a HIP runtime call failed */
+    LGC_EDEVICE = 4  /* a kernel reported an internal failure (see lgc_stats) */
+} lgc_status;
+
+/* Create a context on HIP device `device` able to handle up to max_n elements
+ * per node, max_k selected values per node and max_batch nodes per call.
+ * Allocates all selection scratch here (device memory, a few tens of MB at the
+ * largest benchmark shape); nothing else allocates on the selection path. */
+lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint64_t max_k, int max_batch);
+void lgc_destroy(lgc_ctx *ctx);
+const char *lgc_last_error(const lgc_ctx *ctx);
+const char *lgc_status_string(lgc_status s);
+
+/*
+ * a1. Local accumulation with momentum correction — Alg. 1 / Alg. 2, first
+ * line of the layer loop (g_l = grad + g_acc), with the DGC-style momentum
+ * correction that Sec. V-A refers to:
+ *        u <- momentum*u + g ;  v <- v + u        (in place, elementwise)
+ * Three separate fp32 roundings per element, never a fused multiply-add;
+ * denormals are kept.  momentum = 0 gives the paper's line exactly.
+ * g, u, v: [batch][stride] device fp32, n valid elements per node.
+ */
+lgc_status lgc_accumulate(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n, int batch,
+                          uint64_t stride, float momentum, void *stream);
+
+/*
+ * a2. Exact top-k magnitude selection with residual update — Alg. 1 / Alg. 2:
+ * threshold, mask, g~ = mask.*g_l, g_acc keeps the rest.  Exactly k positions
+ * per node are selected (Sec. V-A fixes the size of g~): order positions by
+ * (|v| descending, index ascending) on the key bits(v) & 0x7fffffff and take
+ * the first k.  Outputs per node b:
+ *   out_idx [b*k .. b*k+k)  the selected positions, ascending
+ *   out_vals[b*k .. b*k+k)  v at those positions (bit-exact, sign kept)
+ * then v <- +0 at the selected positions, and u <- +0 there too (momentum
+ * factor masking) unless u is NULL.  Every other element of v, u is untouched.
+ * The threshold is found on the device; nothing returns to the host.
+ */
+lgc_status lgc_topk(lgc_ctx *ctx, float *v, float *u /* nullable */, uint64_t n, int batch,
+                    uint64_t stride, uint64_t k, float *out_vals, uint32_t *out_idx, void *stream);
+
+/* a1 + a2 in one pass over g, u, v.  Defined as lgc_accumulate followed by
+ * lgc_topk; the results are bit-identical to that pair. */
+lgc_status lgc_accumulate_topk(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n,
+                               int batch, uint64_t stride, float momentum, uint64_t k,
+                               float *out_vals, uint32_t *out_idx, void *stream);
+
+/*
+ * Autoencoder description — Sec. IV-C, Tables I and II: a stack of 1-D
+ * convolutions (encoder) and 1-D transposed convolutions (decoder).
+ * Each layer has kernel size 1 or 3, stride 1 or 2 and padding (ksize-1)/2, so
+ * a stride-2 layer maps length L to ceil(L/2) (encoder) and back to exactly
+ * the length its encoder counterpart consumed (decoder; the two stacks must
+ * hold the same number of stride-2 layers).  Leaky-ReLU with `slope`
+ * (0 = ReLU) follows every layer except the last of each stack.
+ * enc[0].c_in = 1 and dec[n_dec-1].c_out = 1: the input is one node's vector
+ * of k selected values.  dec[0].c_in = enc[n_enc-1].c_out.
+ * Weights (device pointers, read and COPIED during this call, which
+ * synchronises the device once):
+ *   enc_w[l]: [c_out][c_in][ksize]   enc_b[l]: [c_out]
+ *   dec_w[l]: [c_in][c_out][ksize]   dec_b[l]: [c_out]
+ */
+typedef struct {
+    int32_t c_in, c_out, ksize, stride;
+} lgc_layer;
+
+lgc_status lgc_ae_create(lgc_ae **out, int device, int n_enc, const lgc_layer *enc, int n_dec,
+                         const lgc_layer *dec, float slope, const float *const *enc_w,
+                         const float *const *enc_b, const float *const *dec_w,
+                         const float *const *dec_b);
+void lgc_ae_destroy(lgc_ae *ae);
+/* Floats per node in the latent for an input of k values: C_latent * L_latent. */
+uint64_t lgc_latent_len(const lgc_ae *ae, uint64_t k);
+
+/* a3. Encoder g^c = E_c(g~) (Sec. IV, Table I).  vals: [batch][k];
+ * latent: [batch][C_latent][L_latent] (channel-major per node).
+ * fp32 arithmetic with fp32 accumulation.  k == 0 is a no-op.
+ * The first call with a larger (k, batch, autoencoder) than seen before grows
+ * the context's activation scratch (one device allocation). */
+lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, uint64_t k, int batch,
+                      float *latent, void *stream);
+
+/* a4. Decoder g^rec = D_c(latent) (Sec. IV, Table II).  rec: [batch][k]. */
+lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, uint64_t k, int batch,
+                      float *rec, void *stream);
+
+/*
+ * a5. Placement and node average — Sec. V-B, g^rec = (1/K) sum_k g_k^rec
+ * written back at the selected positions:
+ *        dense[idx[b][j]] <- dense[idx[b][j]] + scale*vals[b][j]
+ * for nodes b = 0..batch-1 applied strictly in that order (product and sum
+ * rounded separately).  idx must be distinct within one node (lgc_topk's
+ * output is); across nodes they may repeat.  vals, idx: [batch][k];
+ * dense: [n], zero-filled by the caller beforehand.  An index >= n is skipped
+ * and counted as a device error (lgc_stats).
+ */
+lgc_status lgc_scatter(lgc_ctx *ctx, const float *vals, const uint32_t *idx, uint64_t k, int batch,
+                       float scale, float *dense, uint64_t n, void *stream);
+
+/* ---- diagnostics (never needed on the hot path) ---- */
+
+/* LGC_OPT_SELECT_PATH: 0 = automatic (sampled-threshold fast path with the
+ * exact radix path as on-device fall-back), 1 = always the exact radix path.
+ * LGC_OPT_PROFILE: 1 = bracket the streaming kernel of lgc_accumulate /
+ * lgc_topk / lgc_accumulate_topk with HIP events (read by lgc_profile_read). */
+typedef enum { LGC_OPT_SELECT_PATH = 0, LGC_OPT_PROFILE = 1 } lgc_option;
+lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value);
+
+/* Synchronises the device and reports, summed since the last call of
+ * lgc_stats: node-selections served by the fast path, node-selections that
+ * fell back to the exact path on the device, and device-side error count
+ * (bounded waits that expired, scatter indices out of range).  Returns
+ * LGC_EDEVICE if errors != 0. */
+lgc_status lgc_stats(lgc_ctx *ctx, uint64_t *fast, uint64_t *fallback, uint64_t *errors);
+
+/* Synchronises, then returns the summed duration (ms) and the number of
+ * bracketed streaming-kernel launches since the last read. */
+lgc_status lgc_profile_read(lgc_ctx *ctx, double *total_ms, uint64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LGC_H */

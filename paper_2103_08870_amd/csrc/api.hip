@@ -1,0 +1,583 @@
+// Host side of liblgc: the C ABI declared in include/lgc.h.  Validates arguments, owns the
+// scratch memory, chooses the selection path and enqueues the kernels.  Nothing here
+// synchronises or copies to the host on the hot path.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "lgc_internal.h"
+
+using namespace lgc;
+
+struct lgc_ctx {
+    int device = 0;
+    uint64_t max_n = 0, max_k = 0;
+    int max_batch = 0;
+    uint32_t cap = 0, status_stride = 0;
+    void *scratch = nullptr;  // one device allocation, carved below
+    Sel *sel = nullptr;
+    Stats *stats = nullptr;
+    unsigned long long *status[3] = {nullptr, nullptr, nullptr};
+    uint32_t *samples = nullptr, *sample_hist = nullptr, *fine_hist = nullptr, *radix_hist = nullptr;
+    uint32_t *cand_idx = nullptr, *cand_val = nullptr;
+    float *act[2] = {nullptr, nullptr};  // autoencoder activations (ping-pong), grown on demand
+    size_t act_floats = 0;
+    int opt_path = 0, opt_profile = 0;
+    std::vector<hipEvent_t> ev;  // pairs: start, stop
+    size_t ev_used = 0;
+    char err[256] = {0};
+};
+
+struct lgc_ae {
+    int device = 0;
+    float slope = 0.f;
+    std::vector<lgc_layer> enc, dec;
+    std::vector<LayerDev> enc_dev, dec_dev;
+    float *weights = nullptr;  // device copy of all weights and biases
+};
+
+static thread_local char g_err[256] = "";
+
+static lgc_status fail(lgc_ctx *ctx, lgc_status s, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    if (ctx) memcpy(ctx->err, g_err, sizeof g_err);
+    return s;
+}
+
+#define HIP_TRY(ctx, call)                                                                     \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail(ctx, e_ == hipErrorOutOfMemory ? LGC_ENOMEM : LGC_EHIP, "%s: %s", #call, \
+                        hipGetErrorString(e_));                                                \
+    } while (0)
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+        if (prev == dev) prev = -1;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// expected number of candidates above the sampled estimate, see choose_rank
+double expected_candidates(double n, double k) {
+    const double per = n / (double)kSample;
+    return k + 6.0 * sqrt(k * per) + 8.0 * per;
+}
+
+uint32_t candidate_capacity(uint64_t max_n, uint64_t max_k) {
+    double e = 1.5 * expected_candidates((double)max_n, (double)max_k) + 8192.0;
+    if (e > 2.0e9) e = 2.0e9;
+    return (uint32_t)align_up((size_t)e, kChunk);
+}
+
+// The estimate is the rank-th largest of kSample sampled keys.  With rk = k*kSample/n sampled
+// keys expected among the true top k, rank = rk + 6*sqrt(rk) + 8 leaves about six standard
+// deviations of head-room for count(candidates) >= k.
+uint32_t choose_rank(uint32_t n, uint32_t k) {
+    const double rk = (double)k * (double)kSample / (double)n;
+    return (uint32_t)ceil(rk + 6.0 * sqrt(rk) + 8.0);
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+void profile_begin(lgc_ctx *c, hipStream_t st) {
+    if (!c->opt_profile) return;
+    if (c->ev_used + 2 > c->ev.size()) {
+        if (c->ev.size() >= 2 * 8192) return;  // pool exhausted: stop bracketing until the next read
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess) return;
+        if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+        c->ev.push_back(a);
+        c->ev.push_back(b);
+    }
+    (void)hipEventRecord(c->ev[c->ev_used], st);
+}
+void profile_end(lgc_ctx *c, hipStream_t st) {
+    if (!c->opt_profile || c->ev_used + 2 > c->ev.size()) return;
+    (void)hipEventRecord(c->ev[c->ev_used + 1], st);
+    c->ev_used += 2;
+}
+
+lgc_status check_common(lgc_ctx *ctx, uint64_t n, int batch, uint64_t stride) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    if (n == 0) return fail(ctx, LGC_EINVAL, "n == 0");
+    if (n >= (1ull << 31)) return fail(ctx, LGC_EINVAL, "n = %llu is not below 2^31", (unsigned long long)n);
+    if (n > ctx->max_n) return fail(ctx, LGC_EINVAL, "n = %llu exceeds the context's max_n = %llu",
+                                    (unsigned long long)n, (unsigned long long)ctx->max_n);
+    if (batch < 1 || batch > ctx->max_batch)
+        return fail(ctx, LGC_EINVAL, "batch = %d outside [1, %d]", batch, ctx->max_batch);
+    if (batch > 1 && stride < n) return fail(ctx, LGC_EINVAL, "stride < n");
+    return LGC_OK;
+}
+
+SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, uint64_t stride, float m,
+                  uint64_t k, float *out_vals, uint32_t *out_idx) {
+    SelArgs a;
+    memset(&a, 0, sizeof a);
+    a.g = g; a.u = u; a.v = v;
+    a.stride = stride; a.n = (uint32_t)n; a.k = (uint32_t)k; a.momentum = m;
+    a.rank = 0; a.cap = c->cap; a.status_stride = c->status_stride;
+    a.spin_limit = 1u << 22;
+    a.force = 0;
+    a.sel = c->sel; a.stats = c->stats;
+    for (int i = 0; i < 3; ++i) a.status[i] = c->status[i];
+    a.samples = c->samples; a.sample_hist = c->sample_hist; a.fine_hist = c->fine_hist;
+    a.radix_hist = c->radix_hist; a.cand_idx = c->cand_idx; a.cand_val = c->cand_val;
+    a.out_vals = out_vals; a.out_idx = out_idx;
+    return a;
+}
+
+// accumulate (optional) + select; g == nullptr means selection only
+lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n, int batch, uint64_t stride,
+                      float m, uint64_t k, float *out_vals, uint32_t *out_idx, hipStream_t st) {
+    const bool fused = g != nullptr;
+    const bool vec = aligned(v, 16) && (!u || aligned(u, 16)) && (!g || aligned(g, 16)) &&
+                     (batch == 1 || stride % 4 == 0);
+    if (k == 0) {
+        if (fused) {
+            profile_begin(ctx, st);
+            launch_accumulate(g, u, v, (uint32_t)n, batch, stride, m, vec, st);
+            profile_end(ctx, st);
+        }
+        return LGC_OK;
+    }
+    SelArgs a = make_args(ctx, g, u, v, n, stride, m, k, out_vals, out_idx);
+    const uint32_t chunks_n = (uint32_t)((n + kChunk - 1) / kChunk);
+    const uint32_t chunks_cand = (ctx->cap + kChunk - 1) / kChunk;
+    bool fast = ctx->opt_path == 0 && n >= kMinFastN;
+    if (fast) {
+        a.rank = choose_rank((uint32_t)n, (uint32_t)k);
+        fast = a.rank <= kSample / 4 &&
+               1.5 * expected_candidates((double)n, (double)k) + 4096.0 <= (double)ctx->cap;
+    }
+    launch_clear(a, batch, chunks_n, chunks_cand, st);
+    if (fast) {
+        launch_sample(a, batch, fused, st);
+        profile_begin(ctx, st);
+        launch_candidates(a, batch, fused, vec, st);
+        profile_end(ctx, st);
+        launch_select_candidates(a, batch, st);
+        launch_output_from_candidates(a, batch, st);
+        a.force = 0;
+    } else {
+        if (fused) {
+            profile_begin(ctx, st);
+            launch_accumulate(g, u, v, (uint32_t)n, batch, stride, m, vec, st);
+            profile_end(ctx, st);
+        }
+        a.force = 1;
+    }
+    // exact path: runs when forced, otherwise only for nodes the fast path handed back
+    for (int p = 0; p < 3; ++p) launch_radix_pass(a, batch, p, vec, st);
+    launch_exact_output(a, batch, vec, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return LGC_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ context
+
+extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint64_t max_k, int max_batch) {
+    if (!out) return fail(nullptr, LGC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (max_n == 0 || max_n >= (1ull << 31)) return fail(nullptr, LGC_EINVAL, "max_n must be in [1, 2^31)");
+    if (max_k > max_n) return fail(nullptr, LGC_EINVAL, "max_k > max_n");
+    if (max_batch < 1 || max_batch > 4096) return fail(nullptr, LGC_EINVAL, "max_batch must be in [1, 4096]");
+    int ndev = 0;
+    HIP_TRY(nullptr, hipGetDeviceCount(&ndev));
+    if (device < 0 || device >= ndev) return fail(nullptr, LGC_EINVAL, "no HIP device %d", device);
+    DeviceGuard guard(device);
+    if (!guard.ok) return fail(nullptr, LGC_EHIP, "cannot select device %d", device);
+
+    lgc_ctx *c = new (std::nothrow) lgc_ctx;
+    if (!c) return fail(nullptr, LGC_ENOMEM, "out of host memory");
+    c->device = device; c->max_n = max_n; c->max_k = max_k; c->max_batch = max_batch;
+    c->cap = candidate_capacity(max_n, max_k);
+    const uint32_t chunks_n = (uint32_t)((max_n + kChunk - 1) / kChunk);
+    const uint32_t chunks_c = (c->cap + kChunk - 1) / kChunk;
+    c->status_stride = chunks_n > chunks_c ? chunks_n : chunks_c;
+
+    const size_t B = (size_t)max_batch, A = 256;
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, A); return o; };
+    const size_t o_sel = carve(B * sizeof(Sel));
+    const size_t o_stats = carve(sizeof(Stats));
+    size_t o_status[3];
+    for (int i = 0; i < 3; ++i) o_status[i] = carve(B * c->status_stride * 8);
+    const size_t o_samples = carve(B * kSample * 4);
+    const size_t o_shist = carve(B * kSampleBins * 4);
+    const size_t o_fine = carve(B * kFineBins * 4);
+    const size_t o_radix = carve(B * 3 * kRadixBins * 4);
+    const size_t o_cidx = carve(B * (size_t)c->cap * 4);
+    const size_t o_cval = carve(B * (size_t)c->cap * 4);
+    hipError_t e = hipMalloc(&c->scratch, off);
+    if (e != hipSuccess) {
+        delete c;
+        return fail(nullptr, LGC_ENOMEM, "hipMalloc of %zu bytes of scratch: %s", off, hipGetErrorString(e));
+    }
+    e = hipMemset(c->scratch, 0, off);
+    if (e != hipSuccess) {
+        (void)hipFree(c->scratch);
+        delete c;
+        return fail(nullptr, LGC_EHIP, "hipMemset: %s", hipGetErrorString(e));
+    }
+    char *base = (char *)c->scratch;
+    c->sel = (Sel *)(base + o_sel);
+    c->stats = (Stats *)(base + o_stats);
+    for (int i = 0; i < 3; ++i) c->status[i] = (unsigned long long *)(base + o_status[i]);
+    c->samples = (uint32_t *)(base + o_samples);
+    c->sample_hist = (uint32_t *)(base + o_shist);
+    c->fine_hist = (uint32_t *)(base + o_fine);
+    c->radix_hist = (uint32_t *)(base + o_radix);
+    c->cand_idx = (uint32_t *)(base + o_cidx);
+    c->cand_val = (uint32_t *)(base + o_cval);
+    *out = c;
+    return LGC_OK;
+}
+
+extern "C" void lgc_destroy(lgc_ctx *ctx) {
+    if (!ctx) return;
+    DeviceGuard guard(ctx->device);
+    (void)hipDeviceSynchronize();
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+    if (ctx->act[0]) (void)hipFree(ctx->act[0]);
+    if (ctx->scratch) (void)hipFree(ctx->scratch);
+    delete ctx;
+}
+
+extern "C" const char *lgc_last_error(const lgc_ctx *ctx) { return ctx ? ctx->err : g_err; }
+
+extern "C" const char *lgc_status_string(lgc_status s) {
+    switch (s) {
+        case LGC_OK: return "ok";
+        case LGC_EINVAL: return "invalid argument";
+        case LGC_ENOMEM: return "out of memory";
+        case LGC_EHIP: return "HIP runtime error";
+        case LGC_EDEVICE: return "device-side failure";
+    }
+    return "unknown status";
+}
+
+// ------------------------------------------------------------------ a1, a2
+
+extern "C" lgc_status lgc_accumulate(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n, int batch,
+                                     uint64_t stride, float momentum, void *stream) {
+    lgc_status s = check_common(ctx, n, batch, stride);
+    if (s != LGC_OK) return s;
+    if (!g || !u || !v) return fail(ctx, LGC_EINVAL, "g, u and v must not be NULL");
+    if (!aligned(g, 4) || !aligned(u, 4) || !aligned(v, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    return run_select(ctx, g, u, v, n, batch, stride, momentum, 0, nullptr, nullptr, (hipStream_t)stream);
+}
+
+static lgc_status check_select(lgc_ctx *ctx, uint64_t n, uint64_t k, const float *out_vals, const uint32_t *out_idx) {
+    if (k > n) return fail(ctx, LGC_EINVAL, "k = %llu > n = %llu", (unsigned long long)k, (unsigned long long)n);
+    if (k > ctx->max_k) return fail(ctx, LGC_EINVAL, "k = %llu exceeds the context's max_k = %llu",
+                                    (unsigned long long)k, (unsigned long long)ctx->max_k);
+    if (k > 0 && (!out_vals || !out_idx)) return fail(ctx, LGC_EINVAL, "out_vals and out_idx must not be NULL");
+    if (!aligned(out_vals, 4) || !aligned(out_idx, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    return LGC_OK;
+}
+
+extern "C" lgc_status lgc_topk(lgc_ctx *ctx, float *v, float *u, uint64_t n, int batch, uint64_t stride,
+                               uint64_t k, float *out_vals, uint32_t *out_idx, void *stream) {
+    lgc_status s = check_common(ctx, n, batch, stride);
+    if (s != LGC_OK) return s;
+    if (!v) return fail(ctx, LGC_EINVAL, "v must not be NULL");
+    if (!aligned(v, 4) || !aligned(u, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    if ((s = check_select(ctx, n, k, out_vals, out_idx)) != LGC_OK) return s;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    return run_select(ctx, nullptr, u, v, n, batch, stride, 0.f, k, out_vals, out_idx, (hipStream_t)stream);
+}
+
+extern "C" lgc_status lgc_accumulate_topk(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n,
+                                          int batch, uint64_t stride, float momentum, uint64_t k,
+                                          float *out_vals, uint32_t *out_idx, void *stream) {
+    lgc_status s = check_common(ctx, n, batch, stride);
+    if (s != LGC_OK) return s;
+    if (!g || !u || !v) return fail(ctx, LGC_EINVAL, "g, u and v must not be NULL");
+    if (!aligned(g, 4) || !aligned(u, 4) || !aligned(v, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    if ((s = check_select(ctx, n, k, out_vals, out_idx)) != LGC_OK) return s;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    return run_select(ctx, g, u, v, n, batch, stride, momentum, k, out_vals, out_idx, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------ autoencoder
+
+static bool layer_ok(const lgc_layer &l) {
+    return l.c_in >= 1 && l.c_out >= 1 && l.c_in <= 4096 && l.c_out <= 4096 && (l.ksize == 1 || l.ksize == 3) &&
+           (l.stride == 1 || l.stride == 2);
+}
+
+extern "C" lgc_status lgc_ae_create(lgc_ae **out, int device, int n_enc, const lgc_layer *enc, int n_dec,
+                                    const lgc_layer *dec, float slope, const float *const *enc_w,
+                                    const float *const *enc_b, const float *const *dec_w,
+                                    const float *const *dec_b) {
+    if (!out) return fail(nullptr, LGC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (n_enc < 1 || n_dec < 1 || n_enc > 64 || n_dec > 64 || !enc || !dec || !enc_w || !enc_b || !dec_w || !dec_b)
+        return fail(nullptr, LGC_EINVAL, "bad autoencoder description");
+    int strided_enc = 0, strided_dec = 0;
+    for (int l = 0; l < n_enc; ++l) {
+        if (!layer_ok(enc[l]) || !enc_w[l] || !enc_b[l]) return fail(nullptr, LGC_EINVAL, "bad encoder layer %d", l);
+        if (l > 0 && enc[l].c_in != enc[l - 1].c_out) return fail(nullptr, LGC_EINVAL, "encoder layer %d: channel mismatch", l);
+        strided_enc += enc[l].stride == 2;
+    }
+    for (int l = 0; l < n_dec; ++l) {
+        if (!layer_ok(dec[l]) || !dec_w[l] || !dec_b[l]) return fail(nullptr, LGC_EINVAL, "bad decoder layer %d", l);
+        if (l > 0 && dec[l].c_in != dec[l - 1].c_out) return fail(nullptr, LGC_EINVAL, "decoder layer %d: channel mismatch", l);
+        strided_dec += dec[l].stride == 2;
+    }
+    if (enc[0].c_in != 1 || dec[n_dec - 1].c_out != 1) return fail(nullptr, LGC_EINVAL, "input and output must have one channel");
+    if (dec[0].c_in != enc[n_enc - 1].c_out) return fail(nullptr, LGC_EINVAL, "decoder input channels != latent channels");
+    if (strided_enc != strided_dec) return fail(nullptr, LGC_EINVAL, "encoder and decoder differ in stride-2 layers");
+    int ndev = 0;
+    HIP_TRY(nullptr, hipGetDeviceCount(&ndev));
+    if (device < 0 || device >= ndev) return fail(nullptr, LGC_EINVAL, "no HIP device %d", device);
+    DeviceGuard guard(device);
+    if (!guard.ok) return fail(nullptr, LGC_EHIP, "cannot select device %d", device);
+
+    lgc_ae *ae = new (std::nothrow) lgc_ae;
+    if (!ae) return fail(nullptr, LGC_ENOMEM, "out of host memory");
+    ae->device = device; ae->slope = slope;
+    ae->enc.assign(enc, enc + n_enc);
+    ae->dec.assign(dec, dec + n_dec);
+    size_t total = 0;
+    auto wsize = [](const lgc_layer &l) { return align_up((size_t)l.c_in * l.c_out * l.ksize, 64); };
+    auto bsize = [](const lgc_layer &l) { return align_up((size_t)l.c_out, 64); };
+    for (auto &l : ae->enc) total += wsize(l) + bsize(l);
+    for (auto &l : ae->dec) total += wsize(l) + bsize(l);
+    hipError_t e = hipMalloc((void **)&ae->weights, total * 4);
+    if (e != hipSuccess) { delete ae; return fail(nullptr, LGC_ENOMEM, "hipMalloc of autoencoder weights: %s", hipGetErrorString(e)); }
+    size_t off = 0;
+    auto take = [&](const lgc_layer &l, const float *w, const float *b, std::vector<LayerDev> &dst) -> hipError_t {
+        LayerDev d{l.c_in, l.c_out, l.ksize, l.stride, ae->weights + off, nullptr};
+        hipError_t r = hipMemcpy(ae->weights + off, w, (size_t)l.c_in * l.c_out * l.ksize * 4, hipMemcpyDeviceToDevice);
+        if (r != hipSuccess) return r;
+        off += wsize(l);
+        d.b = ae->weights + off;
+        r = hipMemcpy(ae->weights + off, b, (size_t)l.c_out * 4, hipMemcpyDeviceToDevice);
+        off += bsize(l);
+        dst.push_back(d);
+        return r;
+    };
+    for (int l = 0; l < n_enc && e == hipSuccess; ++l) e = take(enc[l], enc_w[l], enc_b[l], ae->enc_dev);
+    for (int l = 0; l < n_dec && e == hipSuccess; ++l) e = take(dec[l], dec_w[l], dec_b[l], ae->dec_dev);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipFree(ae->weights);
+        delete ae;
+        return fail(nullptr, LGC_EHIP, "copying autoencoder weights: %s", hipGetErrorString(e));
+    }
+    *out = ae;
+    return LGC_OK;
+}
+
+extern "C" void lgc_ae_destroy(lgc_ae *ae) {
+    if (!ae) return;
+    DeviceGuard guard(ae->device);
+    (void)hipDeviceSynchronize();
+    if (ae->weights) (void)hipFree(ae->weights);
+    delete ae;
+}
+
+static uint64_t conv_len(uint64_t l_in, const lgc_layer &l) {
+    if (l_in == 0) return 0;
+    const uint64_t pad = (l.ksize - 1) / 2;
+    return (l_in + 2 * pad - l.ksize) / l.stride + 1;
+}
+
+// lengths after each encoder layer: [k, L1, ..., L_latent]
+static std::vector<uint64_t> enc_lengths(const lgc_ae *ae, uint64_t k) {
+    std::vector<uint64_t> v{k};
+    for (auto &l : ae->enc) v.push_back(conv_len(v.back(), l));
+    return v;
+}
+
+// output length of each decoder layer: a stride-1 layer keeps the length, the strided layers
+// restore, last consumed first, the lengths the strided encoder layers consumed
+static std::vector<uint64_t> dec_lengths(const lgc_ae *ae, uint64_t k) {
+    std::vector<uint64_t> el = enc_lengths(ae, k), consumed, out;
+    for (size_t i = 0; i < ae->enc.size(); ++i)
+        if (ae->enc[i].stride == 2) consumed.push_back(el[i]);
+    uint64_t cur = el.back();
+    for (auto &l : ae->dec) {
+        if (l.stride == 2) { cur = consumed.back(); consumed.pop_back(); }
+        out.push_back(cur);
+    }
+    return out;
+}
+
+extern "C" uint64_t lgc_latent_len(const lgc_ae *ae, uint64_t k) {
+    if (!ae) return 0;
+    return enc_lengths(ae, k).back() * (uint64_t)ae->enc.back().c_out;
+}
+
+static lgc_status ensure_act(lgc_ctx *ctx, size_t floats) {
+    if (floats <= ctx->act_floats) return LGC_OK;
+    if (ctx->act[0]) { HIP_TRY(ctx, hipFree(ctx->act[0])); ctx->act[0] = ctx->act[1] = nullptr; ctx->act_floats = 0; }
+    floats = align_up(floats, 64);
+    HIP_TRY(ctx, hipMalloc((void **)&ctx->act[0], 2 * floats * 4));
+    ctx->act[1] = ctx->act[0] + floats;
+    ctx->act_floats = floats;
+    return LGC_OK;
+}
+
+static lgc_status check_ae_call(lgc_ctx *ctx, const lgc_ae *ae, const void *a, const void *b, uint64_t k, int batch) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    if (!ae) return fail(ctx, LGC_EINVAL, "ae is NULL");
+    if (ae->device != ctx->device) return fail(ctx, LGC_EINVAL, "autoencoder and context live on different devices");
+    if (batch < 1 || batch > ctx->max_batch) return fail(ctx, LGC_EINVAL, "batch = %d outside [1, %d]", batch, ctx->max_batch);
+    if (k > ctx->max_k) return fail(ctx, LGC_EINVAL, "k exceeds the context's max_k");
+    if (k > 0 && (!a || !b)) return fail(ctx, LGC_EINVAL, "NULL data pointer");
+    if (!aligned(a, 4) || !aligned(b, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    return LGC_OK;
+}
+
+extern "C" lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, uint64_t k, int batch,
+                                 float *latent, void *stream) {
+    lgc_status s = check_ae_call(ctx, ae, vals, latent, k, batch);
+    if (s != LGC_OK) return s;
+    if (k == 0) return LGC_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    hipStream_t st = (hipStream_t)stream;
+    std::vector<uint64_t> len = enc_lengths(ae, k);
+    const size_t nl = ae->enc.size();
+    size_t need = 0;
+    for (size_t l = 0; l + 1 < nl; ++l) {
+        size_t f = (size_t)batch * ae->enc[l].c_out * len[l + 1];
+        if (f > need) need = f;
+    }
+    if ((s = ensure_act(ctx, need)) != LGC_OK) return s;
+    const float *cur = vals;
+    for (size_t l = 0; l < nl; ++l) {
+        const bool last = l + 1 == nl;
+        float *dst = last ? latent : ctx->act[l & 1];
+        launch_conv1d(cur, dst, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, !last, ae->slope, st);
+        cur = dst;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return LGC_OK;
+}
+
+extern "C" lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, uint64_t k, int batch,
+                                 float *rec, void *stream) {
+    lgc_status s = check_ae_call(ctx, ae, latent, rec, k, batch);
+    if (s != LGC_OK) return s;
+    if (k == 0) return LGC_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    hipStream_t st = (hipStream_t)stream;
+    std::vector<uint64_t> out_len = dec_lengths(ae, k);
+    uint64_t in_len = enc_lengths(ae, k).back();
+    const size_t nl = ae->dec.size();
+    size_t need = 0;
+    for (size_t l = 0; l + 1 < nl; ++l) {
+        size_t f = (size_t)batch * ae->dec[l].c_out * out_len[l];
+        if (f > need) need = f;
+    }
+    if ((s = ensure_act(ctx, need)) != LGC_OK) return s;
+    const float *cur = latent;
+    for (size_t l = 0; l < nl; ++l) {
+        const bool last = l + 1 == nl;
+        float *dst = last ? rec : ctx->act[l & 1];
+        launch_conv_transpose1d(cur, dst, ae->dec_dev[l], (uint32_t)in_len, (uint32_t)out_len[l], batch, !last,
+                                ae->slope, st);
+        cur = dst;
+        in_len = out_len[l];
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return LGC_OK;
+}
+
+// ------------------------------------------------------------------ a5
+
+extern "C" lgc_status lgc_scatter(lgc_ctx *ctx, const float *vals, const uint32_t *idx, uint64_t k, int batch,
+                                  float scale, float *dense, uint64_t n, void *stream) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    if (n == 0 || n >= (1ull << 31)) return fail(ctx, LGC_EINVAL, "n must be in [1, 2^31)");
+    if (batch < 1 || batch > ctx->max_batch) return fail(ctx, LGC_EINVAL, "batch = %d outside [1, %d]", batch, ctx->max_batch);
+    if (k > n) return fail(ctx, LGC_EINVAL, "k > n");
+    if (!dense || (k > 0 && (!vals || !idx))) return fail(ctx, LGC_EINVAL, "NULL data pointer");
+    if (!aligned(vals, 4) || !aligned(idx, 4) || !aligned(dense, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    for (int b = 0; b < batch; ++b)
+        launch_scatter(vals + (size_t)b * k, idx + (size_t)b * k, (uint32_t)k, scale, dense, (uint32_t)n, ctx->stats,
+                       (hipStream_t)stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return LGC_OK;
+}
+
+// ------------------------------------------------------------------ diagnostics
+
+extern "C" lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    switch (opt) {
+        case LGC_OPT_SELECT_PATH:
+            if (value != 0 && value != 1) return fail(ctx, LGC_EINVAL, "LGC_OPT_SELECT_PATH takes 0 or 1");
+            ctx->opt_path = (int)value;
+            return LGC_OK;
+        case LGC_OPT_PROFILE:
+            ctx->opt_profile = value != 0;
+            return LGC_OK;
+    }
+    return fail(ctx, LGC_EINVAL, "unknown option %d", (int)opt);
+}
+
+extern "C" lgc_status lgc_stats(lgc_ctx *ctx, uint64_t *fast, uint64_t *fallback, uint64_t *errors) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    Stats h;
+    HIP_TRY(ctx, hipMemcpy(&h, ctx->stats, sizeof h, hipMemcpyDeviceToHost));
+    HIP_TRY(ctx, hipMemset(ctx->stats, 0, sizeof h));
+    if (fast) *fast = h.fast;
+    if (fallback) *fallback = h.fallback;
+    if (errors) *errors = h.errors;
+    if (h.errors) return fail(ctx, LGC_EDEVICE, "%u device-side failures since the last lgc_stats", h.errors);
+    return LGC_OK;
+}
+
+extern "C" lgc_status lgc_profile_read(lgc_ctx *ctx, double *total_ms, uint64_t *launches) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    double sum = 0.0;
+    for (size_t i = 0; i + 1 < ctx->ev_used; i += 2) {
+        float ms = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]));
+        sum += ms;
+    }
+    if (total_ms) *total_ms = sum;
+    if (launches) *launches = ctx->ev_used / 2;
+    ctx->ev_used = 0;
+    return LGC_OK;
+}

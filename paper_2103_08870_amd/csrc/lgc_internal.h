@@ -1,0 +1,101 @@
+// Internal declarations shared by the translation units of liblgc (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lgc.h"
+
+namespace lgc {
+
+// ---- geometry of the streaming / ordered-compaction kernels -----------------
+constexpr int kBlock = 256;                     // threads per block (4 wavefronts of 64)
+constexpr int kRows = 4;                        // float4 rows per thread
+constexpr int kRowElems = kBlock * 4;           // 1024 elements per row
+constexpr int kChunk = kRowElems * kRows;       // 4096 elements per block
+constexpr int kWaves = kBlock / 64;
+
+// ---- threshold estimate from a sample --------------------------------------
+constexpr uint32_t kSample = 65536;             // sampled keys per node
+constexpr uint32_t kSampleGroups = kSample / 4; // sampled in groups of 4 neighbours
+constexpr int kSampleBins = 2048;               // first level: key >> 20
+constexpr uint32_t kMinFastN = 1u << 20;        // below this the exact path is used directly
+
+// ---- histogram of the candidates above the estimate -------------------------
+constexpr int kFineBins = 4096;
+constexpr int kFineShift = 12;
+
+// ---- exact radix select over the full vector (3 passes: 11 + 10 + 10 bits) --
+constexpr int kRadixBins = 2048;
+
+// Per-node selection state, device memory.  Cleared by k_clear at the start of
+// every selection call.
+struct Sel {
+    uint32_t t_est;       // fast path: candidates are the elements with key >= t_est
+    uint32_t cand_total;  // number of candidates found
+    uint32_t thr;         // exact k-th largest key T*
+    uint32_t quota;       // how many elements with key == T* are taken (lowest indices first)
+    uint32_t fast_ok;     // 1: the fast path produced this node's output
+    uint32_t wait_failed; // a bounded wait expired in the candidate pass
+    uint32_t prefix;      // radix select: digits fixed so far
+    uint32_t need;        // radix select: rank still to find inside the prefix
+    uint32_t ticket[3];   // chunk tickets of the three ordered-compaction launches
+    uint32_t done[4];     // finished-block counters (sample, radix pass 0..2)
+    uint32_t pad;
+};
+static_assert(sizeof(Sel) == 64, "Sel is one 64-byte record");
+
+struct Stats {
+    uint32_t fast, fallback, errors, pad;
+};
+
+// Everything the selection kernels need; passed by value.
+struct SelArgs {
+    const float *g;   // fresh gradient (fused source only)
+    float *u;         // momentum buffer (nullable for plain selection)
+    float *v;         // accumulated gradient
+    uint64_t stride;  // elements between nodes
+    uint32_t n;       // elements per node
+    uint32_t k;       // selected per node
+    float momentum;
+    uint32_t rank;    // rank of the sample's order statistic used as estimate
+    uint32_t cap;     // candidate capacity per node
+    uint32_t status_stride;   // status words per node in each status array
+    uint32_t spin_limit;      // bound of the look-back wait
+    int force;                // exact path chosen by the host (ignore fast_ok)
+    Sel *sel;
+    Stats *stats;
+    unsigned long long *status[3]; // look-back status arrays (candidate pass, output pass, exact pass)
+    uint32_t *samples;        // [batch][kSample]
+    uint32_t *sample_hist;    // [batch][kSampleBins]
+    uint32_t *fine_hist;      // [batch][kFineBins]
+    uint32_t *radix_hist;     // [batch][3][kRadixBins]
+    uint32_t *cand_idx;       // [batch][cap]
+    uint32_t *cand_val;       // [batch][cap]
+    float *out_vals;          // [batch][k]
+    uint32_t *out_idx;        // [batch][k]
+};
+
+// launchers (topk.hip) — all asynchronous on `st`
+void launch_accumulate(const float *g, float *u, float *v, uint32_t n, int batch, uint64_t stride,
+                       float momentum, bool vec, hipStream_t st);
+void launch_clear(const SelArgs &a, int batch, uint32_t chunks_n, uint32_t chunks_cand, hipStream_t st);
+void launch_sample(const SelArgs &a, int batch, bool fused, hipStream_t st);
+void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
+void launch_select_candidates(const SelArgs &a, int batch, hipStream_t st);
+void launch_output_from_candidates(const SelArgs &a, int batch, hipStream_t st);
+void launch_radix_pass(const SelArgs &a, int batch, int pass, bool vec, hipStream_t st);
+void launch_exact_output(const SelArgs &a, int batch, bool vec, hipStream_t st);
+
+// autoencoder.hip
+struct LayerDev {
+    int c_in, c_out, ksize, stride;
+    const float *w, *b;  // device
+};
+void launch_conv1d(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out,
+                   int batch, bool act, float slope, hipStream_t st);
+void launch_conv_transpose1d(const float *in, float *out, const LayerDev &l, uint32_t l_in,
+                             uint32_t l_out, int batch, bool act, float slope, hipStream_t st);
+void launch_scatter(const float *vals, const uint32_t *idx, uint32_t k, float scale, float *dense,
+                    uint32_t n, Stats *stats, hipStream_t st);
+
+}  // namespace lgc

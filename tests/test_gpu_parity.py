@@ -1,0 +1,382 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by
+element on the same seeded inputs.  Integer / index / bit-pattern work must match exactly
+(indices, selected values, residual v, momentum u, scatter result); the autoencoder must stay
+within 1e-4 relative L2 of the fp64-accumulating oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2103_08870_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL_L2_TOL = 1e-4   # bar for the autoencoder outputs (fp32 accumulation vs the oracle's fp64)
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2103_08870_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def same_bits(t: torch.Tensor, a: np.ndarray) -> bool:
+    h = t.detach().cpu().numpy()
+    return h.shape == a.shape and bool((h.view(np.uint32) == a.view(np.uint32)).all())
+
+
+def rel_l2(t: torch.Tensor, a: np.ndarray) -> float:
+    h = t.detach().cpu().numpy().astype(np.float64).ravel()
+    a = a.astype(np.float64).ravel()
+    return float(np.linalg.norm(h - a) / max(np.linalg.norm(a), 1e-300))
+
+
+# ------------------------------------------------------------------------------ a1
+
+@pytest.mark.parametrize("n,batch,pad", [(1, 1, 0), (5, 1, 0), (4096, 1, 0), (4097, 2, 3), (1_000_003, 3, 1),
+                                         (2_500_000, 2, 0)])
+def test_accumulate(B, oracle, n, batch, pad):
+    rng = np.random.default_rng(n)
+    stride = n + pad
+    ctx = B.Context(max(n, 16), 1, batch)
+    u = (rng.standard_normal((batch, stride)) * 1e-3).astype(np.float32)
+    v = (rng.standard_normal((batch, stride)) * 1e-2).astype(np.float32)
+    u[0, :min(n, 4)] = np.array([1e-42, -1e-45, 0.0, -0.0], np.float32)[:min(n, 4)]   # denormals stay
+    du, dv = dev(u), dev(v)
+    for t in range(3):
+        g = (rng.standard_normal((batch, stride)) * 1e-3).astype(np.float32)
+        dg = dev(g)
+        B.lgc_accumulate(ctx, dg[:, :n], du[:, :n], dv[:, :n], 0.9)
+        for b in range(batch):
+            oracle.accumulate(g[b, :n].copy(), u[b, :n], v[b, :n], 0.9)
+        assert same_bits(du, u) and same_bits(dv, v), (n, t)      # padding untouched too
+    ctx.close()
+
+
+def test_accumulate_unaligned_base(B, oracle):
+    n = 100_001
+    rng = np.random.default_rng(0)
+    ctx = B.Context(n, 1, 1)
+    g, u, v = [rng.standard_normal(n + 1).astype(np.float32) for _ in range(3)]
+    dg, du, dv = dev(g), dev(u), dev(v)
+    B.lgc_accumulate(ctx, dg[1:], du[1:], dv[1:], 0.5)
+    oracle.accumulate(g[1:].copy(), u[1:], v[1:], 0.5)
+    assert same_bits(du, u) and same_bits(dv, v)
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------ a2
+
+def run_topk(B, oracle, ctx, v0, u0, k, expect_path=None):
+    """v0, u0: [batch][n] numpy (u0 may be None).  Compares everything bit for bit."""
+    batch, n = v0.shape
+    dv = dev(v0)
+    du = dev(u0) if u0 is not None else None
+    ovals = torch.full((batch, k), 7.0, device="cuda")
+    oidx = torch.full((batch, k), -1, device="cuda", dtype=torch.int32)
+    B.lgc_topk(ctx, dv, du, k, ovals, oidx)
+    fast, fallback, errors = B.lgc_stats(ctx)
+    assert errors == 0
+    if expect_path == "fast":
+        assert fast == batch and fallback == 0
+    elif expect_path == "fallback":
+        assert fallback == batch and fast == 0
+    elif expect_path == "exact":
+        assert fast == 0 and fallback == 0
+    for b in range(batch):
+        v1 = v0[b].copy()
+        u1 = u0[b].copy() if u0 is not None else None
+        vals, idx = oracle.topk(v1, u1, k)
+        assert (oidx[b].cpu().numpy().astype(np.uint32) == idx).all(), (b, n, k)
+        assert same_bits(ovals[b], vals)
+        assert same_bits(dv[b], v1)
+        if u0 is not None:
+            assert same_bits(du[b], u1)
+
+
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 1000, 4096, 4097, 50_000, 300_001])
+def test_topk_exact_path_small(B, oracle, n):
+    rng = np.random.default_rng(n)
+    ctx = B.Context(n, n, 2)
+    ks = sorted({0, 1, 2, n // 1000 + 1, n // 7, n - 1, n} & set(range(n + 1)))
+    for k in ks:
+        v0 = rng.standard_normal((2, n)).astype(np.float32)
+        u0 = rng.standard_normal((2, n)).astype(np.float32)
+        run_topk(B, oracle, ctx, v0, u0 if k % 2 == 0 else None, k, "exact" if k else None)
+        # few distinct magnitudes: ties everywhere, mixed signs
+        v0 = (rng.integers(-5, 6, (2, n)) * 0.125).astype(np.float32)
+        run_topk(B, oracle, ctx, v0, u0, k, "exact" if k else None)
+    ctx.close()
+
+
+def test_topk_special_values(B, oracle):
+    ctx = B.Context(4096, 4096, 1)
+    v0 = np.array([[0.0, -0.0, -0.0, 0.0, -0.0]], np.float32)
+    run_topk(B, oracle, ctx, v0, None, 3)
+    v0 = np.array([[1e-45, -3e-45, 2e-45, 0.0, 1e-44]], np.float32)            # denormals
+    run_topk(B, oracle, ctx, v0, None, 2)
+    v0 = np.array([[1.0, np.inf, -5.0, np.nan, 3.0, -np.inf, 2.0]], np.float32)
+    run_topk(B, oracle, ctx, v0, None, 3)
+    v0 = np.full((1, 3000), 0.125, np.float32)                                  # all equal
+    v0[0, ::3] *= -1
+    run_topk(B, oracle, ctx, v0, np.ones((1, 3000), np.float32), 777)
+    ctx.close()
+
+
+@pytest.mark.parametrize("n,k", [(1 << 20, 1024), (1_300_007, 1300), (3_000_001, 300), (2_000_000, 60_000)])
+def test_topk_fast_path_and_forced_exact(B, oracle, n, k):
+    rng = np.random.default_rng(k)
+    ctx = B.Context(n, k, 2)
+    v0 = rng.laplace(0, 1e-3, (2, n)).astype(np.float32)
+    u0 = rng.standard_normal((2, n)).astype(np.float32)
+    run_topk(B, oracle, ctx, v0, u0, k, "fast")
+    B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 1)
+    run_topk(B, oracle, ctx, v0, u0, k, "exact")
+    ctx.close()
+
+
+def test_topk_falls_back_on_device(B, oracle):
+    # all magnitudes equal: every element is a candidate, the list overflows, the device
+    # switches to the exact path by itself; node 1 is ordinary and stays on the fast path
+    n, k = 1 << 20, 2000
+    rng = np.random.default_rng(1)
+    ctx = B.Context(n, k, 2)
+    v0 = np.empty((2, n), np.float32)
+    v0[0] = 0.5
+    v0[0, ::2] = -0.5
+    v0[1] = rng.standard_normal(n)
+    dv = dev(v0)
+    ovals = torch.zeros((2, k), device="cuda")
+    oidx = torch.zeros((2, k), device="cuda", dtype=torch.int32)
+    B.lgc_topk(ctx, dv, None, k, ovals, oidx)
+    assert B.lgc_stats(ctx) == (1, 1, 0)
+    for b in range(2):
+        v1 = v0[b].copy()
+        vals, idx = oracle.topk(v1, None, k)
+        assert (oidx[b].cpu().numpy().astype(np.uint32) == idx).all()
+        assert same_bits(ovals[b], vals) and same_bits(dv[b], v1)
+    ctx.close()
+
+
+def test_topk_heavy_tail_beyond_histogram_range(B, oracle):
+    # more than k elements far above the estimate: the k-th key lies in the histogram's
+    # open-ended last bin and is found by the radix passes over the candidates
+    n, k = 1 << 20, 1500
+    rng = np.random.default_rng(2)
+    v0 = (rng.standard_normal((1, n)) * 1e-6).astype(np.float32)
+    # slightly more than k spikes, nine orders of magnitude above the rest
+    v0[0, 5000:5000 + 1600] = (rng.standard_normal(1600) * 100 + 1000).astype(np.float32)
+    ctx = B.Context(n, k, 1)
+    run_topk(B, oracle, ctx, v0, None, k)
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------ a1+a2 fused
+
+def run_iterations(B, oracle, w, ks, iters, force_exact=False, check_every=1):
+    n, K = w.n, w.nodes
+    ctx = B.Context(n, max(ks), K)
+    if force_exact:
+        B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 1)
+    du = torch.zeros((K, n), device="cuda")
+    dv = torch.zeros((K, n), device="cuda")
+    u = np.zeros((K, n), np.float32)
+    v = np.zeros((K, n), np.float32)
+    for t in range(iters):
+        k = ks[t % len(ks)]
+        dg = synth.gradients(w, t, device="cuda", k_for_ties=ks)
+        g = dg.cpu().numpy()
+        ovals = torch.zeros((K, k), device="cuda")
+        oidx = torch.zeros((K, k), device="cuda", dtype=torch.int32)
+        B.lgc_accumulate_topk(ctx, dg, du, dv, w.momentum, k, ovals, oidx)
+        fast, fallback, errors = B.lgc_stats(ctx)
+        assert errors == 0
+        for b in range(K):
+            oracle.accumulate(g[b], u[b], v[b], w.momentum)
+            vals, idx = oracle.topk(v[b], u[b], k)
+            assert (oidx[b].cpu().numpy().astype(np.uint32) == idx).all(), (t, b)
+            assert same_bits(ovals[b], vals), (t, b)
+        if t % check_every == 0 or t == iters - 1:
+            assert same_bits(dv, v) and same_bits(du, u), t
+    ctx.close()
+    return fast, fallback
+
+
+@pytest.mark.parametrize("cfg,n", [(1, None), (2, 2_000_003), (3, 1_500_000), (4, 2_100_000), (5, 1 << 21)])
+def test_fused_iterations_match_oracle(B, oracle, cfg, n):
+    w = synth.workload(cfg, n=n, nodes=min(synth.workload(cfg).nodes, 3))
+    fast, fallback = run_iterations(B, oracle, w, w.ks, iters=4)
+    assert fast + fallback == w.nodes
+
+
+def test_fused_exact_path_iterations(B, oracle):
+    w = synth.workload(2, n=1_200_000, nodes=2)
+    run_iterations(B, oracle, w, w.ks, iters=3, force_exact=True)
+    w = synth.workload(5, n=300_000, nodes=1)          # below the fast path's minimum size
+    run_iterations(B, oracle, w, w.ks, iters=3)
+
+
+def test_fused_equals_accumulate_then_topk(B):
+    w = synth.workload(2, n=1_500_000, nodes=2)
+    k = w.k
+    ctx = B.Context(w.n, k, 2)
+    g = synth.gradients(w, 0, device="cuda")
+    u1 = torch.randn((2, w.n), device="cuda") * 1e-3
+    v1 = torch.randn((2, w.n), device="cuda") * 1e-3
+    u2, v2 = u1.clone(), v1.clone()
+    a_vals, b_vals = torch.zeros((2, k), device="cuda"), torch.zeros((2, k), device="cuda")
+    a_idx = torch.zeros((2, k), device="cuda", dtype=torch.int32)
+    b_idx = torch.zeros_like(a_idx)
+    B.lgc_accumulate_topk(ctx, g, u1, v1, 0.9, k, a_vals, a_idx)
+    B.lgc_accumulate(ctx, g, u2, v2, 0.9)
+    B.lgc_topk(ctx, v2, u2, k, b_vals, b_idx)
+    assert torch.equal(a_idx, b_idx) and torch.equal(a_vals.view(torch.int32), b_vals.view(torch.int32))
+    assert torch.equal(u1.view(torch.int32), u2.view(torch.int32))
+    assert torch.equal(v1.view(torch.int32), v2.view(torch.int32))
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------ a3, a4
+
+def make_ae(B, channels=None, paper=False, slope=0.0):
+    enc, dec = synth.paper_ae() if paper else synth.mirrored_ae(channels)
+    ew, eb, dw, db = synth.ae_weights(enc, dec, device="cuda")
+    ae = B.Autoencoder(enc, dec, ew, eb, dw, db, slope=slope)
+    host = [[t.cpu().numpy() for t in xs] for xs in (ew, eb, dw, db)]
+    return ae, enc, dec, host
+
+
+@pytest.mark.parametrize("channels,k,batch", [((1, 8, 4), 1024, 1), ((1, 8, 4), 25_600, 4), ((1, 16, 8), 44_500, 3),
+                                              ((1, 16, 8), 6_701, 2), ((1, 16, 8), 5, 2), ((1, 16, 8), 1, 1),
+                                              ((1, 16, 8), 268_435, 1)])
+def test_encode_decode(B, oracle, channels, k, batch):
+    ae, enc, dec, (ew, eb, dw, db) = make_ae(B, channels)
+    ctx = B.Context(1 << 20, 1 << 20, 8)
+    rng = np.random.default_rng(k)
+    x = rng.laplace(0, 1e-2, (batch, k)).astype(np.float32)
+    lat_len = B.lgc_latent_len(ae, k)
+    lens = oracle.encoder_lengths(k, enc)
+    assert lat_len == lens[-1] * channels[-1]
+    lat = torch.zeros((batch, lat_len), device="cuda")
+    B.lgc_encode(ctx, ae, dev(x), lat)
+    rec = torch.zeros((batch, k), device="cuda")
+    B.lgc_decode(ctx, ae, lat, rec)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        ol = oracle.encode(x[b], enc, ew, eb)
+        assert rel_l2(lat[b], ol) <= REL_L2_TOL
+        # decoder checked on the oracle's latent (so errors do not compound) and end to end
+        rec_o = oracle.decode(ol, k, enc, dec, dw, db)
+        rec2 = torch.zeros((1, k), device="cuda")
+        B.lgc_decode(ctx, ae, dev(ol.reshape(1, -1)), rec2)
+        assert rel_l2(rec2[0], rec_o) <= REL_L2_TOL
+        assert rel_l2(rec[b], rec_o) <= 2 * REL_L2_TOL
+    ctx.close(); ae.close()
+
+
+def test_paper_size_autoencoder_small_input(B, oracle):
+    # Table I / Table II layer shapes (with leaky-ReLU) on a short input
+    ae, enc, dec, (ew, eb, dw, db) = make_ae(B, paper=True, slope=0.01)
+    ctx = B.Context(1 << 16, 1 << 16, 2)
+    k = 777
+    x = np.random.default_rng(0).laplace(0, 1e-2, (2, k)).astype(np.float32)
+    lat = torch.zeros((2, B.lgc_latent_len(ae, k)), device="cuda")
+    rec = torch.zeros((2, k), device="cuda")
+    B.lgc_encode(ctx, ae, dev(x), lat)
+    B.lgc_decode(ctx, ae, lat, rec)
+    for b in range(2):
+        ol = oracle.encode(x[b], enc, ew, eb, slope=0.01)
+        assert ol.shape == (4, 49)
+        assert rel_l2(lat[b], ol) <= REL_L2_TOL
+        assert rel_l2(rec[b], oracle.decode(ol, k, enc, dec, dw, db, slope=0.01)) <= 2 * REL_L2_TOL
+    ctx.close(); ae.close()
+
+
+# ------------------------------------------------------------------------------ a5
+
+def test_scatter_nodes_in_order(B, oracle):
+    n, k, K = 100_000, 3000, 4
+    rng = np.random.default_rng(3)
+    ctx = B.Context(n, k, K)
+    common = rng.choice(n, k // 2, replace=False)          # positions that several nodes picked
+    idx = np.stack([np.sort(np.unique(np.concatenate([common, rng.choice(n, k, replace=False)]))[:k])
+                    for _ in range(K)]).astype(np.uint32)
+    vals = rng.standard_normal((K, k)).astype(np.float32)
+    dense = torch.zeros(n, device="cuda")
+    B.lgc_scatter(ctx, dev(vals), dev(idx.astype(np.int32)), 1.0 / 3.0, dense)
+    ref = np.zeros(n, np.float32)
+    for b in range(K):
+        oracle.scatter(vals[b], idx[b], 1.0 / 3.0, ref)
+    assert B.lgc_stats(ctx)[2] == 0
+    assert same_bits(dense, ref)
+    # out-of-range index: skipped and counted, nothing else disturbed
+    bad = idx[0].astype(np.int64).copy()
+    bad[5] = n + 17
+    dense2 = torch.zeros(n, device="cuda")
+    B.lgc_scatter(ctx, dev(vals[0]), dev(bad.astype(np.int32)), 1.0, dense2)
+    assert B.lgc_stats(ctx, check=False)[2] == 1
+    ref2 = np.zeros(n, np.float32)
+    keep = np.arange(k) != 5
+    oracle.scatter(vals[0][keep], idx[0][keep], 1.0, ref2)
+    assert same_bits(dense2, ref2)
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------ whole path
+
+def test_whole_path_small(B, oracle):
+    """accumulate+top-k -> encode -> decode -> scatter for two iterations, every stage checked."""
+    w = synth.workload(3, n=1_100_000, nodes=3)
+    k, K, n = w.k, w.nodes, w.n
+    ae, enc, dec, (ew, eb, dw, db) = make_ae(B, w.ae_channels)
+    ctx = B.Context(n, k, K)
+    du, dv = torch.zeros((K, n), device="cuda"), torch.zeros((K, n), device="cuda")
+    u, v = np.zeros((K, n), np.float32), np.zeros((K, n), np.float32)
+    for t in range(2):
+        dg = synth.gradients(w, t, device="cuda")
+        g = dg.cpu().numpy()
+        vals = torch.zeros((K, k), device="cuda")
+        idx = torch.zeros((K, k), device="cuda", dtype=torch.int32)
+        lat = torch.zeros((K, B.lgc_latent_len(ae, k)), device="cuda")
+        rec = torch.zeros((K, k), device="cuda")
+        dense = torch.zeros(n, device="cuda")
+        B.lgc_accumulate_topk(ctx, dg, du, dv, w.momentum, k, vals, idx)
+        B.lgc_encode(ctx, ae, vals, lat)
+        B.lgc_decode(ctx, ae, lat, rec)
+        B.lgc_scatter(ctx, rec, idx, 1.0 / K, dense)
+        assert B.lgc_stats(ctx)[2] == 0
+        ref_dense = np.zeros(n, np.float32)
+        for b in range(K):
+            oracle.accumulate(g[b], u[b], v[b], w.momentum)
+            ov, oi = oracle.topk(v[b], u[b], k)
+            assert (idx[b].cpu().numpy().astype(np.uint32) == oi).all() and same_bits(vals[b], ov)
+            ol = oracle.encode(ov, enc, ew, eb)
+            assert rel_l2(lat[b], ol) <= REL_L2_TOL
+            orec = oracle.decode(ol, k, enc, dec, dw, db)
+            assert rel_l2(rec[b], orec) <= 2 * REL_L2_TOL
+            oracle.scatter(orec, oi, 1.0 / K, ref_dense)
+        assert rel_l2(dense, ref_dense) <= 2 * REL_L2_TOL
+        assert same_bits(dv, v) and same_bits(du, u)
+    ctx.close(); ae.close()
+
+
+def test_argument_errors_on_device(B):
+    ctx = B.Context(1000, 10, 2)
+    v = torch.zeros(1000, device="cuda")
+    ov, oi = torch.zeros(10, device="cuda"), torch.zeros(10, device="cuda", dtype=torch.int32)
+    with pytest.raises(B.LgcError) as e:
+        B.lgc_topk(ctx, torch.zeros(2000, device="cuda"), None, 10, ov, oi)
+    assert e.value.status == B.LGC_EINVAL and "max_n" in str(e.value)
+    with pytest.raises(B.LgcError):
+        B.lgc_topk(ctx, v, None, 11, torch.zeros(11, device="cuda"), torch.zeros(11, device="cuda", dtype=torch.int32))
+    with pytest.raises(B.LgcError):
+        B.lgc_accumulate(ctx, torch.zeros((3, 100), device="cuda"), torch.zeros((3, 100), device="cuda"),
+                         torch.zeros((3, 100), device="cuda"), 0.9)
+    B.lgc_topk(ctx, v, None, 0, ov[:0], oi[:0])          # k == 0 is valid
+    assert B.lgc_stats(ctx) == (0, 0, 0)
+    ctx.close()
