@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the LGC per-node compression hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic gradients of the
+ResNet50-sized workload (4 simulated nodes x 25.6 M fp32 elements, k = 25 600 per node):
+fused accumulate + exact top-k (all nodes in one call), encoder, decoder, scatter/average.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+ALGO_BYTES_PER_ELEM = 20       # read g,u,v + write u,v, fp32: what accumulate+select must move
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--workload", type=int, default=2, help="1..5 (default 2: ResNet50-sized)")
+    p.add_argument("--ratio-index", type=int, default=-1, help="which of the workload's ratios")
+    p.add_argument("--grad-sets", type=int, default=0, help="distinct gradient sets kept in HBM (0 = workload's)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-kernel-events", action="store_true",
+                   help="do not bracket the streaming kernel with HIP events (roofline.achieved = null)")
+    return p.parse_args()
+
+
+def cpu_baseline(w, k, enc, dec, host_w, g_host, momentum):
+    """The oracle, as it stands, on one iteration of the same workload: accumulate + top-k +
+    encode + decode + scatter for every node, nodes on separate threads (the only parallelism
+    that cannot change its results)."""
+    import numpy as np
+    from oracle import lgc_oracle as oracle
+    K, n = g_host.shape
+    threads = min(K, os.cpu_count() or 1)
+    ew, eb, dw, db = host_w
+
+    def node(b):
+        u = np.zeros(n, np.float32)
+        v = np.zeros(n, np.float32)
+        oracle.accumulate(g_host[b], u, v, momentum)
+        vals, idx = oracle.topk(v, u, k)
+        lat = oracle.encode(vals, enc, ew, eb)
+        rec = oracle.decode(lat, k, enc, dec, dw, db)
+        return rec, idx
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        outs = list(ex.map(node, range(K)))
+    dense = np.zeros(n, np.float32)
+    for rec, idx in outs:
+        oracle.scatter(rec, idx, 1.0 / K, dense)
+    dt = time.perf_counter() - t0
+    return {"value": K * n / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+            "sample": f"1 iteration of all {K} nodes x {n} elements (zero initial state), "
+                      f"{dt:.2f} s wall on {threads} threads"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the method shards by "
+              "node, one simulated node set per GPU); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2103_08870_amd import binding as B
+    from paper_2103_08870_amd import synth
+
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2103_08870_amd import build
+        build.build()
+    B.lib()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+
+    w = synth.workload(args.workload)
+    K, n = w.nodes, w.n
+    k = w.ks[args.ratio_index]
+    sets = args.grad_sets or w.iters
+    enc, dec = synth.mirrored_ae(w.ae_channels)
+    ew, eb, dw, db = synth.ae_weights(enc, dec, device="cuda")
+    ae = B.Autoencoder(enc, dec, ew, eb, dw, db)
+    ctx = B.Context(n, k, K)
+
+    grads = [synth.gradients(w, t, device="cuda", k_for_ties=(k,)) for t in range(sets)]
+    u = torch.zeros((K, n), device="cuda")
+    v = torch.zeros((K, n), device="cuda")
+    vals = torch.zeros((K, k), device="cuda")
+    idx = torch.zeros((K, k), device="cuda", dtype=torch.int32)
+    lat = torch.zeros((K, B.lgc_latent_len(ae, k)), device="cuda")
+    rec = torch.zeros((K, k), device="cuda")
+    dense = torch.zeros(n, device="cuda")
+    clear = torch.zeros(n, device="cuda")
+
+    def step(t):
+        B.lgc_accumulate_topk(ctx, grads[t % sets], u, v, w.momentum, k, vals, idx)
+        B.lgc_encode(ctx, ae, vals, lat)
+        B.lgc_decode(ctx, ae, lat, rec)
+        B.lgc_scatter(ctx, rec, idx, 1.0 / K, dense)
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    B.lgc_stats(ctx)
+    dense.zero_()
+    if not args.no_kernel_events:
+        B.lgc_set_option(ctx, B.LGC_OPT_PROFILE, 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        step(args.warmup + t)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    B.lgc_set_option(ctx, B.LGC_OPT_PROFILE, 0)
+    kern_ms, kern_launches = B.lgc_profile_read(ctx)
+    fast, fallback, errors = B.lgc_stats(ctx)
+    assert errors == 0, "device-side failure during the timed region"
+
+    ms_per_step = dt * 1e3 / args.steps
+    value = K * n * args.steps / dt
+    roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                "traffic": None, "kernel": "k_emit<fused accumulate + candidate extraction>",
+                "algorithmic_bytes_per_launch": ALGO_BYTES_PER_ELEM * K * n}
+    if kern_launches:
+        avg_ms = kern_ms / kern_launches
+        ach = ALGO_BYTES_PER_ELEM * K * n / (avg_ms * 1e-3) / 1e9
+        roofline.update(achieved=ach, frac=ach / HBM_PEAK_GBS, kernel_avg_ms=avg_ms, launches=kern_launches)
+
+    out = {
+        "metric": "gradient elements/sec compressed (accumulate+top-k+AE encode); % of HBM peak",
+        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {w.cfg} ({w.name}-sized): {K} nodes x {n} fp32 elements, k={k}/node, "
+                               f"momentum {w.momentum}, autoencoder {'->'.join(map(str, w.ae_channels))}, "
+                               f"{sets} gradient sets resident in HBM",
+                   "step": "accumulate+top-k (fused, all nodes in one call) + encode + decode + scatter"},
+        "whole_step_hbm_frac": ALGO_BYTES_PER_ELEM * value / (HBM_PEAK_GBS * 1e9),
+        "whole_step_algorithmic_GBps": ALGO_BYTES_PER_ELEM * value / 1e9,
+        "select_path": {"fast": fast, "fallback": fallback},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        host_w = [[t.cpu().numpy() for t in xs] for xs in (ew, eb, dw, db)]
+        out["cpu_baseline"] = cpu_baseline(w, k, enc, dec, host_w, grads[0].cpu().numpy(), w.momentum)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

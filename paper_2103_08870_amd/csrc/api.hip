@@ -4,6 +4,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -17,12 +18,16 @@ struct lgc_ctx {
     int device = 0;
     uint64_t max_n = 0, max_k = 0;
     int max_batch = 0;
-    uint32_t cap = 0, status_stride = 0;
+    uint32_t cap = 0;
     void *scratch = nullptr;  // one device allocation, carved below
-    Sel *sel = nullptr;
     Stats *stats = nullptr;
-    unsigned long long *status[3] = {nullptr, nullptr, nullptr};
-    uint32_t *samples = nullptr, *sample_hist = nullptr, *fine_hist = nullptr, *radix_hist = nullptr;
+    // two state sets (Sel records, histograms, look-back status), used by alternate calls
+    uint32_t *state[2] = {nullptr, nullptr};
+    uint32_t state_words = 0;
+    int cur = 0;                      // set the next call will use (it is clean)
+    int cus = 1;                      // compute units of the device
+    uint32_t region = 1024, regions = 0, status_cand_stride = 0, status_exact_stride = 0;
+    uint32_t *samples = nullptr, *reg_count = nullptr, *reg_idx = nullptr, *reg_val = nullptr;
     uint32_t *cand_idx = nullptr, *cand_val = nullptr;
     float *act[2] = {nullptr, nullptr};  // autoencoder activations (ping-pong), grown on demand
     size_t act_floats = 0;
@@ -126,19 +131,45 @@ lgc_status check_common(lgc_ctx *ctx, uint64_t n, int batch, uint64_t stride) {
     return LGC_OK;
 }
 
+// word offsets of the parts of one state set
+struct StateLayout {
+    size_t sel, sample_hist, fine_hist, level2_hist, radix_hist, status_cand, status_exact, words;
+};
+StateLayout state_layout(int max_batch, uint32_t status_cand_stride, uint32_t status_exact_stride) {
+    StateLayout L;
+    const size_t B = (size_t)max_batch;
+    size_t o = 0;
+    L.sel = o; o += B * sizeof(Sel) / 4;
+    L.sample_hist = o; o += B * kSampleBins;
+    L.fine_hist = o; o += B * kFineBins;
+    L.level2_hist = o; o += B * kFineBins;
+    L.radix_hist = o; o += B * 3 * kRadixBins;
+    L.status_cand = o; o += B * status_cand_stride * 2;
+    L.status_exact = o; o += B * status_exact_stride * 2;
+    L.words = o;
+    return L;
+}
+
 SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, uint64_t stride, float m,
                   uint64_t k, float *out_vals, uint32_t *out_idx) {
     SelArgs a;
     memset(&a, 0, sizeof a);
     a.g = g; a.u = u; a.v = v;
     a.stride = stride; a.n = (uint32_t)n; a.k = (uint32_t)k; a.momentum = m;
-    a.rank = 0; a.cap = c->cap; a.status_stride = c->status_stride;
-    a.spin_limit = 1u << 22;
+    a.rank = 0; a.cap = c->cap; a.region = c->region; a.regions = c->regions;
+    a.status_cand_stride = c->status_cand_stride; a.status_exact_stride = c->status_exact_stride;
+    a.spin_limit = 1u << 20;
     a.force = 0;
-    a.sel = c->sel; a.stats = c->stats;
-    for (int i = 0; i < 3; ++i) a.status[i] = c->status[i];
-    a.samples = c->samples; a.sample_hist = c->sample_hist; a.fine_hist = c->fine_hist;
-    a.radix_hist = c->radix_hist; a.cand_idx = c->cand_idx; a.cand_val = c->cand_val;
+    a.stats = c->stats;
+    const StateLayout L = state_layout(c->max_batch, c->status_cand_stride, c->status_exact_stride);
+    uint32_t *cur = c->state[c->cur];
+    a.sel = (Sel *)(cur + L.sel);
+    a.sample_hist = cur + L.sample_hist; a.fine_hist = cur + L.fine_hist; a.level2_hist = cur + L.level2_hist; a.radix_hist = cur + L.radix_hist;
+    a.status_cand = (unsigned long long *)(cur + L.status_cand);
+    a.status_exact = (unsigned long long *)(cur + L.status_exact);
+    a.next_state = c->state[c->cur ^ 1]; a.next_words = c->state_words;
+    a.samples = c->samples; a.reg_count = c->reg_count; a.reg_idx = c->reg_idx; a.reg_val = c->reg_val;
+    a.cand_idx = c->cand_idx; a.cand_val = c->cand_val;
     a.out_vals = out_vals; a.out_idx = out_idx;
     return a;
 }
@@ -158,24 +189,23 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
         return LGC_OK;
     }
     SelArgs a = make_args(ctx, g, u, v, n, stride, m, k, out_vals, out_idx);
-    const uint32_t chunks_n = (uint32_t)((n + kChunk - 1) / kChunk);
-    const uint32_t chunks_cand = (ctx->cap + kChunk - 1) / kChunk;
     bool fast = ctx->opt_path == 0 && n >= kMinFastN;
     if (fast) {
         a.rank = choose_rank((uint32_t)n, (uint32_t)k);
         fast = a.rank <= kSample / 4 &&
                1.5 * expected_candidates((double)n, (double)k) + 4096.0 <= (double)ctx->cap;
     }
-    launch_clear(a, batch, chunks_n, chunks_cand, st);
+    ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
     if (fast) {
-        launch_sample(a, batch, fused, st);
+        launch_sample(a, batch, fused, vec, st);   // also clears the next call's state set
         profile_begin(ctx, st);
         launch_candidates(a, batch, fused, vec, st);
         profile_end(ctx, st);
-        launch_select_candidates(a, batch, st);
-        launch_output_from_candidates(a, batch, st);
+        launch_gather(a, batch, st);
+        launch_output_from_candidates(a, batch, expected_candidates((double)n, (double)k) <= 131072.0, st);
         a.force = 0;
     } else {
+        launch_clear(a.next_state, a.next_words, st);
         if (fused) {
             profile_begin(ctx, st);
             launch_accumulate(g, u, v, (uint32_t)n, batch, stride, m, vec, st);
@@ -184,8 +214,7 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
         a.force = 1;
     }
     // exact path: runs when forced, otherwise only for nodes the fast path handed back
-    for (int p = 0; p < 3; ++p) launch_radix_pass(a, batch, p, vec, st);
-    launch_exact_output(a, batch, vec, st);
+    launch_exact(a, batch, vec, ctx->cus, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
     return LGC_OK;
@@ -211,21 +240,43 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
     if (!c) return fail(nullptr, LGC_ENOMEM, "out of host memory");
     c->device = device; c->max_n = max_n; c->max_k = max_k; c->max_batch = max_batch;
     c->cap = candidate_capacity(max_n, max_k);
-    const uint32_t chunks_n = (uint32_t)((max_n + kChunk - 1) / kChunk);
-    const uint32_t chunks_c = (c->cap + kChunk - 1) / kChunk;
-    c->status_stride = chunks_n > chunks_c ? chunks_n : chunks_c;
+    {
+        // Elements per wavefront in the candidate pass: the grid should be a whole number of
+        // "rounds" of what the device holds at once (8 blocks of 4 wavefronts per compute
+        // unit), about four rounds, so that no tail of half-empty rounds is left.
+        hipDeviceProp_t prop;
+        hipError_t pe = hipGetDeviceProperties(&prop, device);
+        if (pe != hipSuccess) { delete c; return fail(nullptr, LGC_EHIP, "hipGetDeviceProperties: %s", hipGetErrorString(pe)); }
+        c->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+        const double resident_waves = (double)c->cus * 8 * kWaves;
+        double rounds = 4.0;
+        if (const char *e = getenv("LGC_ROUNDS")) { const double r = atof(e); if (r >= 1.0 && r <= 64.0) rounds = r; }
+        double r = ceil((double)max_n * max_batch / (resident_waves * rounds) / 64.0) * 64.0;
+        if (r < 1024.0) r = 1024.0;
+        if (r > 65536.0) r = 65536.0;
+        c->region = (uint32_t)r;
+        if (const char *e = getenv("LGC_REGION")) {  // tuning knob: fixed region size, multiple of 64
+            const long v = atol(e);
+            if (v >= 256 && v <= 65536 && v % 64 == 0) c->region = (uint32_t)v;
+        }
+    }
+    c->regions = (uint32_t)((max_n + c->region - 1) / c->region);
+    c->status_exact_stride = (uint32_t)((max_n + kChunk - 1) / kChunk);
+    c->status_cand_stride = (c->cap + kChunk - 1) / kChunk;
+    const StateLayout L = state_layout(max_batch, c->status_cand_stride, c->status_exact_stride);
+    if (L.words >= (1ull << 31)) { delete c; return fail(nullptr, LGC_EINVAL, "max_n * max_batch too large"); }
+    c->state_words = (uint32_t)L.words;
 
     const size_t B = (size_t)max_batch, A = 256;
     size_t off = 0;
     auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, A); return o; };
-    const size_t o_sel = carve(B * sizeof(Sel));
     const size_t o_stats = carve(sizeof(Stats));
-    size_t o_status[3];
-    for (int i = 0; i < 3; ++i) o_status[i] = carve(B * c->status_stride * 8);
+    const size_t o_state0 = carve(L.words * 4);
+    const size_t o_state1 = carve(L.words * 4);
     const size_t o_samples = carve(B * kSample * 4);
-    const size_t o_shist = carve(B * kSampleBins * 4);
-    const size_t o_fine = carve(B * kFineBins * 4);
-    const size_t o_radix = carve(B * 3 * kRadixBins * 4);
+    const size_t o_rcount = carve(B * c->regions * 4);
+    const size_t o_ridx = carve(B * (size_t)c->regions * (c->region / kRegionDiv) * 4);
+    const size_t o_rval = carve(B * (size_t)c->regions * (c->region / kRegionDiv) * 4);
     const size_t o_cidx = carve(B * (size_t)c->cap * 4);
     const size_t o_cval = carve(B * (size_t)c->cap * 4);
     hipError_t e = hipMalloc(&c->scratch, off);
@@ -233,20 +284,22 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
         delete c;
         return fail(nullptr, LGC_ENOMEM, "hipMalloc of %zu bytes of scratch: %s", off, hipGetErrorString(e));
     }
-    e = hipMemset(c->scratch, 0, off);
+    // only the statistics and the two state sets must start at zero
+    e = hipMemset(c->scratch, 0, o_samples);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         (void)hipFree(c->scratch);
         delete c;
         return fail(nullptr, LGC_EHIP, "hipMemset: %s", hipGetErrorString(e));
     }
     char *base = (char *)c->scratch;
-    c->sel = (Sel *)(base + o_sel);
     c->stats = (Stats *)(base + o_stats);
-    for (int i = 0; i < 3; ++i) c->status[i] = (unsigned long long *)(base + o_status[i]);
+    c->state[0] = (uint32_t *)(base + o_state0);
+    c->state[1] = (uint32_t *)(base + o_state1);
     c->samples = (uint32_t *)(base + o_samples);
-    c->sample_hist = (uint32_t *)(base + o_shist);
-    c->fine_hist = (uint32_t *)(base + o_fine);
-    c->radix_hist = (uint32_t *)(base + o_radix);
+    c->reg_count = (uint32_t *)(base + o_rcount);
+    c->reg_idx = (uint32_t *)(base + o_ridx);
+    c->reg_val = (uint32_t *)(base + o_rval);
     c->cand_idx = (uint32_t *)(base + o_cidx);
     c->cand_val = (uint32_t *)(base + o_cval);
     *out = c;

@@ -27,20 +27,23 @@ constexpr int kFineShift = 12;
 // ---- exact radix select over the full vector (3 passes: 11 + 10 + 10 bits) --
 constexpr int kRadixBins = 2048;
 
-// Per-node selection state, device memory.  Cleared by k_clear at the start of
-// every selection call.
+// ---- candidate regions: every wavefront of the candidate pass owns `region` consecutive
+// elements (a multiple of 1024) and appends its candidates, in index order, to its own slots
+constexpr int kRegionDiv = 4;                   // slots per region = region size / 4
+
+// Per-node selection state, device memory.  It lives in a "state set" together with the
+// histograms and look-back status words; there are two sets, used by alternate calls, and each
+// call clears the set of the next one.
 struct Sel {
     uint32_t t_est;       // fast path: candidates are the elements with key >= t_est
     uint32_t cand_total;  // number of candidates found
     uint32_t thr;         // exact k-th largest key T*
     uint32_t quota;       // how many elements with key == T* are taken (lowest indices first)
     uint32_t fast_ok;     // 1: the fast path produced this node's output
-    uint32_t wait_failed; // a bounded wait expired in the candidate pass
-    uint32_t prefix;      // radix select: digits fixed so far
-    uint32_t need;        // radix select: rank still to find inside the prefix
-    uint32_t ticket[3];   // chunk tickets of the three ordered-compaction launches
-    uint32_t done[4];     // finished-block counters (sample, radix pass 0..2)
-    uint32_t pad;
+    uint32_t fast_failed; // a region overflowed or a bounded wait expired: use the exact path
+    uint32_t barrier;     // exact path: arrivals at the node's barrier
+    uint32_t ticket[1];   // chunk tickets of the compaction over the candidates
+    uint32_t pad[8];
 };
 static_assert(sizeof(Sel) == 64, "Sel is one 64-byte record");
 
@@ -58,19 +61,31 @@ struct SelArgs {
     uint32_t k;       // selected per node
     float momentum;
     uint32_t rank;    // rank of the sample's order statistic used as estimate
-    uint32_t cap;     // candidate capacity per node
-    uint32_t status_stride;   // status words per node in each status array
+    uint32_t cap;     // capacity of the gathered candidate list, per node
+    uint32_t region;  // elements per candidate region
+    uint32_t regions; // candidate regions per node (stride of reg_count / reg_idx / reg_val)
+    uint32_t status_cand_stride, status_exact_stride;  // status words per node
     uint32_t spin_limit;      // bound of the look-back wait
     int force;                // exact path chosen by the host (ignore fast_ok)
-    Sel *sel;
     Stats *stats;
-    unsigned long long *status[3]; // look-back status arrays (candidate pass, output pass, exact pass)
-    uint32_t *samples;        // [batch][kSample]
+    // current state set
+    Sel *sel;
     uint32_t *sample_hist;    // [batch][kSampleBins]
     uint32_t *fine_hist;      // [batch][kFineBins]
+    uint32_t *level2_hist;    // [batch][kFineBins]
     uint32_t *radix_hist;     // [batch][3][kRadixBins]
-    uint32_t *cand_idx;       // [batch][cap]
-    uint32_t *cand_val;       // [batch][cap]
+    unsigned long long *status_cand;   // look-back status of the output pass over the candidates
+    unsigned long long *status_exact;  // look-back status of the exact pass over v
+    // state set of the next call, cleared by this one
+    uint32_t *next_state;
+    uint32_t next_words;
+    // bulk scratch
+    uint32_t *samples;        // [batch][kSample]
+    uint32_t *reg_count;      // [batch][regions]
+    uint32_t *reg_idx;        // [batch][regions][kRegionCap]
+    uint32_t *reg_val;
+    uint32_t *cand_idx;       // [batch][cap]  gathered, index-ordered
+    uint32_t *cand_val;
     float *out_vals;          // [batch][k]
     uint32_t *out_idx;        // [batch][k]
 };
@@ -78,13 +93,12 @@ struct SelArgs {
 // launchers (topk.hip) — all asynchronous on `st`
 void launch_accumulate(const float *g, float *u, float *v, uint32_t n, int batch, uint64_t stride,
                        float momentum, bool vec, hipStream_t st);
-void launch_clear(const SelArgs &a, int batch, uint32_t chunks_n, uint32_t chunks_cand, hipStream_t st);
-void launch_sample(const SelArgs &a, int batch, bool fused, hipStream_t st);
+void launch_clear(uint32_t *words, uint32_t count, hipStream_t st);
+void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
 void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
-void launch_select_candidates(const SelArgs &a, int batch, hipStream_t st);
-void launch_output_from_candidates(const SelArgs &a, int batch, hipStream_t st);
-void launch_radix_pass(const SelArgs &a, int batch, int pass, bool vec, hipStream_t st);
-void launch_exact_output(const SelArgs &a, int batch, bool vec, hipStream_t st);
+void launch_gather(const SelArgs &a, int batch, hipStream_t st);
+void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hipStream_t st);
+void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st);
 
 // autoencoder.hip
 struct LayerDev {

@@ -14,8 +14,12 @@
 //    not (or if the candidate buffer would overflow) the device itself falls back to
 //  * exact path: a 3-pass (11+10+10 bit) radix select over all of v, then an ordered
 //    compaction of v with the exact threshold.
-//  Ordered compaction uses one look-back chain over 4096-element chunks (chunk ids are handed
-//  out by an atomic ticket, so a chunk only ever waits for chunks that already run).
+//  In the candidate pass every wavefront owns 4096 consecutive elements and a private slot
+//  region, so the streaming kernel has no communication between wavefronts at all; a small
+//  gather kernel concatenates the regions (they are already in index order).
+//  The two output compactions (over the candidates; over v in the exact path) use one look-back
+//  chain over 4096-element chunks; chunk ids are handed out by an atomic ticket, so a chunk
+//  only ever waits for chunks that already run.
 #include "lgc_internal.h"
 
 namespace lgc {
@@ -130,27 +134,17 @@ void launch_accumulate(const float *g, float *u, float *v, uint32_t n, int batch
     else hipLaunchKernelGGL(k_accumulate<false>, grid, dim3(kBlock), 0, st, g, u, v, n, stride, momentum);
 }
 
-// ------------------------------------------------------------------ clearing of the scratch
+// ------------------------------------------------------------------ clearing of a state set
 
-__global__ __launch_bounds__(kBlock) void k_clear(SelArgs a, uint32_t chunks_n, uint32_t chunks_cand) {
-    const int node = blockIdx.y;
-    const uint32_t tid = blockIdx.x * kBlock + threadIdx.x, nthreads = gridDim.x * kBlock;
-    unsigned long long *s0 = a.status[0] + (size_t)node * a.status_stride;
-    unsigned long long *s1 = a.status[1] + (size_t)node * a.status_stride;
-    unsigned long long *s2 = a.status[2] + (size_t)node * a.status_stride;
-    for (uint32_t i = tid; i < chunks_n; i += nthreads) { s0[i] = 0; s2[i] = 0; }
-    for (uint32_t i = tid; i < chunks_cand; i += nthreads) s1[i] = 0;
-    for (uint32_t i = tid; i < (uint32_t)kSampleBins; i += nthreads) a.sample_hist[node * kSampleBins + i] = 0;
-    for (uint32_t i = tid; i < (uint32_t)kFineBins; i += nthreads) a.fine_hist[node * kFineBins + i] = 0;
-    for (uint32_t i = tid; i < 3u * kRadixBins; i += nthreads) a.radix_hist[node * 3 * kRadixBins + i] = 0;
-    if (tid < sizeof(Sel) / 4) ((uint32_t *)(a.sel + node))[tid] = 0;
+__global__ __launch_bounds__(kBlock) void k_clear(uint32_t *words, uint32_t count) {
+    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < count; i += gridDim.x * kBlock) words[i] = 0;
 }
 
-void launch_clear(const SelArgs &a, int batch, uint32_t chunks_n, uint32_t chunks_cand, hipStream_t st) {
-    uint32_t work = chunks_n > (uint32_t)(3 * kRadixBins) ? chunks_n : 3 * kRadixBins;
-    uint32_t blocks = (work + kBlock - 1) / kBlock;
-    if (blocks > 64) blocks = 64;
-    hipLaunchKernelGGL(k_clear, dim3(blocks, batch), dim3(kBlock), 0, st, a, chunks_n, chunks_cand);
+void launch_clear(uint32_t *words, uint32_t count, hipStream_t st) {
+    uint32_t blocks = (count + kBlock - 1) / kBlock;
+    if (blocks > 256) blocks = 256;
+    if (blocks == 0) return;
+    hipLaunchKernelGGL(k_clear, dim3(blocks), dim3(kBlock), 0, st, words, count);
 }
 
 // ------------------------------------------------------------------ sampled threshold estimate
@@ -162,67 +156,463 @@ __device__ __forceinline__ uint32_t mix32(uint32_t h) {
 
 // One group of four neighbouring elements per thread, at a jittered position inside the thread's
 // own stratum of the vector.  The keys that the accumulation WILL produce are sampled (the fused
-// source recomputes v + (m*u + g) without storing it).  The last block to finish picks the key
-// t_est = (roughly) the rank-th largest sampled key.
-template <bool FUSED>
-__global__ __launch_bounds__(kBlock) void k_sample(SelArgs a) {
+// source recomputes v + (m*u + g) without storing it); their first-level histogram (key >> 20)
+// is accumulated per block in LDS and flushed with a few atomics.
+// The kernel also clears the state set that the next call will use.
+template <bool FUSED, bool VEC>
+__global__ __launch_bounds__(1024) void k_sample(SelArgs a) {
     __shared__ uint32_t hist[kSampleBins];
-    __shared__ uint32_t wave_tmp[kWaves], res[2];
-    __shared__ uint32_t is_last;
     const int node = blockIdx.y, tid = threadIdx.x;
+    {
+        const uint32_t gt = (blockIdx.y * gridDim.x + blockIdx.x) * 1024u + tid, nt = gridDim.x * gridDim.y * 1024u;
+        for (uint32_t i = gt; i < a.next_words; i += nt) a.next_state[i] = 0;
+    }
     const size_t off = (size_t)node * a.stride;
-    const uint32_t j = blockIdx.x * kBlock + tid;  // < kSampleGroups
+    const uint32_t j = blockIdx.x * 1024u + tid;  // < kSampleGroups
     const uint32_t stratum = (a.n >> 2) / kSampleGroups;
     const uint32_t e = (j * stratum + mix32(j + 0x5bd1e995u * (uint32_t)node) % stratum) << 2;
     uint32_t *smp = a.samples + (size_t)node * kSample;
     uint32_t *sh = a.sample_hist + node * kSampleBins;
-    for (int i = tid; i < kSampleBins; i += kBlock) hist[i] = 0;
+    for (int i = tid; i < kSampleBins; i += 1024) hist[i] = 0;
     __syncthreads();
+    u4 keys;
+    f4 vv, uu = {0.f, 0.f, 0.f, 0.f}, gg = {0.f, 0.f, 0.f, 0.f};
+    if (VEC) {
+        vv = *(const f4 *)(a.v + off + e);
+        if (FUSED) { uu = *(const f4 *)(a.u + off + e); gg = *(const f4 *)(a.g + off + e); }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            vv[i] = a.v[off + e + i];
+            if (FUSED) { uu[i] = a.u[off + e + i]; gg[i] = a.g[off + e + i]; }
+        }
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        float vv = a.v[off + e + i];
-        if (FUSED) {
-            float uu = a.u[off + e + i];
-            accum1(a.g[off + e + i], uu, vv, a.momentum);
-        }
-        uint32_t key = key_of(vv);
-        smp[j * 4 + i] = key;
-        atomicAdd(&hist[key >> 20], 1u);
+        float x = uu[i], y = vv[i];
+        if (FUSED) accum1(gg[i], x, y, a.momentum);
+        keys[i] = key_of(y);
+        atomicAdd(&hist[keys[i] >> 20], 1u);
     }
+    *(u4 *)(smp + j * 4) = keys;
     __syncthreads();
-    for (int i = tid; i < kSampleBins; i += kBlock) { uint32_t h = hist[i]; if (h) atomicAdd(&sh[i], h); }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) is_last = (atomicAdd(&a.sel[node].done[0], 1u) == gridDim.x - 1);
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-    for (int i = tid; i < kSampleBins; i += kBlock) hist[i] = ld_agent32(&sh[i]);
+    for (int i = tid; i < kSampleBins; i += 1024) { uint32_t h = hist[i]; if (h) atomicAdd(&sh[i], h); }
+}
+
+// One block per node: t_est = (roughly) the rank-th largest sampled key, to 2^-13 relative
+// resolution (first level from the histogram, second level from the keys).
+__global__ __launch_bounds__(1024) void k_estimate(SelArgs a) {
+    __shared__ uint32_t hist[kSampleBins];
+    __shared__ uint32_t wave_tmp[16], res[2];
+    const int node = blockIdx.x, tid = threadIdx.x;
+    const uint32_t *smp = a.samples + (size_t)node * kSample;
+    u4 x[kSample / 4 / 1024];
+#pragma unroll
+    for (int r = 0; r < (int)(kSample / 4 / 1024); ++r) x[r] = *(const u4 *)(smp + (r * 1024 + tid) * 4);
+    for (int i = tid; i < kSampleBins; i += 1024) hist[i] = a.sample_hist[node * kSampleBins + i];
     __syncthreads();
     find_rank_bin<kSampleBins>(hist, a.rank, wave_tmp, res);
     const uint32_t b1 = res[0], need = a.rank - res[1];
     __syncthreads();
-    if (b1 == 0xffffffffu) {  // cannot happen (rank <= kSample); leave t_est = 0: everything is a candidate
-        return;
-    }
-    for (int i = tid; i < 1024; i += kBlock) hist[i] = 0;
+    if (b1 == 0xffffffffu) return;  // cannot happen (rank <= kSample); t_est stays 0: everything is a candidate
+    hist[tid] = 0;
     __syncthreads();
-    for (uint32_t i = tid; i < kSample; i += kBlock) {
-        uint32_t key = ld_agent32(&smp[i]);
-        if ((key >> 20) == b1) atomicAdd(&hist[(key >> 10) & 1023u], 1u);
+#pragma unroll
+    for (int r = 0; r < (int)(kSample / 4 / 1024); ++r) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if ((x[r][i] >> 20) == b1) atomicAdd(&hist[(x[r][i] >> 10) & 1023u], 1u);
     }
     __syncthreads();
     find_rank_bin<1024>(hist, need, wave_tmp, res);
     if (tid == 0) a.sel[node].t_est = (b1 << 20) | ((res[0] == 0xffffffffu ? 0u : res[0]) << 10);
 }
 
-void launch_sample(const SelArgs &a, int batch, bool fused, hipStream_t st) {
-    dim3 grid(kSampleGroups / kBlock, batch);
-    if (fused) hipLaunchKernelGGL(k_sample<true>, grid, dim3(kBlock), 0, st, a);
-    else hipLaunchKernelGGL(k_sample<false>, grid, dim3(kBlock), 0, st, a);
+void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st) {
+    dim3 grid(kSampleGroups / 1024, batch);
+    if (fused) {
+        if (vec) hipLaunchKernelGGL((k_sample<true, true>), grid, dim3(1024), 0, st, a);
+        else hipLaunchKernelGGL((k_sample<true, false>), grid, dim3(1024), 0, st, a);
+    } else {
+        if (vec) hipLaunchKernelGGL((k_sample<false, true>), grid, dim3(1024), 0, st, a);
+        else hipLaunchKernelGGL((k_sample<false, false>), grid, dim3(1024), 0, st, a);
+    }
+    hipLaunchKernelGGL(k_estimate, dim3(batch), dim3(1024), 0, st, a);
 }
 
-// ------------------------------------------------------------------ ordered compaction
+// ------------------------------------------------------------------ candidate pass (the streaming kernel)
+
+// FUSED: reads g,u,v, writes u,v (the accumulation) and classifies the new v; otherwise reads v.
+// Each wavefront owns a.region consecutive elements (a multiple of 64) and appends every
+// element with key >= t_est to its private slots, in index order.
+// No barrier, no LDS, no atomics, no communication between wavefronts.
+template <bool FUSED, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
+    const int node = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t region = blockIdx.x * kWaves + wave;
+    const uint32_t begin = region * a.region;
+    if (begin >= a.n) return;
+    const uint32_t end = (a.n - begin > a.region) ? begin + a.region : a.n;
+    const size_t off = (size_t)node * a.stride;
+    const float *g = a.g + off;
+    float *u = a.u + off;
+    float *v = a.v + off;
+    const uint32_t t_est = a.sel[node].t_est;
+    const uint32_t rcap = a.region / kRegionDiv;
+    const size_t rbase = ((size_t)node * a.regions + region) * rcap;
+    uint32_t *ridx = a.reg_idx + rbase, *rval = a.reg_val + rbase;
+    const float m = a.momentum;
+    uint32_t count = 0;
+
+    for (uint32_t row = begin; row < end; row += 1024) {
+        uint32_t bits[4][4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t e0 = row + s * 256 + lane * 4;
+            f4 vv = {0.f, 0.f, 0.f, 0.f};
+            if (VEC && e0 + 3 < end) {
+                if (FUSED) {
+                    f4 gg = __builtin_nontemporal_load((const f4 *)(g + e0));
+                    f4 uu = *(const f4 *)(u + e0);
+                    vv = *(const f4 *)(v + e0);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) { float x = uu[j], y = vv[j]; accum1(gg[j], x, y, m); uu[j] = x; vv[j] = y; }
+                    *(f4 *)(u + e0) = uu;
+                    *(f4 *)(v + e0) = vv;
+                } else {
+                    vv = *(const f4 *)(v + e0);
+                }
+            } else {
+                for (int j = 0; j < 4; ++j) if (e0 + j < end) {
+                    float y = v[e0 + j];
+                    if (FUSED) {
+                        float x = u[e0 + j];
+                        accum1(g[e0 + j], x, y, m);
+                        u[e0 + j] = x; v[e0 + j] = y;
+                    }
+                    vv[j] = y;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bits[s][j] = __float_as_uint(vv[j]);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t e0 = row + s * 256 + lane * 4;
+            bool f[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) f[j] = (e0 + j < end) && (bits[s][j] & 0x7fffffffu) >= t_est;
+            if (__ballot(f[0] | f[1] | f[2] | f[3]) != 0ull) {  // wave-uniform
+                uint32_t below = 0, tot = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const unsigned long long mk = __ballot(f[j]);
+                    below += lanes_below(mk);
+                    tot += (uint32_t)__popcll(mk);
+                }
+                uint32_t p = count + below;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (f[j]) {
+                        if (p < rcap) { ridx[p] = e0 + j; rval[p] = bits[s][j]; }
+                        ++p;
+                    }
+                }
+                count += tot;
+            }
+        }
+    }
+    if (lane == 0) a.reg_count[(size_t)node * a.regions + region] = count;
+}
+
+void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st) {
+    const uint32_t nreg = (a.n + a.region - 1) / a.region;
+    dim3 grid((nreg + kWaves - 1) / kWaves, batch);
+    if (fused) {
+        if (vec) hipLaunchKernelGGL((k_candidates<true, true>), grid, dim3(kBlock), 0, st, a);
+        else hipLaunchKernelGGL((k_candidates<true, false>), grid, dim3(kBlock), 0, st, a);
+    } else {
+        if (vec) hipLaunchKernelGGL((k_candidates<false, true>), grid, dim3(kBlock), 0, st, a);
+        else hipLaunchKernelGGL((k_candidates<false, false>), grid, dim3(kBlock), 0, st, a);
+    }
+}
+
+// ------------------------------------------------------------------ gather the regions
+
+__device__ __forceinline__ uint32_t block_sum_1024(uint32_t x, uint32_t *tmp /*[16]*/) {
+    x = wave_sum(x);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) tmp[threadIdx.x >> 6] = x;
+    __syncthreads();
+    uint32_t t = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) t += tmp[w];
+    return t;
+}
+
+// kGatherRegions regions per block of 1024 threads.  Copies each region's candidates behind those
+// of all earlier regions of the node (the regions are in index order already, so the gathered
+// list is too), counts them in the fine histogram of d = key - t_est (bins of 2^12, last bin
+// open-ended) and adds the block's count to the node's total.  The copy is balanced over the
+// block's threads by output position (binary search of the owning region), whatever the
+// spread of the counts.
+constexpr int kGatherRegions = 256;
+
+__global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
+    __shared__ uint32_t hist[kFineBins];
+    __shared__ uint32_t offs[kGatherRegions];
+    __shared__ uint32_t tmp[16];
+    const int node = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    Sel *s = a.sel + node;
+    const uint32_t nreg = (a.n + a.region - 1) / a.region;
+    const uint32_t first = blockIdx.x * (uint32_t)kGatherRegions;
+    const uint32_t rcap = a.region / kRegionDiv;
+    const uint32_t *cnt = a.reg_count + (size_t)node * a.regions;
+    const uint32_t *ridx = a.reg_idx + ((size_t)node * a.regions + first) * rcap;
+    const uint32_t *rval = a.reg_val + ((size_t)node * a.regions + first) * rcap;
+    uint32_t *cidx = a.cand_idx + (size_t)node * a.cap, *cval = a.cand_val + (size_t)node * a.cap;
+
+    const uint32_t region = first + tid;
+    uint32_t c = (tid < kGatherRegions && region < nreg) ? cnt[region] : 0u;
+    const uint32_t t_est = s->t_est;
+    uint32_t part = 0;
+    for (uint32_t i0 = tid; i0 < first; i0 += 4096) {
+        uint32_t x[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = (i0 + r * 1024 < first) ? cnt[i0 + r * 1024] : 0u;
+        part += x[0] + x[1] + x[2] + x[3];
+    }
+    for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
+    const uint32_t before = block_sum_1024(part, tmp);   // contains barriers: hist is zeroed for all
+    if (c > rcap) { s->fast_failed = 1; c = rcap; }      // lost candidates: the node goes to the exact path
+    // exclusive scan of c over the first kGatherRegions threads
+    uint32_t incl = c;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += y;
+    }
+    __syncthreads();
+    if (lane == 63) tmp[wave] = incl;
+    __syncthreads();
+    uint32_t excl = incl - c, block_total = 0;
+#pragma unroll
+    for (int w = 0; w < kGatherRegions / 64; ++w) { if (w < wave) excl += tmp[w]; block_total += tmp[w]; }
+    if (tid < kGatherRegions) offs[tid] = excl;
+    if (tid == 0 && block_total) atomicAdd(&s->cand_total, block_total);
+    __syncthreads();
+
+    for (uint32_t p = tid; p < block_total; p += 1024) {
+        // last region r with offs[r] <= p: it is the one that holds output position p
+        uint32_t r = 0;
+#pragma unroll
+        for (int step = kGatherRegions / 2; step >= 1; step >>= 1)
+            if (offs[r + step] <= p) r += step;
+        const uint32_t i = p - offs[r];
+        const uint32_t ix = ridx[(size_t)r * rcap + i], vb = rval[(size_t)r * rcap + i];
+        const uint32_t q = before + p;
+        if (q < a.cap) { cidx[q] = ix; cval[q] = vb; }
+        const uint32_t d = ((vb & 0x7fffffffu) - t_est) >> kFineShift;
+        atomicAdd(&hist[d < (uint32_t)kFineBins - 1 ? d : (uint32_t)kFineBins - 1], 1u);
+    }
+    __syncthreads();
+    uint32_t *fine = a.fine_hist + node * kFineBins;
+    for (int i = tid; i < kFineBins; i += 1024) { const uint32_t h = hist[i]; if (h) atomicAdd(&fine[i], h); }
+}
+
+void launch_gather(const SelArgs &a, int batch, hipStream_t st) {
+    const uint32_t nreg = (a.n + a.region - 1) / a.region;
+    hipLaunchKernelGGL(k_gather, dim3((nreg + kGatherRegions - 1) / kGatherRegions, batch), dim3(1024), 0, st, a);
+}
+
+// Adds, for every candidate i < total that passes `member`, one count to hist[digit(d)], where
+// d = key - t_est.  Four independent 16-byte loads are issued before their LDS atomics.
+template <typename Member, typename Digit>
+__device__ __forceinline__ void count_candidates(const uint32_t *cval, uint32_t total, uint32_t t_est,
+                                                 uint32_t *hist, Member member, Digit digit) {
+    const uint32_t tid = threadIdx.x, nt = blockDim.x, n4 = total >> 2;
+    for (uint32_t i = tid; i < n4; i += 4 * nt) {
+        u4 x[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t ii = i + r * nt;
+            x[r] = ii < n4 ? *(const u4 *)(cval + ii * 4) : (u4){0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (i + r * nt < n4) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t d = (x[r][c] & 0x7fffffffu) - t_est;
+                    if (member(d)) atomicAdd(&hist[digit(d)], 1u);
+                }
+            }
+        }
+    }
+    for (uint32_t i = (n4 << 2) + tid; i < total; i += nt) {
+        const uint32_t d = (cval[i] & 0x7fffffffu) - t_est;
+        if (member(d)) atomicAdd(&hist[digit(d)], 1u);
+    }
+}
+
+// ------------------------------------------------------------------ exact k-th key among the candidates
+
+// Block-wide: the exact k-th largest key T* and the number of ties to take, from the fine
+// histogram (first level, bins of 2^12 above t_est) and a second-level histogram of the low 12
+// bits inside the bin that holds the k-th key.  LOCAL = true: the second level is counted here
+// from all gathered candidates; false: it was counted by k_select_level2 into a.level2_hist.
+// Returns false (for all threads alike) if count(candidates) < k, candidates were lost, or T*
+// lies in the open-ended last bin: then the node is left to the exact path.
+template <bool LOCAL>
+__device__ bool find_threshold(const SelArgs &a, int node, uint32_t total, uint32_t *hist /*[kFineBins]*/,
+                               uint32_t *wave_tmp, uint32_t *res, uint32_t &thr, uint32_t &quota) {
+    const Sel *s = a.sel + node;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    if (s->fast_failed || total < a.k || total > a.cap) return false;
+    const uint32_t t_est = s->t_est;
+    for (int i = tid; i < kFineBins; i += nt) hist[i] = a.fine_hist[node * kFineBins + i];
+    __syncthreads();
+    find_rank_bin<kFineBins>(hist, a.k, wave_tmp, res);
+    const uint32_t bin = res[0], need = a.k - res[1];
+    __syncthreads();
+    if (bin >= (uint32_t)kFineBins - 1) return false;
+    if (LOCAL) {
+        for (int i = tid; i < kFineBins; i += nt) hist[i] = 0;
+        __syncthreads();
+        count_candidates(a.cand_val + (size_t)node * a.cap, total, t_est, hist,
+                         [=](uint32_t d) { return (d >> kFineShift) == bin; },
+                         [=](uint32_t d) { return d & ((1u << kFineShift) - 1); });
+    } else {
+        for (int i = tid; i < kFineBins; i += nt) hist[i] = a.level2_hist[node * kFineBins + i];
+    }
+    __syncthreads();
+    find_rank_bin<kFineBins>(hist, need, wave_tmp, res);
+    thr = t_est + (bin << kFineShift) + res[0];
+    quota = need - res[1];
+    __syncthreads();
+    return true;
+}
+
+// Second-level histogram for long candidate lists: many blocks, each counts a slice.
+__global__ __launch_bounds__(1024) void k_select_level2(SelArgs a) {
+    __shared__ uint32_t hist[kFineBins];
+    __shared__ uint32_t wave_tmp[16], res[2];
+    const int node = blockIdx.y, tid = threadIdx.x;
+    const Sel *s = a.sel + node;
+    const uint32_t total = s->cand_total;
+    if (s->fast_failed || total < a.k || total > a.cap) return;
+    const uint32_t t_est = s->t_est;
+    for (int i = tid; i < kFineBins; i += 1024) hist[i] = a.fine_hist[node * kFineBins + i];
+    __syncthreads();
+    find_rank_bin<kFineBins>(hist, a.k, wave_tmp, res);
+    const uint32_t bin = res[0];
+    __syncthreads();
+    if (bin >= (uint32_t)kFineBins - 1) return;
+    for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
+    __syncthreads();
+    const uint32_t per = (((total + gridDim.x - 1) / gridDim.x) + 3) & ~3u;   // slice, multiple of 4
+    const uint32_t lo = blockIdx.x * per;
+    if (lo < total) {
+        const uint32_t len = total - lo < per ? total - lo : per;
+        count_candidates(a.cand_val + (size_t)node * a.cap + lo, len, t_est, hist,
+                         [=](uint32_t d) { return (d >> kFineShift) == bin; },
+                         [=](uint32_t d) { return d & ((1u << kFineShift) - 1); });
+    }
+    __syncthreads();
+    uint32_t *l2 = a.level2_hist + node * kFineBins;
+    for (int i = tid; i < kFineBins; i += 1024) { const uint32_t h = hist[i]; if (h) atomicAdd(&l2[i], h); }
+}
+
+// Output for short candidate lists: block b (1024 threads) owns candidates [4096 b, 4096 b + 4096),
+// finds T* itself and counts the selected candidates before its own by reading them: no
+// communication between blocks.  Writes the selected elements in index order and zeroes them
+// in v (and u).
+__global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
+    __shared__ uint32_t hist[kFineBins];
+    __shared__ uint32_t wave_tmp[16], res[2], sh_pg[16], sh_pe[16], sh_tg[16], sh_te[16];
+    const int node = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    Sel *s = a.sel + node;
+    const uint32_t total = s->cand_total;
+    const uint32_t *cidx = a.cand_idx + (size_t)node * a.cap;
+    const uint32_t *cval = a.cand_val + (size_t)node * a.cap;
+    const uint32_t base = blockIdx.x * 4096u, e0 = base + tid * 4;
+    // my four candidates, loaded before the search for T* so that the latencies overlap
+    u4 ci = {0, 0, 0, 0}, cv = {0, 0, 0, 0};
+    if (total <= a.cap) {
+        if (e0 + 3 < total) { ci = *(const u4 *)(cidx + e0); cv = *(const u4 *)(cval + e0); }
+        else { for (int j = 0; j < 4; ++j) if (e0 + j < total) { ci[j] = cidx[e0 + j]; cv[j] = cval[e0 + j]; } }
+    }
+    uint32_t thr = 0, quota = 0;
+    const bool ok = find_threshold<true>(a, node, total, hist, wave_tmp, res, thr, quota);
+    if (blockIdx.x == 0 && tid == 0) {
+        s->fast_ok = ok;
+        if (ok) { s->thr = thr; s->quota = quota; }
+        atomicAdd(ok ? &a.stats->fast : &a.stats->fallback, 1u);
+    }
+    if (!ok || base >= total) return;
+
+    // selected-or-tied counts among the candidates before mine (they are L2-warm by now)
+    uint32_t pg = 0, pe = 0;
+    for (uint32_t i0 = tid; i0 < base / 4; i0 += 4096) {
+        u4 x[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            x[r] = (i0 + r * 1024 < base / 4) ? *(const u4 *)(cval + (size_t)(i0 + r * 1024) * 4) : (u4){0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (i0 + r * 1024 < base / 4) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) { const uint32_t key = x[r][c] & 0x7fffffffu; pg += key > thr; pe += key == thr; }
+            }
+        }
+    }
+    pg = wave_sum(pg); pe = wave_sum(pe);
+    uint32_t lg = 0, le = 0, tg = 0, te = 0;
+    bool fg[4], fe[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t key = cv[j] & 0x7fffffffu;
+        fg[j] = e0 + j < total && key > thr;
+        fe[j] = e0 + j < total && key == thr;
+        const unsigned long long mg = __ballot(fg[j]), me = __ballot(fe[j]);
+        lg += lanes_below(mg); tg += (uint32_t)__popcll(mg);
+        le += lanes_below(me); te += (uint32_t)__popcll(me);
+    }
+    if (lane == 0) { sh_pg[wave] = pg; sh_pe[wave] = pe; sh_tg[wave] = tg; sh_te[wave] = te; }
+    __syncthreads();
+    // flagged elements before my first one: all of the earlier blocks' candidates, the lower
+    // wavefronts of this block, the lower lanes of this wavefront
+    uint32_t cg = lg, ce = le;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        cg += sh_pg[w]; ce += sh_pe[w];
+        if (w < wave) { cg += sh_tg[w]; ce += sh_te[w]; }
+    }
+
+    if (blockIdx.x == (total - 1) / 4096 && tid == 1023) {
+        // the last thread of the last block sees everything: the selection must add up to k
+        uint32_t g_all = cg, e_all = ce;
+        for (int j = 0; j < 4; ++j) { g_all += fg[j]; e_all += fe[j]; }
+        if (g_all + (e_all < quota ? e_all : quota) != a.k) atomicAdd(&a.stats->errors, 1u);
+    }
+    float *v = a.v + (size_t)node * a.stride;
+    float *u = a.u ? a.u + (size_t)node * a.stride : nullptr;
+    uint32_t *oidx = a.out_idx + (size_t)node * a.k;
+    float *oval = a.out_vals + (size_t)node * a.k;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (fg[j] || (fe[j] && ce < quota)) {
+            const uint32_t o = cg + (ce < quota ? ce : quota);
+            if (o < a.k) { oidx[o] = ci[j]; oval[o] = __uint_as_float(cv[j]); }
+            else atomicAdd(&a.stats->errors, 1u);
+            v[ci[j]] = 0.0f;
+            if (u) u[ci[j]] = 0.0f;
+        }
+        cg += fg[j]; ce += fe[j];
+    }
+}
+
+// ------------------------------------------------------------------ ordered output compaction
 
 // status word of a chunk: [63:62] 0 = nothing yet, 1 = this chunk's own counts, 2 = counts of all
 // chunks up to and including this one; [61:31] count of "greater", [30:0] count of "equal".
@@ -230,195 +620,149 @@ __device__ __forceinline__ unsigned long long pack_status(uint32_t st, uint32_t 
     return ((unsigned long long)st << 62) | ((unsigned long long)gt << 31) | (unsigned long long)eq;
 }
 
-// SRC_FUSED: reads g,u,v, writes u,v (accumulation) and classifies the new v.
-// SRC_PLAIN: reads v.   SRC_CAND: reads the candidate list.
-// EXACT = false: "greater" means key >= t_est; such elements are appended, in index order, to
-//                the candidate list and counted in the fine histogram.
-// EXACT = true : threshold T* and tie quota are known; the selected elements are written to the
-//                output in index order and zeroed in v (and u).
-template <int SRC, bool EXACT, bool VEC>
-__global__ __launch_bounds__(kBlock) void k_emit(SelArgs a) {
-    constexpr int SLOT = (SRC == SRC_CAND) ? 1 : (EXACT ? 2 : 0);
+// The threshold T* and the tie quota are known.  The selected elements (key > T*, and the first
+// `quota` elements with key == T*) are written to the output in index order and zeroed in v
+// (and u).  SRC_CAND reads the gathered candidate list, SRC_PLAIN reads v itself (exact path).
+// Persistent blocks take 4096-element chunks by ticket; a chunk's output offset comes from a
+// look-back over the chunks before it.
+template <int SRC, bool VEC>
+__device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, const uint32_t n_src,
+                                            const uint32_t thr, const uint32_t quota) {
     __shared__ uint32_t sh_chunk;
     __shared__ uint32_t sh_gt[kRows][kWaves], sh_eq[kRows][kWaves];
     __shared__ uint32_t sh_prefix[2];
 
-    const int node = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Sel *s = a.sel + node;
-    if (SRC == SRC_CAND) { if (!s->fast_ok) return; }
-    if (SRC == SRC_PLAIN && EXACT) { if (!a.force && s->fast_ok) return; }
-
-    if (tid == 0) sh_chunk = atomicAdd(&s->ticket[SLOT], 1u);
-    __syncthreads();
-    const uint32_t chunk = sh_chunk;
-    const uint32_t n_src = (SRC == SRC_CAND) ? s->cand_total : a.n;
-    const uint32_t base = chunk * (uint32_t)kChunk;
-    if (base >= n_src) return;
     const uint32_t nchunks = (n_src + kChunk - 1) / kChunk;
-
     const size_t off = (size_t)node * a.stride;
-    const float *g = a.g + off;
     float *u = a.u ? a.u + off : nullptr;
     float *v = a.v + off;
     const uint32_t *cidx = a.cand_idx + (size_t)node * a.cap;
     const uint32_t *cval = a.cand_val + (size_t)node * a.cap;
+    unsigned long long *st = (SRC == SRC_CAND) ? a.status_cand + (size_t)node * a.status_cand_stride
+                                               : a.status_exact + (size_t)node * a.status_exact_stride;
+    uint32_t *oidx = a.out_idx + (size_t)node * a.k;
+    float *oval = a.out_vals + (size_t)node * a.k;
 
-    const uint32_t thr = EXACT ? s->thr : s->t_est;
-    const uint32_t quota = EXACT ? s->quota : 0u;
-
-    uint32_t bits[kRows][4];   // value bits of my 16 elements
-    uint32_t pos[kRows][4];    // original index (SRC_CAND only)
-    uint32_t gtm = 0, eqm = 0; // flag bit r*4+j
-
-#pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-        const uint32_t e0 = base + r * kRowElems + tid * 4;
+    for (uint32_t it = 0;; ++it) {
+        __syncthreads();
         if (SRC == SRC_CAND) {
-            u4 ci = {0, 0, 0, 0}, cv = {0, 0, 0, 0};
-            if (e0 + 3 < n_src) { ci = *(const u4 *)(cidx + e0); cv = *(const u4 *)(cval + e0); }
-            else {
-                for (int j = 0; j < 4; ++j) if (e0 + j < n_src) { ci[j] = cidx[e0 + j]; cv[j] = cval[e0 + j]; }
-            }
+            if (tid == 0) sh_chunk = atomicAdd(&s->ticket[0], 1u);
+            __syncthreads();
+        }
+        const uint32_t chunk = (SRC == SRC_CAND) ? sh_chunk : blockIdx.x + it * gridDim.x;
+        if (chunk >= nchunks) break;
+        const uint32_t base = chunk * (uint32_t)kChunk;
+
+        uint32_t bits[kRows][4];   // value bits of my 16 elements
+        uint32_t pos[kRows][4];    // original index (SRC_CAND only)
+        uint32_t gtm = 0, eqm = 0; // flag bit r*4+j
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { pos[r][j] = ci[j]; bits[r][j] = cv[j]; }
-        } else if (SRC == SRC_PLAIN) {
-            f4 vv = {0.f, 0.f, 0.f, 0.f};
-            if (VEC && e0 + 3 < n_src) vv = *(const f4 *)(v + e0);
-            else { for (int j = 0; j < 4; ++j) if (e0 + j < n_src) vv[j] = v[e0 + j]; }
+        for (int r = 0; r < kRows; ++r) {
+            const uint32_t e0 = base + r * kRowElems + tid * 4;
+            if (SRC == SRC_CAND) {
+                u4 ci = {0, 0, 0, 0}, cv = {0, 0, 0, 0};
+                if (e0 + 3 < n_src) { ci = *(const u4 *)(cidx + e0); cv = *(const u4 *)(cval + e0); }
+                else {
+                    for (int j = 0; j < 4; ++j) if (e0 + j < n_src) { ci[j] = cidx[e0 + j]; cv[j] = cval[e0 + j]; }
+                }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bits[r][j] = __float_as_uint(vv[j]);
-        } else {
-            f4 vv = {0.f, 0.f, 0.f, 0.f};
-            if (VEC && e0 + 3 < n_src) {
-                f4 gg = __builtin_nontemporal_load((const f4 *)(g + e0));
-                f4 uu = *(const f4 *)(u + e0);
-                vv = *(const f4 *)(v + e0);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) { float x = uu[j], y = vv[j]; accum1(gg[j], x, y, a.momentum); uu[j] = x; vv[j] = y; }
-                *(f4 *)(u + e0) = uu;
-                *(f4 *)(v + e0) = vv;
+                for (int j = 0; j < 4; ++j) { pos[r][j] = ci[j]; bits[r][j] = cv[j]; }
             } else {
-                for (int j = 0; j < 4; ++j) if (e0 + j < n_src) {
-                    float x = u[e0 + j], y = v[e0 + j];
-                    accum1(g[e0 + j], x, y, a.momentum);
-                    u[e0 + j] = x; v[e0 + j] = y; vv[j] = y;
+                f4 vv = {0.f, 0.f, 0.f, 0.f};
+                if (VEC && e0 + 3 < n_src) vv = *(const f4 *)(v + e0);
+                else { for (int j = 0; j < 4; ++j) if (e0 + j < n_src) vv[j] = v[e0 + j]; }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bits[r][j] = __float_as_uint(vv[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool valid = e0 + j < n_src;
+                const uint32_t key = bits[r][j] & 0x7fffffffu;
+                gtm |= (uint32_t)(valid && key > thr) << (r * 4 + j);
+                eqm |= (uint32_t)(valid && key == thr) << (r * 4 + j);
+            }
+        }
+
+        // position of my flagged elements inside the chunk, in index order (row, wave, lane, j)
+        uint32_t lane_gt[kRows], lane_eq[kRows];
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            uint32_t lg = 0, le = 0, tg = 0, te = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const unsigned long long mg = __ballot((gtm >> (r * 4 + j)) & 1u);
+                const unsigned long long me = __ballot((eqm >> (r * 4 + j)) & 1u);
+                lg += lanes_below(mg); tg += (uint32_t)__popcll(mg);
+                le += lanes_below(me); te += (uint32_t)__popcll(me);
+            }
+            lane_gt[r] = lg; lane_eq[r] = le;
+            if (lane == 0) { sh_gt[r][wave] = tg; sh_eq[r][wave] = te; }
+        }
+        __syncthreads();
+        uint32_t off_gt[kRows], off_eq[kRows], blk_gt = 0, blk_eq = 0;
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                if (w == wave) { off_gt[r] = blk_gt; off_eq[r] = blk_eq; }
+                blk_gt += sh_gt[r][w]; blk_eq += sh_eq[r][w];
+            }
+        }
+
+        // look-back over the preceding chunks (first wavefront only)
+        if (wave == 0) {
+            uint32_t pg = 0, pe = 0;
+            if (chunk == 0) {
+                if (lane == 0) st_agent(&st[0], pack_status(2, blk_gt, blk_eq));
+            } else {
+                if (lane == 0) st_agent(&st[chunk], pack_status(1, blk_gt, blk_eq));
+                int first = (int)chunk - 1;
+                uint32_t spins = 0;
+                bool failed = false;
+                while (first >= 0) {
+                    const int jn = first - lane;
+                    const bool valid = jn >= 0;
+                    unsigned long long w = 0;
+                    while (true) {
+                        if (valid) w = ld_agent(&st[jn]);
+                        const bool ready = !valid || (w >> 62) != 0;
+                        if (__all(ready)) break;
+                        if (++spins > a.spin_limit) { failed = true; break; }
+                        __builtin_amdgcn_s_sleep(2);
+                    }
+                    if (failed) break;
+                    const unsigned long long incl = __ballot(valid && (w >> 62) == 2);
+                    const int nearest = incl ? (__ffsll((long long)incl) - 1) : 64;
+                    const bool take = valid && lane <= nearest;
+                    pg += wave_sum(take ? (uint32_t)((w >> 31) & 0x7fffffffu) : 0u);
+                    pe += wave_sum(take ? (uint32_t)(w & 0x7fffffffu) : 0u);
+                    if (incl) break;
+                    first -= 64;
                 }
+                if (failed && lane == 0) atomicAdd(&a.stats->errors, 1u);
+                if (lane == 0) st_agent(&st[chunk], pack_status(2, pg + blk_gt, pe + blk_eq));
             }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bits[r][j] = __float_as_uint(vv[j]);
+            if (lane == 0) { sh_prefix[0] = pg; sh_prefix[1] = pe; }
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool valid = e0 + j < n_src;
-            const uint32_t key = bits[r][j] & 0x7fffffffu;
-            const bool fg = valid && (EXACT ? key > thr : key >= thr);
-            const bool fe = EXACT && valid && key == thr;
-            gtm |= (uint32_t)fg << (r * 4 + j);
-            eqm |= (uint32_t)fe << (r * 4 + j);
-        }
-    }
+        __syncthreads();
+        const uint32_t pre_gt = sh_prefix[0], pre_eq = sh_prefix[1];
 
-    // position of my flagged elements inside the block, in index order (row, wave, lane, j)
-    uint32_t lane_gt[kRows], lane_eq[kRows];
-#pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-        uint32_t lg = 0, le = 0, tg = 0, te = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            unsigned long long m = __ballot((gtm >> (r * 4 + j)) & 1u);
-            lg += lanes_below(m); tg += __popcll(m);
-            if (EXACT) {
-                unsigned long long me = __ballot((eqm >> (r * 4 + j)) & 1u);
-                le += lanes_below(me); te += __popcll(me);
-            }
-        }
-        lane_gt[r] = lg; lane_eq[r] = le;
-        if (lane == 0) { sh_gt[r][wave] = tg; sh_eq[r][wave] = te; }
-    }
-    __syncthreads();
-    uint32_t off_gt[kRows], off_eq[kRows], blk_gt = 0, blk_eq = 0;
-#pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            if (w == wave) { off_gt[r] = blk_gt; off_eq[r] = blk_eq; }
-            blk_gt += sh_gt[r][w]; blk_eq += sh_eq[r][w];
-        }
-    }
-
-    // look-back over the preceding chunks (first wave only)
-    if (wave == 0) {
-        unsigned long long *st = a.status[SLOT] + (size_t)node * a.status_stride;
-        uint32_t pg = 0, pe = 0;
-        if (chunk == 0) {
-            if (lane == 0) st_agent(&st[0], pack_status(2, blk_gt, blk_eq));
-        } else {
-            if (lane == 0) st_agent(&st[chunk], pack_status(1, blk_gt, blk_eq));
-            int first = (int)chunk - 1;
-            uint32_t spins = 0;
-            bool failed = false;
-            while (first >= 0) {
-                const int jn = first - lane;
-                const bool valid = jn >= 0;
-                unsigned long long w = 0;
-                while (true) {
-                    if (valid) w = ld_agent(&st[jn]);
-                    const bool ready = !valid || (w >> 62) != 0;
-                    if (__all(ready)) break;
-                    if (++spins > a.spin_limit) { failed = true; break; }
-                    __builtin_amdgcn_s_sleep(2);
-                }
-                if (failed) break;
-                const unsigned long long incl = __ballot(valid && (w >> 62) == 2);
-                const int nearest = incl ? (__ffsll((long long)incl) - 1) : 64;
-                const bool take = valid && lane <= nearest;
-                pg += wave_sum(take ? (uint32_t)((w >> 31) & 0x7fffffffu) : 0u);
-                pe += wave_sum(take ? (uint32_t)(w & 0x7fffffffu) : 0u);
-                if (incl) break;
-                first -= 64;
-            }
-            if (failed && lane == 0) {
-                atomicAdd(&a.stats->errors, 1u);
-                s->wait_failed = 1;
-            }
-            if (lane == 0) st_agent(&st[chunk], pack_status(2, pg + blk_gt, pe + blk_eq));
-        }
-        if (lane == 0) { sh_prefix[0] = pg; sh_prefix[1] = pe; }
-    }
-    __syncthreads();
-    const uint32_t pre_gt = sh_prefix[0], pre_eq = sh_prefix[1];
-
-    if (tid == 0 && chunk == nchunks - 1) {
-        if (!EXACT) s->cand_total = pre_gt + blk_gt;
-        else {
+        if (tid == 0 && chunk == nchunks - 1) {
             const uint32_t te = pre_eq + blk_eq;
             if (pre_gt + blk_gt + (te < quota ? te : quota) != a.k) atomicAdd(&a.stats->errors, 1u);
         }
-    }
-
-    if ((gtm | eqm) == 0) return;
-
-    uint32_t *oidx = a.out_idx + (size_t)node * a.k;
-    float *oval = a.out_vals + (size_t)node * a.k;
-    uint32_t *widx = a.cand_idx + (size_t)node * a.cap;
-    uint32_t *wval = a.cand_val + (size_t)node * a.cap;
-    uint32_t *fine = a.fine_hist + node * kFineBins;
+        if ((gtm | eqm) == 0) continue;
 
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-        uint32_t cg = pre_gt + off_gt[r] + lane_gt[r];
-        uint32_t ce = pre_eq + off_eq[r] + lane_eq[r];
-        const uint32_t e0 = base + r * kRowElems + tid * 4;
+        for (int r = 0; r < kRows; ++r) {
+            uint32_t cg = pre_gt + off_gt[r] + lane_gt[r];
+            uint32_t ce = pre_eq + off_eq[r] + lane_eq[r];
+            const uint32_t e0 = base + r * kRowElems + tid * 4;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool fg = (gtm >> (r * 4 + j)) & 1u, fe = (eqm >> (r * 4 + j)) & 1u;
-            if (!EXACT) {
-                if (fg) {
-                    if (cg < a.cap) { widx[cg] = e0 + j; wval[cg] = bits[r][j]; }
-                    uint32_t d = ((bits[r][j] & 0x7fffffffu) - thr) >> kFineShift;
-                    atomicAdd(&fine[d < (uint32_t)kFineBins - 1 ? d : (uint32_t)kFineBins - 1], 1u);
-                }
-            } else {
+            for (int j = 0; j < 4; ++j) {
+                const bool fg = (gtm >> (r * 4 + j)) & 1u, fe = (eqm >> (r * 4 + j)) & 1u;
                 if (fg || (fe && ce < quota)) {
                     const uint32_t o = cg + (ce < quota ? ce : quota);
                     const uint32_t where = (SRC == SRC_CAND) ? pos[r][j] : e0 + j;
@@ -427,169 +771,140 @@ __global__ __launch_bounds__(kBlock) void k_emit(SelArgs a) {
                     v[where] = 0.0f;
                     if (u) u[where] = 0.0f;
                 }
+                cg += fg; ce += fe;
             }
-            cg += fg; ce += fe;
         }
     }
 }
 
-void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st) {
-    dim3 grid((a.n + kChunk - 1) / kChunk, batch);
-    if (fused) {
-        if (vec) hipLaunchKernelGGL((k_emit<SRC_FUSED, false, true>), grid, dim3(kBlock), 0, st, a);
-        else hipLaunchKernelGGL((k_emit<SRC_FUSED, false, false>), grid, dim3(kBlock), 0, st, a);
-    } else {
-        if (vec) hipLaunchKernelGGL((k_emit<SRC_PLAIN, false, true>), grid, dim3(kBlock), 0, st, a);
-        else hipLaunchKernelGGL((k_emit<SRC_PLAIN, false, false>), grid, dim3(kBlock), 0, st, a);
-    }
-}
-
-void launch_output_from_candidates(const SelArgs &a, int batch, hipStream_t st) {
-    dim3 grid((a.cap + kChunk - 1) / kChunk, batch);
-    hipLaunchKernelGGL((k_emit<SRC_CAND, true, true>), grid, dim3(kBlock), 0, st, a);
-}
-
-void launch_exact_output(const SelArgs &a, int batch, bool vec, hipStream_t st) {
-    dim3 grid((a.n + kChunk - 1) / kChunk, batch);
-    if (vec) hipLaunchKernelGGL((k_emit<SRC_PLAIN, true, true>), grid, dim3(kBlock), 0, st, a);
-    else hipLaunchKernelGGL((k_emit<SRC_PLAIN, true, false>), grid, dim3(kBlock), 0, st, a);
-}
-
-// ------------------------------------------------------------------ exact k-th key among the candidates
-
-// One block per node.  Needs count(candidates) >= k and the list complete; otherwise the node is
-// handed to the exact path (fast_ok stays 0).
-__global__ __launch_bounds__(1024) void k_select_candidates(SelArgs a) {
+// Long candidate lists: T* from the two histograms, then look-back compaction of the gathered list.
+__global__ __launch_bounds__(kBlock) void k_emit_candidates(SelArgs a) {
     __shared__ uint32_t hist[kFineBins];
-    __shared__ uint32_t wave_tmp[16], res[2];
-    const int node = blockIdx.x, tid = threadIdx.x;
+    __shared__ uint32_t wave_tmp[kWaves], res[2];
+    const int node = blockIdx.y;
     Sel *s = a.sel + node;
     const uint32_t total = s->cand_total;
-    if (s->wait_failed || total < a.k || total > a.cap) {
-        if (tid == 0) { s->fast_ok = 0; atomicAdd(&a.stats->fallback, 1u); }
+    uint32_t thr = 0, quota = 0;
+    // every block derives T* and the tie quota from the two histograms (same result in all)
+    const bool ok = find_threshold<false>(a, node, total, hist, wave_tmp, res, thr, quota);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        s->fast_ok = ok;
+        if (ok) { s->thr = thr; s->quota = quota; }
+        atomicAdd(ok ? &a.stats->fast : &a.stats->fallback, 1u);
+    }
+    if (!ok) return;
+    emit_chunks<SRC_CAND, true>(a, node, total, thr, quota);
+}
+
+// direct = true: short candidate lists (each block reads the whole list); false: long lists
+// (second-level histogram by many blocks, then look-back compaction).
+void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hipStream_t st) {
+    if (direct) {
+        hipLaunchKernelGGL(k_output_direct, dim3((a.cap + 4095) / 4096, batch), dim3(1024), 0, st, a);
         return;
     }
-    const uint32_t t_est = s->t_est;
-    const uint32_t *cval = a.cand_val + (size_t)node * a.cap;
-    for (int i = tid; i < kFineBins; i += 1024) hist[i] = a.fine_hist[node * kFineBins + i];
-    __syncthreads();
-    find_rank_bin<kFineBins>(hist, a.k, wave_tmp, res);
-    const uint32_t bin = res[0];
-    uint32_t need = a.k - res[1];
-    __syncthreads();
-
-    uint32_t thr;
-    if (bin < (uint32_t)kFineBins - 1) {
-        for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
-        __syncthreads();
-        for (uint32_t i = tid; i < total; i += 1024) {
-            const uint32_t d = (cval[i] & 0x7fffffffu) - t_est;
-            if ((d >> kFineShift) == bin) atomicAdd(&hist[d & ((1u << kFineShift) - 1)], 1u);
-        }
-        __syncthreads();
-        find_rank_bin<kFineBins>(hist, need, wave_tmp, res);
-        thr = t_est + (bin << kFineShift) + res[0];
-        need -= res[1];
-    } else {
-        // the k-th key lies beyond the histogram's range: radix select on (key - t_est) over the
-        // candidates of the last bin, digits [31:20], [19:8], [7:0]
-        const uint32_t lo = ((uint32_t)kFineBins - 1) << kFineShift;
-        uint32_t prefix = 0;
-        const int shifts[3] = {20, 8, 0};
-        const uint32_t masks[3] = {0xfffu, 0xfffu, 0xffu};
-        for (int p = 0; p < 3; ++p) {
-            for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
-            __syncthreads();
-            for (uint32_t i = tid; i < total; i += 1024) {
-                const uint32_t d = (cval[i] & 0x7fffffffu) - t_est;
-                const bool member = d >= lo && (p == 0 || (d >> (shifts[p - 1])) == prefix);
-                if (member) atomicAdd(&hist[(d >> shifts[p]) & masks[p]], 1u);
-            }
-            __syncthreads();
-            find_rank_bin<kFineBins>(hist, need, wave_tmp, res);
-            need -= res[1];
-            prefix = (p == 0) ? res[0] : ((prefix << (shifts[p - 1] - shifts[p])) | res[0]);
-            __syncthreads();
-        }
-        thr = t_est + prefix;
-    }
-    if (tid == 0) {
-        s->thr = thr;
-        s->quota = need;
-        s->fast_ok = 1;
-        atomicAdd(&a.stats->fast, 1u);
-    }
+    uint32_t blocks = (a.cap + 16383) / 16384;
+    if (blocks > 256) blocks = 256;
+    hipLaunchKernelGGL(k_select_level2, dim3(blocks, batch), dim3(1024), 0, st, a);
+    blocks = (a.cap + kChunk - 1) / kChunk;
+    if (blocks > 256) blocks = 256;
+    hipLaunchKernelGGL(k_emit_candidates, dim3(blocks, batch), dim3(kBlock), 0, st, a);
 }
 
-void launch_select_candidates(const SelArgs &a, int batch, hipStream_t st) {
-    hipLaunchKernelGGL(k_select_candidates, dim3(batch), dim3(1024), 0, st, a);
+// ------------------------------------------------------------------ exact path: one persistent kernel
+
+// Barrier over the blocks of one node.  All of them are resident (the host sizes the grid by
+// the kernel's occupancy), so the wait ends; it is bounded all the same.
+__device__ __forceinline__ void node_barrier(const SelArgs &a, Sel *s, uint32_t &epoch) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        epoch += gridDim.x;
+        atomicAdd(&s->barrier, 1u);
+        uint32_t spins = 0;
+        while (ld_agent32(&s->barrier) < epoch) {
+            if (++spins > a.spin_limit) { atomicAdd(&a.stats->errors, 1u); break; }
+            __builtin_amdgcn_s_sleep(8);
+        }
+        __threadfence();
+    }
+    __syncthreads();
 }
 
-// ------------------------------------------------------------------ exact path: radix select over v
-
-// pass 0: digit = key >> 20 ; pass 1: (key >> 10) & 1023 under prefix key >> 20 ;
-// pass 2: key & 1023 under prefix key >> 10.  The last block to finish a pass fixes the digit.
-template <int PASS, bool VEC>
-__global__ __launch_bounds__(kBlock) void k_radix_pass(SelArgs a) {
+// Radix select of the exact k-th largest key over all of v (digits of 11, 10 and 10 bits: each
+// pass histograms one digit of the keys that match the digits fixed so far, all blocks then
+// fix the next digit from the summed histogram), followed by the ordered output compaction
+// of v with that key.  Runs for the nodes the fast path handed back, or for all when forced.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
     __shared__ uint32_t hist[kRadixBins];
     __shared__ uint32_t wave_tmp[kWaves], res[2];
-    __shared__ uint32_t is_last;
     const int node = blockIdx.y, tid = threadIdx.x;
     Sel *s = a.sel + node;
     if (!a.force && s->fast_ok) return;
     const float *v = a.v + (size_t)node * a.stride;
-    uint32_t *gh = a.radix_hist + (node * 3 + PASS) * kRadixBins;
-    const uint32_t prefix = s->prefix;
-    const uint32_t rank = PASS == 0 ? a.k : s->need;
-    constexpr int NB = PASS == 0 ? kRadixBins : 1024;
-
-    for (int i = tid; i < NB; i += kBlock) hist[i] = 0;
-    __syncthreads();
-    auto count = [&](uint32_t key) {
-        if (PASS == 0) atomicAdd(&hist[key >> 20], 1u);
-        else if (PASS == 1) { if ((key >> 20) == prefix) atomicAdd(&hist[(key >> 10) & 1023u], 1u); }
-        else { if ((key >> 10) == prefix) atomicAdd(&hist[key & 1023u], 1u); }
-    };
     const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock;
-    if (VEC) {
-        const uint32_t n4 = a.n >> 2;
-        for (uint32_t i = gtid; i < n4; i += nthreads) {
-            f4 vv = ((const f4 *)v)[i];
-            count(key_of(vv.x)); count(key_of(vv.y)); count(key_of(vv.z)); count(key_of(vv.w));
+    uint32_t epoch = 0, prefix = 0, rank = a.k;
+
+    for (int pass = 0; pass < 3; ++pass) {
+        const int nb = pass == 0 ? kRadixBins : 1024;
+        uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
+        for (int i = tid; i < nb; i += kBlock) hist[i] = 0;
+        __syncthreads();
+        auto count = [&](uint32_t key) {
+            if (pass == 0) atomicAdd(&hist[key >> 20], 1u);
+            else if (pass == 1) { if ((key >> 20) == prefix) atomicAdd(&hist[(key >> 10) & 1023u], 1u); }
+            else { if ((key >> 10) == prefix) atomicAdd(&hist[key & 1023u], 1u); }
+        };
+        if (VEC) {
+            const uint32_t n4 = a.n >> 2;
+            for (uint32_t i = gtid; i < n4; i += nthreads) {
+                const f4 vv = ((const f4 *)v)[i];
+                count(key_of(vv.x)); count(key_of(vv.y)); count(key_of(vv.z)); count(key_of(vv.w));
+            }
+            for (uint32_t i = (n4 << 2) + gtid; i < a.n; i += nthreads) count(key_of(v[i]));
+        } else {
+            for (uint32_t i = gtid; i < a.n; i += nthreads) count(key_of(v[i]));
         }
-        for (uint32_t i = (n4 << 2) + gtid; i < a.n; i += nthreads) count(key_of(v[i]));
-    } else {
-        for (uint32_t i = gtid; i < a.n; i += nthreads) count(key_of(v[i]));
-    }
-    __syncthreads();
-    for (int i = tid; i < NB; i += kBlock) { uint32_t h = hist[i]; if (h) atomicAdd(&gh[i], h); }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) is_last = (atomicAdd(&s->done[1 + PASS], 1u) == gridDim.x - 1);
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-    for (int i = tid; i < NB; i += kBlock) hist[i] = ld_agent32(&gh[i]);
-    __syncthreads();
-    find_rank_bin<NB>(hist, rank, wave_tmp, res);
-    if (tid == 0) {
+        __syncthreads();
+        for (int i = tid; i < nb; i += kBlock) { const uint32_t h = hist[i]; if (h) atomicAdd(&gh[i], h); }
+        node_barrier(a, s, epoch);
+        for (int i = tid; i < kRadixBins; i += kBlock) hist[i] = i < nb ? ld_agent32(&gh[i]) : 0u;
+        __syncthreads();
+        if (pass == 0) find_rank_bin<kRadixBins>(hist, rank, wave_tmp, res);
+        else find_rank_bin<1024>(hist, rank, wave_tmp, res);
         const uint32_t digit = res[0] == 0xffffffffu ? 0u : res[0];
-        const uint32_t left = rank - res[1];
-        if (PASS == 0) { s->prefix = digit; s->need = left; }
-        else if (PASS == 1) { s->prefix = (prefix << 10) | digit; s->need = left; }
-        else { s->thr = (prefix << 10) | digit; s->quota = left; }
+        rank -= res[1];
+        prefix = pass == 0 ? digit : ((prefix << 10) | digit);
+        __syncthreads();
     }
+    // prefix is now the full key T*; rank the number of ties to take
+    if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }
+    emit_chunks<SRC_PLAIN, VEC>(a, node, a.n, prefix, rank);
 }
 
-void launch_radix_pass(const SelArgs &a, int batch, int pass, bool vec, hipStream_t st) {
-    uint32_t blocks = (a.n + kChunk - 1) / kChunk;
-    if (blocks > 2048) blocks = 2048;
-    dim3 grid(blocks, batch);
-#define LGC_RP(P)                                                                             \
-    if (vec) hipLaunchKernelGGL((k_radix_pass<P, true>), grid, dim3(kBlock), 0, st, a);       \
-    else hipLaunchKernelGGL((k_radix_pass<P, false>), grid, dim3(kBlock), 0, st, a)
-    if (pass == 0) { LGC_RP(0); } else if (pass == 1) { LGC_RP(1); } else { LGC_RP(2); }
-#undef LGC_RP
+static int exact_blocks_per_cu(bool vec) {
+    static int cached[2] = {0, 0};
+    if (!cached[vec]) {
+        int nb = 0;
+        hipError_t e = vec ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_exact<true>, kBlock, 0)
+                           : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_exact<false>, kBlock, 0);
+        cached[vec] = (e == hipSuccess && nb > 0) ? nb : 1;
+    }
+    return cached[vec];
+}
+
+// The grid holds only as many blocks as are resident at once on `cus` compute units, shared
+// evenly by the nodes (the barriers need every block of a node to be running).
+void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st) {
+    uint32_t per_node = (uint32_t)(exact_blocks_per_cu(vec) * cus / batch);
+    const uint32_t chunks = (a.n + kChunk - 1) / kChunk;
+    if (per_node > chunks) per_node = chunks;
+    if (per_node > 1024) per_node = 1024;
+    if (per_node < 1) per_node = 1;
+    dim3 grid(per_node, batch);
+    if (vec) hipLaunchKernelGGL(k_exact<true>, grid, dim3(kBlock), 0, st, a);
+    else hipLaunchKernelGGL(k_exact<false>, grid, dim3(kBlock), 0, st, a);
 }
 
 }  // namespace lgc
