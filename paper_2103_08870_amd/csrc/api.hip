@@ -26,8 +26,12 @@ struct lgc_ctx {
     uint32_t state_words = 0;
     int cur = 0;                      // set the next call will use (it is clean)
     int cus = 1;                      // compute units of the device
-    uint32_t region = 1024, regions = 0, status_cand_stride = 0, status_exact_stride = 0;
-    uint32_t *samples = nullptr, *reg_count = nullptr, *reg_idx = nullptr, *reg_val = nullptr;
+    uint32_t cand_blocks = 0;
+    int pingpong = 1;                 // alternate the direction of the candidate pass
+    unsigned calls = 0;
+    uint32_t rows = 0, status_cand_stride = 0, status_exact_stride = 0;
+    uint32_t *samples = nullptr, *row_count = nullptr;
+    unsigned long long *bitmap = nullptr;
     uint32_t *cand_idx = nullptr, *cand_val = nullptr;
     float *act[2] = {nullptr, nullptr};  // autoencoder activations (ping-pong), grown on demand
     size_t act_floats = 0;
@@ -156,7 +160,7 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     memset(&a, 0, sizeof a);
     a.g = g; a.u = u; a.v = v;
     a.stride = stride; a.n = (uint32_t)n; a.k = (uint32_t)k; a.momentum = m;
-    a.rank = 0; a.cap = c->cap; a.region = c->region; a.regions = c->regions;
+    a.rank = 0; a.cap = c->cap; a.rows = c->rows; a.cand_blocks = c->cand_blocks;
     a.status_cand_stride = c->status_cand_stride; a.status_exact_stride = c->status_exact_stride;
     a.spin_limit = 1u << 20;
     a.force = 0;
@@ -168,7 +172,7 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     a.status_cand = (unsigned long long *)(cur + L.status_cand);
     a.status_exact = (unsigned long long *)(cur + L.status_exact);
     a.next_state = c->state[c->cur ^ 1]; a.next_words = c->state_words;
-    a.samples = c->samples; a.reg_count = c->reg_count; a.reg_idx = c->reg_idx; a.reg_val = c->reg_val;
+    a.samples = c->samples; a.row_count = c->row_count; a.bitmap = c->bitmap;
     a.cand_idx = c->cand_idx; a.cand_val = c->cand_val;
     a.out_vals = out_vals; a.out_idx = out_idx;
     return a;
@@ -197,6 +201,7 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
     }
     ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
     if (fast) {
+        a.reverse = ctx->pingpong ? (ctx->calls++ & 1) : 0;
         launch_sample(a, batch, fused, vec, st);   // also clears the next call's state set
         profile_begin(ctx, st);
         launch_candidates(a, batch, fused, vec, st);
@@ -241,26 +246,14 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
     c->device = device; c->max_n = max_n; c->max_k = max_k; c->max_batch = max_batch;
     c->cap = candidate_capacity(max_n, max_k);
     {
-        // Elements per wavefront in the candidate pass: the grid should be a whole number of
-        // "rounds" of what the device holds at once (8 blocks of 4 wavefronts per compute
-        // unit), about four rounds, so that no tail of half-empty rounds is left.
         hipDeviceProp_t prop;
         hipError_t pe = hipGetDeviceProperties(&prop, device);
         if (pe != hipSuccess) { delete c; return fail(nullptr, LGC_EHIP, "hipGetDeviceProperties: %s", hipGetErrorString(pe)); }
         c->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
-        const double resident_waves = (double)c->cus * 8 * kWaves;
-        double rounds = 4.0;
-        if (const char *e = getenv("LGC_ROUNDS")) { const double r = atof(e); if (r >= 1.0 && r <= 64.0) rounds = r; }
-        double r = ceil((double)max_n * max_batch / (resident_waves * rounds) / 64.0) * 64.0;
-        if (r < 1024.0) r = 1024.0;
-        if (r > 65536.0) r = 65536.0;
-        c->region = (uint32_t)r;
-        if (const char *e = getenv("LGC_REGION")) {  // tuning knob: fixed region size, multiple of 64
-            const long v = atol(e);
-            if (v >= 256 && v <= 65536 && v % 64 == 0) c->region = (uint32_t)v;
-        }
     }
-    c->regions = (uint32_t)((max_n + c->region - 1) / c->region);
+    if (const char *e = getenv("LGC_CAND_BLOCKS")) c->cand_blocks = (uint32_t)atol(e);  // tuning knob
+    if (const char *e = getenv("LGC_PINGPONG")) c->pingpong = atoi(e) != 0;             // tuning knob
+    c->rows = (uint32_t)align_up((max_n + kRow - 1) / kRow, 4);
     c->status_exact_stride = (uint32_t)((max_n + kChunk - 1) / kChunk);
     c->status_cand_stride = (c->cap + kChunk - 1) / kChunk;
     const StateLayout L = state_layout(max_batch, c->status_cand_stride, c->status_exact_stride);
@@ -274,9 +267,8 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
     const size_t o_state0 = carve(L.words * 4);
     const size_t o_state1 = carve(L.words * 4);
     const size_t o_samples = carve(B * kSample * 4);
-    const size_t o_rcount = carve(B * c->regions * 4);
-    const size_t o_ridx = carve(B * (size_t)c->regions * (c->region / kRegionDiv) * 4);
-    const size_t o_rval = carve(B * (size_t)c->regions * (c->region / kRegionDiv) * 4);
+    const size_t o_rcount = carve(B * c->rows * 4);
+    const size_t o_bitmap = carve(B * (size_t)c->rows * kRowWords * 8);
     const size_t o_cidx = carve(B * (size_t)c->cap * 4);
     const size_t o_cval = carve(B * (size_t)c->cap * 4);
     hipError_t e = hipMalloc(&c->scratch, off);
@@ -297,9 +289,8 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
     c->state[0] = (uint32_t *)(base + o_state0);
     c->state[1] = (uint32_t *)(base + o_state1);
     c->samples = (uint32_t *)(base + o_samples);
-    c->reg_count = (uint32_t *)(base + o_rcount);
-    c->reg_idx = (uint32_t *)(base + o_ridx);
-    c->reg_val = (uint32_t *)(base + o_rval);
+    c->row_count = (uint32_t *)(base + o_rcount);
+    c->bitmap = (unsigned long long *)(base + o_bitmap);
     c->cand_idx = (uint32_t *)(base + o_cidx);
     c->cand_val = (uint32_t *)(base + o_cval);
     *out = c;

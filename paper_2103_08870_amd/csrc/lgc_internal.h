@@ -27,9 +27,11 @@ constexpr int kFineShift = 12;
 // ---- exact radix select over the full vector (3 passes: 11 + 10 + 10 bits) --
 constexpr int kRadixBins = 2048;
 
-// ---- candidate regions: every wavefront of the candidate pass owns `region` consecutive
-// elements (a multiple of 1024) and appends its candidates, in index order, to its own slots
-constexpr int kRegionDiv = 4;                   // slots per region = region size / 4
+// ---- candidate bitmap: the candidate pass works in rows of 1024 consecutive elements, one
+// wavefront per row; a row's candidate flags are 16 words of 64 bits (one full 128-byte line):
+// word 4s+j, bit l  <->  element  row*1024 + 256 s + 4 l + j   (s, j in 0..3, l = lane)
+constexpr int kRow = 1024;
+constexpr int kRowWords = 16;
 
 // Per-node selection state, device memory.  It lives in a "state set" together with the
 // histograms and look-back status words; there are two sets, used by alternate calls, and each
@@ -40,7 +42,7 @@ struct Sel {
     uint32_t thr;         // exact k-th largest key T*
     uint32_t quota;       // how many elements with key == T* are taken (lowest indices first)
     uint32_t fast_ok;     // 1: the fast path produced this node's output
-    uint32_t fast_failed; // a region overflowed or a bounded wait expired: use the exact path
+    uint32_t fast_failed; // reserved
     uint32_t barrier;     // exact path: arrivals at the node's barrier
     uint32_t ticket[1];   // chunk tickets of the compaction over the candidates
     uint32_t pad[8];
@@ -62,11 +64,12 @@ struct SelArgs {
     float momentum;
     uint32_t rank;    // rank of the sample's order statistic used as estimate
     uint32_t cap;     // capacity of the gathered candidate list, per node
-    uint32_t region;  // elements per candidate region
-    uint32_t regions; // candidate regions per node (stride of reg_count / reg_idx / reg_val)
+    uint32_t rows;    // bitmap rows per node (stride of row_count; bitmap stride is rows * kRowWords)
+    uint32_t cand_blocks;  // blocks per node of the candidate pass (0 = one wavefront per row)
     uint32_t status_cand_stride, status_exact_stride;  // status words per node
     uint32_t spin_limit;      // bound of the look-back wait
     int force;                // exact path chosen by the host (ignore fast_ok)
+    int reverse;              // candidate pass walks the data backwards (alternate calls)
     Stats *stats;
     // current state set
     Sel *sel;
@@ -81,9 +84,8 @@ struct SelArgs {
     uint32_t next_words;
     // bulk scratch
     uint32_t *samples;        // [batch][kSample]
-    uint32_t *reg_count;      // [batch][regions]
-    uint32_t *reg_idx;        // [batch][regions][kRegionCap]
-    uint32_t *reg_val;
+    uint32_t *row_count;      // [batch][rows]  candidates per row
+    unsigned long long *bitmap;  // [batch][rows][kRowWords]
     uint32_t *cand_idx;       // [batch][cap]  gathered, index-ordered
     uint32_t *cand_val;
     float *out_vals;          // [batch][k]

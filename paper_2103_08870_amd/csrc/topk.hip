@@ -14,9 +14,9 @@
 //    not (or if the candidate buffer would overflow) the device itself falls back to
 //  * exact path: a 3-pass (11+10+10 bit) radix select over all of v, then an ordered
 //    compaction of v with the exact threshold.
-//  In the candidate pass every wavefront owns 4096 consecutive elements and a private slot
-//  region, so the streaming kernel has no communication between wavefronts at all; a small
-//  gather kernel concatenates the regions (they are already in index order).
+//  The candidate pass writes one flag bit per element (a dense bitmap, full cache lines) and a
+//  count per row of 1024, so the streaming kernel has no communication between wavefronts at
+//  all and no scattered stores; a small gather kernel lists the flagged elements in index order.
 //  The two output compactions (over the candidates; over v in the exact path) use one look-back
 //  chain over 4096-element chunks; chunk ids are handed out by an atomic ticket, so a chunk
 //  only ever waits for chunks that already run.
@@ -154,8 +154,7 @@ __device__ __forceinline__ uint32_t mix32(uint32_t h) {
     return h;
 }
 
-// One group of four neighbouring elements per thread, at a jittered position inside the thread's
-// own stratum of the vector.  The keys that the accumulation WILL produce are sampled (the fused
+// Four neighbouring elements per thread.  The keys that the accumulation WILL produce are sampled (the fused
 // source recomputes v + (m*u + g) without storing it); their first-level histogram (key >> 20)
 // is accumulated per block in LDS and flushed with a few atomics.
 // The kernel also clears the state set that the next call will use.
@@ -168,9 +167,12 @@ __global__ __launch_bounds__(1024) void k_sample(SelArgs a) {
         for (uint32_t i = gt; i < a.next_words; i += nt) a.next_state[i] = 0;
     }
     const size_t off = (size_t)node * a.stride;
+    // four neighbouring threads read one 64-byte cluster of 16 elements; the clusters sit at
+    // jittered positions, one in each of kSampleGroups/4 equal strata of the vector
     const uint32_t j = blockIdx.x * 1024u + tid;  // < kSampleGroups
-    const uint32_t stratum = (a.n >> 2) / kSampleGroups;
-    const uint32_t e = (j * stratum + mix32(j + 0x5bd1e995u * (uint32_t)node) % stratum) << 2;
+    const uint32_t cl = j >> 2;
+    const uint32_t stratum = (a.n >> 4) / (kSampleGroups / 4);
+    const uint32_t e = ((cl * stratum + mix32(cl + 0x5bd1e995u * (uint32_t)node) % stratum) << 4) + ((j & 3u) << 2);
     uint32_t *smp = a.samples + (size_t)node * kSample;
     uint32_t *sh = a.sample_hist + node * kSampleBins;
     for (int i = tid; i < kSampleBins; i += 1024) hist[i] = 0;
@@ -242,92 +244,113 @@ void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_
 
 // ------------------------------------------------------------------ candidate pass (the streaming kernel)
 
+// One full row of a wavefront: 4 x 256 consecutive elements, lane l holds elements 4l..4l+3 of
+// each 256.  All twelve 16-byte loads are issued before anything depends on them.
+template <bool FUSED>
+__device__ __forceinline__ void full_row(const float *__restrict__ g, float *__restrict__ u, float *__restrict__ v,
+                                         const float m, uint32_t (&bits)[4][4]) {
+    f4 gg[4], uu[4], vv[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        if (FUSED) {
+            gg[s] = __builtin_nontemporal_load((const f4 *)(g + s * 256));
+            uu[s] = *(const f4 *)(u + s * 256);
+        }
+        vv[s] = *(const f4 *)(v + s * 256);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        if (FUSED) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { float x = uu[s][j], y = vv[s][j]; accum1(gg[s][j], x, y, m); uu[s][j] = x; vv[s][j] = y; }
+            *(f4 *)(u + s * 256) = uu[s];
+            *(f4 *)(v + s * 256) = vv[s];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bits[s][j] = __float_as_uint(vv[s][j]);
+    }
+}
+
 // FUSED: reads g,u,v, writes u,v (the accumulation) and classifies the new v; otherwise reads v.
-// Each wavefront owns a.region consecutive elements (a multiple of 64) and appends every
-// element with key >= t_est to its private slots, in index order.
-// No barrier, no LDS, no atomics, no communication between wavefronts.
+// One wavefront per row of 1024 elements.  The flags "key >= t_est" of the row go out as one
+// full 128-byte line of the candidate bitmap (dense, coalesced: no partial-line writes), the
+// row's candidate count as one word.  No barrier, no LDS, no atomics, nothing shared.
 template <bool FUSED, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
-    const int node = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t region = blockIdx.x * kWaves + wave;
-    const uint32_t begin = region * a.region;
-    if (begin >= a.n) return;
-    const uint32_t end = (a.n - begin > a.region) ? begin + a.region : a.n;
+    // a.reverse: walk nodes and rows backwards, so that a call starts on the data the previous
+    // (forward) call touched last, which the memory-side cache may still hold
+    const int node = a.reverse ? (int)gridDim.y - 1 - (int)blockIdx.y : (int)blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t off = (size_t)node * a.stride;
-    const float *g = a.g + off;
-    float *u = a.u + off;
-    float *v = a.v + off;
+    const float *__restrict__ g = a.g + off;
+    float *__restrict__ u = a.u + off;
+    float *__restrict__ v = a.v + off;
     const uint32_t t_est = a.sel[node].t_est;
-    const uint32_t rcap = a.region / kRegionDiv;
-    const size_t rbase = ((size_t)node * a.regions + region) * rcap;
-    uint32_t *ridx = a.reg_idx + rbase, *rval = a.reg_val + rbase;
     const float m = a.momentum;
-    uint32_t count = 0;
-
-    for (uint32_t row = begin; row < end; row += 1024) {
+    const uint32_t nrows = (a.n + kRow - 1) / kRow;
+    unsigned long long *bitmap = a.bitmap + (size_t)node * a.rows * kRowWords;
+    uint32_t *row_count = a.row_count + (size_t)node * a.rows;
+    for (uint32_t r0 = blockIdx.x * kWaves + wave; r0 < nrows; r0 += gridDim.x * kWaves) {
+        const uint32_t r = a.reverse ? nrows - 1 - r0 : r0;
+        const uint32_t row = r * (uint32_t)kRow;
+        const uint32_t end = (a.n - row > (uint32_t)kRow) ? row + kRow : a.n;
         uint32_t bits[4][4];
+        if (VEC && row + 1024 <= end) {
+            full_row<FUSED>(g + row + lane * 4, u + row + lane * 4, v + row + lane * 4, m, bits);
+        } else {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const uint32_t e0 = row + s * 256 + lane * 4;
-            f4 vv = {0.f, 0.f, 0.f, 0.f};
-            if (VEC && e0 + 3 < end) {
-                if (FUSED) {
-                    f4 gg = __builtin_nontemporal_load((const f4 *)(g + e0));
-                    f4 uu = *(const f4 *)(u + e0);
+            for (int s = 0; s < 4; ++s) {
+                const uint32_t e0 = row + s * 256 + lane * 4;
+                f4 vv = {0.f, 0.f, 0.f, 0.f};
+                if (VEC && e0 + 3 < end) {
                     vv = *(const f4 *)(v + e0);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) { float x = uu[j], y = vv[j]; accum1(gg[j], x, y, m); uu[j] = x; vv[j] = y; }
-                    *(f4 *)(u + e0) = uu;
-                    *(f4 *)(v + e0) = vv;
-                } else {
-                    vv = *(const f4 *)(v + e0);
-                }
-            } else {
-                for (int j = 0; j < 4; ++j) if (e0 + j < end) {
-                    float y = v[e0 + j];
                     if (FUSED) {
-                        float x = u[e0 + j];
-                        accum1(g[e0 + j], x, y, m);
-                        u[e0 + j] = x; v[e0 + j] = y;
-                    }
-                    vv[j] = y;
-                }
-            }
+                        const f4 gg = *(const f4 *)(g + e0);
+                        f4 uu = *(const f4 *)(u + e0);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bits[s][j] = __float_as_uint(vv[j]);
+                        for (int j = 0; j < 4; ++j) { float x = uu[j], y = vv[j]; accum1(gg[j], x, y, m); uu[j] = x; vv[j] = y; }
+                        *(f4 *)(u + e0) = uu;
+                        *(f4 *)(v + e0) = vv;
+                    }
+                } else {
+                    for (int j = 0; j < 4; ++j) if (e0 + j < end) {
+                        float y = v[e0 + j];
+                        if (FUSED) {
+                            float x = u[e0 + j];
+                            accum1(g[e0 + j], x, y, m);
+                            u[e0 + j] = x; v[e0 + j] = y;
+                        }
+                        vv[j] = y;
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bits[s][j] = __float_as_uint(vv[j]);
+            }
         }
+        // 16 flag words of the row; lane i < 16 ends up holding word i
+        uint32_t lo = 0, hi = 0, count = 0;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const uint32_t e0 = row + s * 256 + lane * 4;
-            bool f[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) f[j] = (e0 + j < end) && (bits[s][j] & 0x7fffffffu) >= t_est;
-            if (__ballot(f[0] | f[1] | f[2] | f[3]) != 0ull) {  // wave-uniform
-                uint32_t below = 0, tot = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const unsigned long long mk = __ballot(f[j]);
-                    below += lanes_below(mk);
-                    tot += (uint32_t)__popcll(mk);
-                }
-                uint32_t p = count + below;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (f[j]) {
-                        if (p < rcap) { ridx[p] = e0 + j; rval[p] = bits[s][j]; }
-                        ++p;
-                    }
-                }
-                count += tot;
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t e = row + s * 256 + lane * 4 + j;
+                const unsigned long long mk = __ballot(e < end && (bits[s][j] & 0x7fffffffu) >= t_est);
+                count += (uint32_t)__popcll(mk);
+                const bool mine = lane == s * 4 + j;
+                lo = mine ? (uint32_t)mk : lo;
+                hi = mine ? (uint32_t)(mk >> 32) : hi;
             }
         }
+        if (lane < kRowWords) bitmap[(size_t)r * kRowWords + lane] = ((unsigned long long)hi << 32) | lo;
+        if (lane == 0) row_count[r] = count;
     }
-    if (lane == 0) a.reg_count[(size_t)node * a.regions + region] = count;
 }
 
 void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st) {
-    const uint32_t nreg = (a.n + a.region - 1) / a.region;
-    dim3 grid((nreg + kWaves - 1) / kWaves, batch);
+    const uint32_t nrows = (a.n + kRow - 1) / kRow;
+    uint32_t blocks = (nrows + kWaves - 1) / kWaves;
+    if (a.cand_blocks && blocks > a.cand_blocks) blocks = a.cand_blocks;
+    dim3 grid(blocks, batch);
     if (fused) {
         if (vec) hipLaunchKernelGGL((k_candidates<true, true>), grid, dim3(kBlock), 0, st, a);
         else hipLaunchKernelGGL((k_candidates<true, false>), grid, dim3(kBlock), 0, st, a);
@@ -337,7 +360,7 @@ void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStr
     }
 }
 
-// ------------------------------------------------------------------ gather the regions
+// ------------------------------------------------------------------ gather the candidates
 
 __device__ __forceinline__ uint32_t block_sum_1024(uint32_t x, uint32_t *tmp /*[16]*/) {
     x = wave_sum(x);
@@ -350,42 +373,54 @@ __device__ __forceinline__ uint32_t block_sum_1024(uint32_t x, uint32_t *tmp /*[
     return t;
 }
 
-// kGatherRegions regions per block of 1024 threads.  Copies each region's candidates behind those
-// of all earlier regions of the node (the regions are in index order already, so the gathered
-// list is too), counts them in the fine histogram of d = key - t_est (bins of 2^12, last bin
-// open-ended) and adds the block's count to the node's total.  The copy is balanced over the
-// block's threads by output position (binary search of the owning region), whatever the
-// spread of the counts.
-constexpr int kGatherRegions = 256;
+// kGatherRows bitmap rows per block of 1024 threads.  Lists the candidates of its rows, in index
+// order, behind those of all earlier rows of the node: position, and value re-read from v.
+// Counts them in the fine histogram of d = key - t_est (bins of 2^12, last bin open-ended) and
+// adds the block's count to the node's total.  The block's part of the bitmap is staged in LDS;
+// the work is balanced over the threads by output position (binary search of the owning row,
+// then of the bit inside the row), whatever the spread of the candidates.
+constexpr int kGatherRows = 256;
 
 __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
     __shared__ uint32_t hist[kFineBins];
-    __shared__ uint32_t offs[kGatherRegions];
+    __shared__ unsigned long long rows_lds[kGatherRows * kRowWords];
+    __shared__ uint32_t offs[kGatherRows];
     __shared__ uint32_t tmp[16];
     const int node = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Sel *s = a.sel + node;
-    const uint32_t nreg = (a.n + a.region - 1) / a.region;
-    const uint32_t first = blockIdx.x * (uint32_t)kGatherRegions;
-    const uint32_t rcap = a.region / kRegionDiv;
-    const uint32_t *cnt = a.reg_count + (size_t)node * a.regions;
-    const uint32_t *ridx = a.reg_idx + ((size_t)node * a.regions + first) * rcap;
-    const uint32_t *rval = a.reg_val + ((size_t)node * a.regions + first) * rcap;
+    const uint32_t nrows = (a.n + kRow - 1) / kRow;
+    const uint32_t first = blockIdx.x * (uint32_t)kGatherRows;
+    const uint32_t mine = nrows - first < (uint32_t)kGatherRows ? nrows - first : (uint32_t)kGatherRows;
+    const uint32_t *cnt = a.row_count + (size_t)node * a.rows;
+    const unsigned long long *bitmap = a.bitmap + ((size_t)node * a.rows + first) * kRowWords;
+    const float *v = a.v + (size_t)node * a.stride;
     uint32_t *cidx = a.cand_idx + (size_t)node * a.cap, *cval = a.cand_val + (size_t)node * a.cap;
 
-    const uint32_t region = first + tid;
-    uint32_t c = (tid < kGatherRegions && region < nreg) ? cnt[region] : 0u;
+    // all independent loads first: my row's count, my slice of the bitmap, the counts before the block
+    const uint32_t c = (uint32_t)tid < mine ? cnt[first + tid] : 0u;
+    ulonglong2 bm[kGatherRows * kRowWords / 2 / 1024];
+#pragma unroll
+    for (int q = 0; q < (int)(kGatherRows * kRowWords / 2 / 1024); ++q) {
+        const uint32_t w2 = q * 1024 + tid;   // pair of words
+        bm[q] = (w2 * 2 < mine * kRowWords) ? *(const ulonglong2 *)(bitmap + (size_t)w2 * 2) : ulonglong2{0ull, 0ull};
+    }
     const uint32_t t_est = s->t_est;
     uint32_t part = 0;
-    for (uint32_t i0 = tid; i0 < first; i0 += 4096) {
-        uint32_t x[4];
+    for (uint32_t i0 = tid * 4; i0 < first; i0 += 4096 * 4) {   // first and the row stride are multiples of 4
+        u4 x[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) x[r] = (i0 + r * 1024 < first) ? cnt[i0 + r * 1024] : 0u;
-        part += x[0] + x[1] + x[2] + x[3];
+        for (int r = 0; r < 4; ++r) x[r] = (i0 + r * 4096 < first) ? *(const u4 *)(cnt + i0 + r * 4096) : (u4){0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part += x[r][0] + x[r][1] + x[r][2] + x[r][3];
+    }
+#pragma unroll
+    for (int q = 0; q < (int)(kGatherRows * kRowWords / 2 / 1024); ++q) {
+        rows_lds[(q * 1024 + tid) * 2] = bm[q].x;
+        rows_lds[(q * 1024 + tid) * 2 + 1] = bm[q].y;
     }
     for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
-    const uint32_t before = block_sum_1024(part, tmp);   // contains barriers: hist is zeroed for all
-    if (c > rcap) { s->fast_failed = 1; c = rcap; }      // lost candidates: the node goes to the exact path
-    // exclusive scan of c over the first kGatherRegions threads
+    const uint32_t before = block_sum_1024(part, tmp);   // contains barriers: LDS is filled for all
+    // exclusive scan of c over the first kGatherRows threads
     uint32_t incl = c;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -397,19 +432,47 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
     __syncthreads();
     uint32_t excl = incl - c, block_total = 0;
 #pragma unroll
-    for (int w = 0; w < kGatherRegions / 64; ++w) { if (w < wave) excl += tmp[w]; block_total += tmp[w]; }
-    if (tid < kGatherRegions) offs[tid] = excl;
+    for (int w = 0; w < kGatherRows / 64; ++w) { if (w < wave) excl += tmp[w]; block_total += tmp[w]; }
+    if (tid < kGatherRows) offs[tid] = excl;
     if (tid == 0 && block_total) atomicAdd(&s->cand_total, block_total);
     __syncthreads();
 
     for (uint32_t p = tid; p < block_total; p += 1024) {
-        // last region r with offs[r] <= p: it is the one that holds output position p
+        // last row r with offs[r] <= p: it is the one that holds output position p
         uint32_t r = 0;
 #pragma unroll
-        for (int step = kGatherRegions / 2; step >= 1; step >>= 1)
+        for (int step = kGatherRows / 2; step >= 1; step >>= 1)
             if (offs[r + step] <= p) r += step;
-        const uint32_t i = p - offs[r];
-        const uint32_t ix = ridx[(size_t)r * rcap + i], vb = rval[(size_t)r * rcap + i];
+        uint32_t i = p - offs[r];   // the i-th candidate of row r, in element order (s, lane, j)
+        const unsigned long long *w = rows_lds + r * kRowWords;
+        unsigned long long w0 = 0, w1 = 0, w2 = 0, w3 = 0;
+        uint32_t sub = 0;
+        bool found = false;
+#pragma unroll
+        for (int sr = 0; sr < 4; ++sr) {
+            const unsigned long long x0 = w[4 * sr], x1 = w[4 * sr + 1], x2 = w[4 * sr + 2], x3 = w[4 * sr + 3];
+            const uint32_t cs = (uint32_t)(__popcll(x0) + __popcll(x1) + __popcll(x2) + __popcll(x3));
+            if (!found) {
+                if (i < cs) { found = true; sub = sr; w0 = x0; w1 = x1; w2 = x2; w3 = x3; }
+                else i -= cs;
+            }
+        }
+        // largest l such that the lanes below l hold at most i flags: lane l holds candidate i
+        uint32_t l = 0;
+#pragma unroll
+        for (int step = 32; step >= 1; step >>= 1) {
+            const unsigned long long below = (1ull << (l + step)) - 1ull;   // lanes 0 .. l+step-1
+            const uint32_t cb = (uint32_t)(__popcll(w0 & below) + __popcll(w1 & below) + __popcll(w2 & below) + __popcll(w3 & below));
+            if (cb <= i) l += step;
+        }
+        const unsigned long long below = (1ull << l) - 1ull;
+        uint32_t rem = i - (uint32_t)(__popcll(w0 & below) + __popcll(w1 & below) + __popcll(w2 & below) + __popcll(w3 & below));
+        const uint32_t b0 = (uint32_t)(w0 >> l) & 1u, b1 = (uint32_t)(w1 >> l) & 1u, b2 = (uint32_t)(w2 >> l) & 1u;
+        uint32_t j;
+        if (b0 && rem == 0) j = 0;
+        else { rem -= b0; if (b1 && rem == 0) j = 1; else { rem -= b1; j = (b2 && rem == 0) ? 2 : 3; } }
+        const uint32_t ix = (first + r) * (uint32_t)kRow + sub * 256 + l * 4 + j;
+        const uint32_t vb = ix < a.n ? __float_as_uint(v[ix]) : 0u;
         const uint32_t q = before + p;
         if (q < a.cap) { cidx[q] = ix; cval[q] = vb; }
         const uint32_t d = ((vb & 0x7fffffffu) - t_est) >> kFineShift;
@@ -421,8 +484,8 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
 }
 
 void launch_gather(const SelArgs &a, int batch, hipStream_t st) {
-    const uint32_t nreg = (a.n + a.region - 1) / a.region;
-    hipLaunchKernelGGL(k_gather, dim3((nreg + kGatherRegions - 1) / kGatherRegions, batch), dim3(1024), 0, st, a);
+    const uint32_t nrows = (a.n + kRow - 1) / kRow;
+    hipLaunchKernelGGL(k_gather, dim3((nrows + kGatherRows - 1) / kGatherRows, batch), dim3(1024), 0, st, a);
 }
 
 // Adds, for every candidate i < total that passes `member`, one count to hist[digit(d)], where
@@ -523,10 +586,12 @@ __global__ __launch_bounds__(1024) void k_select_level2(SelArgs a) {
     for (int i = tid; i < kFineBins; i += 1024) { const uint32_t h = hist[i]; if (h) atomicAdd(&l2[i], h); }
 }
 
-// Output for short candidate lists: block b (1024 threads) owns candidates [4096 b, 4096 b + 4096),
-// finds T* itself and counts the selected candidates before its own by reading them: no
-// communication between blocks.  Writes the selected elements in index order and zeroes them
-// in v (and u).
+// Output for short candidate lists: block b (1024 threads) owns candidates [4096 b, 4096 b + 4096).
+// Every block reads ALL candidate keys once (the first 64 K stay in registers), finds T* from
+// them itself and counts the selected candidates before its own: no communication between
+// blocks.  Writes the selected elements in index order and zeroes them in v (and u).
+constexpr int kKeep = 16;   // 16-byte key groups per thread held in registers
+
 __global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
     __shared__ uint32_t hist[kFineBins];
     __shared__ uint32_t wave_tmp[16], res[2], sh_pg[16], sh_pe[16], sh_tg[16], sh_te[16];
@@ -536,14 +601,51 @@ __global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
     const uint32_t *cidx = a.cand_idx + (size_t)node * a.cap;
     const uint32_t *cval = a.cand_val + (size_t)node * a.cap;
     const uint32_t base = blockIdx.x * 4096u, e0 = base + tid * 4;
-    // my four candidates, loaded before the search for T* so that the latencies overlap
-    u4 ci = {0, 0, 0, 0}, cv = {0, 0, 0, 0};
-    if (total <= a.cap) {
-        if (e0 + 3 < total) { ci = *(const u4 *)(cidx + e0); cv = *(const u4 *)(cval + e0); }
-        else { for (int j = 0; j < 4; ++j) if (e0 + j < total) { ci[j] = cidx[e0 + j]; cv[j] = cval[e0 + j]; } }
+    bool ok = !s->fast_failed && total >= a.k && total <= a.cap;
+    const uint32_t n4 = ok ? (total + 3) / 4 : 0u;   // 16-byte groups (the list's capacity is a multiple of 4)
+
+    // independent loads first: the keys, my four positions, the fine histogram
+    u4 keys[kKeep];
+#pragma unroll
+    for (int r = 0; r < kKeep; ++r) {
+        const uint32_t g4 = r * 1024 + tid;
+        keys[r] = g4 < n4 ? *(const u4 *)(cval + (size_t)g4 * 4) : (u4){0u, 0u, 0u, 0u};
     }
+    u4 ci = {0, 0, 0, 0};
+    if (ok && e0 < total) ci = *(const u4 *)(cidx + e0);
+    for (int i = tid; i < kFineBins; i += 1024) hist[i] = a.fine_hist[node * kFineBins + i];
+    const uint32_t t_est = s->t_est;
+    __syncthreads();
+
     uint32_t thr = 0, quota = 0;
-    const bool ok = find_threshold<true>(a, node, total, hist, wave_tmp, res, thr, quota);
+    if (ok) {   // uniform
+        find_rank_bin<kFineBins>(hist, a.k, wave_tmp, res);
+        const uint32_t bin = res[0], need = a.k - res[1];
+        __syncthreads();
+        ok = bin < (uint32_t)kFineBins - 1;   // T* beyond the histogram's range: leave it to the exact path
+        if (ok) {
+            for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
+            __syncthreads();
+            auto tally = [&](uint32_t key, uint32_t pos) {
+                const uint32_t d = (key & 0x7fffffffu) - t_est;
+                if (pos < total && (d >> kFineShift) == bin) atomicAdd(&hist[d & ((1u << kFineShift) - 1)], 1u);
+            };
+#pragma unroll
+            for (int r = 0; r < kKeep; ++r) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) tally(keys[r][c], (r * 1024 + tid) * 4 + c);
+            }
+            for (uint32_t g4 = kKeep * 1024 + tid; g4 < n4; g4 += 1024) {
+                const u4 x = *(const u4 *)(cval + (size_t)g4 * 4);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) tally(x[c], g4 * 4 + c);
+            }
+            __syncthreads();
+            find_rank_bin<kFineBins>(hist, need, wave_tmp, res);
+            thr = t_est + (bin << kFineShift) + res[0];
+            quota = need - res[1];
+        }
+    }
     if (blockIdx.x == 0 && tid == 0) {
         s->fast_ok = ok;
         if (ok) { s->thr = thr; s->quota = quota; }
@@ -551,19 +653,25 @@ __global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
     }
     if (!ok || base >= total) return;
 
-    // selected-or-tied counts among the candidates before mine (they are L2-warm by now)
+    // selected-or-tied counts among the candidates before mine: groups r*1024 + tid, r < blockIdx.x
     uint32_t pg = 0, pe = 0;
-    for (uint32_t i0 = tid; i0 < base / 4; i0 += 4096) {
-        u4 x[4];
+    u4 cv = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            x[r] = (i0 + r * 1024 < base / 4) ? *(const u4 *)(cval + (size_t)(i0 + r * 1024) * 4) : (u4){0u, 0u, 0u, 0u};
+    for (int r = 0; r < kKeep; ++r) {
+        if (r < (int)blockIdx.x) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            if (i0 + r * 1024 < base / 4) {
+            for (int c = 0; c < 4; ++c) { const uint32_t key = keys[r][c] & 0x7fffffffu; pg += key > thr; pe += key == thr; }
+        } else if (r == (int)blockIdx.x) {
+            cv = keys[r];
+        }
+    }
+    for (uint32_t r = kKeep; r <= blockIdx.x; ++r) {
+        const u4 x = *(const u4 *)(cval + (size_t)(r * 1024 + tid) * 4);
+        if (r < blockIdx.x) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) { const uint32_t key = x[r][c] & 0x7fffffffu; pg += key > thr; pe += key == thr; }
-            }
+            for (int c = 0; c < 4; ++c) { const uint32_t key = x[c] & 0x7fffffffu; pg += key > thr; pe += key == thr; }
+        } else {
+            cv = x;
         }
     }
     pg = wave_sum(pg); pe = wave_sum(pe);
