@@ -738,7 +738,7 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
                                             const uint32_t thr, const uint32_t quota) {
     __shared__ uint32_t sh_chunk;
     __shared__ uint32_t sh_gt[kRows][kWaves], sh_eq[kRows][kWaves];
-    __shared__ uint32_t sh_prefix[2];
+    __shared__ uint32_t sh_prefix[3];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Sel *s = a.sel + node;
@@ -822,13 +822,13 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
         // look-back over the preceding chunks (first wavefront only)
         if (wave == 0) {
             uint32_t pg = 0, pe = 0;
+            bool failed = false;
             if (chunk == 0) {
                 if (lane == 0) st_agent(&st[0], pack_status(2, blk_gt, blk_eq));
             } else {
                 if (lane == 0) st_agent(&st[chunk], pack_status(1, blk_gt, blk_eq));
                 int first = (int)chunk - 1;
                 uint32_t spins = 0;
-                bool failed = false;
                 while (first >= 0) {
                     const int jn = first - lane;
                     const bool valid = jn >= 0;
@@ -837,7 +837,11 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
                         if (valid) w = ld_agent(&st[jn]);
                         const bool ready = !valid || (w >> 62) != 0;
                         if (__all(ready)) break;
-                        if (++spins > a.spin_limit) { failed = true; break; }
+                        // bounded wait; a failure anywhere (counted in stats) ends all waits at once
+                        if (++spins > a.spin_limit || ((spins & 255u) == 0 && ld_agent32(&a.stats->errors) != 0)) {
+                            failed = true;
+                            break;
+                        }
                         __builtin_amdgcn_s_sleep(2);
                     }
                     if (failed) break;
@@ -852,9 +856,10 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
                 if (failed && lane == 0) atomicAdd(&a.stats->errors, 1u);
                 if (lane == 0) st_agent(&st[chunk], pack_status(2, pg + blk_gt, pe + blk_eq));
             }
-            if (lane == 0) { sh_prefix[0] = pg; sh_prefix[1] = pe; }
+            if (lane == 0) { sh_prefix[0] = pg; sh_prefix[1] = pe; sh_prefix[2] = failed; }
         }
         __syncthreads();
+        if (sh_prefix[2]) break;   // the output is invalid anyway: stop, the error is reported by lgc_stats
         const uint32_t pre_gt = sh_prefix[0], pre_eq = sh_prefix[1];
 
         if (tid == 0 && chunk == nchunks - 1) {
@@ -922,21 +927,26 @@ void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hip
 // ------------------------------------------------------------------ exact path: one persistent kernel
 
 // Barrier over the blocks of one node.  All of them are resident (the host sizes the grid by
-// the kernel's occupancy), so the wait ends; it is bounded all the same.
-__device__ __forceinline__ void node_barrier(const SelArgs &a, Sel *s, uint32_t &epoch) {
+// the kernel's occupancy), so the wait ends; it is bounded all the same, and a failure of any
+// wait in the library ends every other wait within a few polls.
+__device__ __forceinline__ bool node_barrier(const SelArgs &a, Sel *s, uint32_t &epoch) {
+    __shared__ uint32_t sh_ok;
     __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {
         epoch += gridDim.x;
         atomicAdd(&s->barrier, 1u);
-        uint32_t spins = 0;
+        uint32_t spins = 0, ok = 1;
         while (ld_agent32(&s->barrier) < epoch) {
-            if (++spins > a.spin_limit) { atomicAdd(&a.stats->errors, 1u); break; }
+            if (++spins > a.spin_limit) { atomicAdd(&a.stats->errors, 1u); ok = 0; break; }
+            if ((spins & 255u) == 0 && ld_agent32(&a.stats->errors) != 0) { ok = 0; break; }
             __builtin_amdgcn_s_sleep(8);
         }
         __threadfence();
+        sh_ok = ok;
     }
     __syncthreads();
+    return sh_ok != 0;
 }
 
 // Radix select of the exact k-th largest key over all of v (digits of 11, 10 and 10 bits: each
@@ -976,7 +986,7 @@ __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
         }
         __syncthreads();
         for (int i = tid; i < nb; i += kBlock) { const uint32_t h = hist[i]; if (h) atomicAdd(&gh[i], h); }
-        node_barrier(a, s, epoch);
+        if (!node_barrier(a, s, epoch)) return;   // a wait expired somewhere: give up, lgc_stats reports it
         for (int i = tid; i < kRadixBins; i += kBlock) hist[i] = i < nb ? ld_agent32(&gh[i]) : 0u;
         __syncthreads();
         if (pass == 0) find_rank_bin<kRadixBins>(hist, rank, wave_tmp, res);
@@ -991,24 +1001,13 @@ __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
     emit_chunks<SRC_PLAIN, VEC>(a, node, a.n, prefix, rank);
 }
 
-static int exact_blocks_per_cu(bool vec) {
-    static int cached[2] = {0, 0};
-    if (!cached[vec]) {
-        int nb = 0;
-        hipError_t e = vec ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_exact<true>, kBlock, 0)
-                           : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_exact<false>, kBlock, 0);
-        cached[vec] = (e == hipSuccess && nb > 0) ? nb : 1;
-    }
-    return cached[vec];
-}
-
-// The grid holds only as many blocks as are resident at once on `cus` compute units, shared
-// evenly by the nodes (the barriers need every block of a node to be running).
+// The barriers and the static chunk order need every block of a node to be running at the same
+// time.  The grid is therefore at most one block per compute unit, shared evenly by the nodes:
+// that many blocks are resident whatever the kernel's register use.
 void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st) {
-    uint32_t per_node = (uint32_t)(exact_blocks_per_cu(vec) * cus / batch);
+    uint32_t per_node = (uint32_t)(cus / batch);
     const uint32_t chunks = (a.n + kChunk - 1) / kChunk;
     if (per_node > chunks) per_node = chunks;
-    if (per_node > 1024) per_node = 1024;
     if (per_node < 1) per_node = 1;
     dim3 grid(per_node, batch);
     if (vec) hipLaunchKernelGGL(k_exact<true>, grid, dim3(kBlock), 0, st, a);
