@@ -25,11 +25,9 @@
  *  - A context owns only scratch memory.  One context serves one stream at a
  *    time and is not thread-safe; calls on one context that overlap race.
  *  - Argument errors are detected on the host before anything is launched and
- *    reported as LGC_EINVAL (null pointer, n == 0, n > 2^27 (see below), k > n, k, n or
+ *    reported as LGC_EINVAL (null pointer, n == 0, n >= 2^31, k > n, k, n or
  *    batch beyond what the context was created for, stride < n, pointers not
  *    4-byte aligned).  k == 0 is valid: nothing is selected.
- *  - n is limited to 2^27 elements per node for now: accumulate and selection calls on longer
- *    vectors return LGC_EINVAL (a run at 2^28 did not complete and is not explained yet).
  *  - No exceptions cross the boundary.  lgc_last_error gives a message for the
  *    last failing call on that context (or, with NULL, of the calling thread).
  */

@@ -127,10 +127,6 @@ lgc_status check_common(lgc_ctx *ctx, uint64_t n, int batch, uint64_t stride) {
     if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
     if (n == 0) return fail(ctx, LGC_EINVAL, "n == 0");
     if (n >= (1ull << 31)) return fail(ctx, LGC_EINVAL, "n = %llu is not below 2^31", (unsigned long long)n);
-    if (n > kMaxVerifiedN)
-        return fail(ctx, LGC_EINVAL, "n = %llu: vectors above 2^27 elements per node are switched off "
-                    "(a selection call at 2^28 elements did not finish in time; not yet explained)",
-                    (unsigned long long)n);
     if (n > ctx->max_n) return fail(ctx, LGC_EINVAL, "n = %llu exceeds the context's max_n = %llu",
                                     (unsigned long long)n, (unsigned long long)ctx->max_n);
     if (batch < 1 || batch > ctx->max_batch)
@@ -141,12 +137,13 @@ lgc_status check_common(lgc_ctx *ctx, uint64_t n, int batch, uint64_t stride) {
 
 // word offsets of the parts of one state set
 struct StateLayout {
-    size_t sel, sample_hist, fine_hist, level2_hist, radix_hist, status_cand, status_exact, words;
+    size_t ctr, sel, sample_hist, fine_hist, level2_hist, radix_hist, status_cand, status_exact, words;
 };
 StateLayout state_layout(int max_batch, uint32_t status_cand_stride, uint32_t status_exact_stride) {
     StateLayout L;
     const size_t B = (size_t)max_batch;
     size_t o = 0;
+    L.ctr = o; o += B * sizeof(Ctr) / 4;   // first: the set starts on a 256-byte boundary
     L.sel = o; o += B * sizeof(Sel) / 4;
     L.sample_hist = o; o += B * kSampleBins;
     L.fine_hist = o; o += B * kFineBins;
@@ -166,12 +163,13 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     a.stride = stride; a.n = (uint32_t)n; a.k = (uint32_t)k; a.momentum = m;
     a.rank = 0; a.cap = c->cap; a.rows = c->rows; a.cand_blocks = c->cand_blocks;
     a.status_cand_stride = c->status_cand_stride; a.status_exact_stride = c->status_exact_stride;
-    a.spin_limit = 1u << 20;
+    a.spin_limit = getenv("LGC_SPIN_LIMIT") ? (uint32_t)atol(getenv("LGC_SPIN_LIMIT")) : 1u << 20;
     a.force = 0;
     a.stats = c->stats;
     const StateLayout L = state_layout(c->max_batch, c->status_cand_stride, c->status_exact_stride);
     uint32_t *cur = c->state[c->cur];
     a.sel = (Sel *)(cur + L.sel);
+    a.ctr = (Ctr *)(cur + L.ctr);
     a.sample_hist = cur + L.sample_hist; a.fine_hist = cur + L.fine_hist; a.level2_hist = cur + L.level2_hist; a.radix_hist = cur + L.radix_hist;
     a.status_cand = (unsigned long long *)(cur + L.status_cand);
     a.status_exact = (unsigned long long *)(cur + L.status_exact);
@@ -204,14 +202,25 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
                1.5 * expected_candidates((double)n, (double)k) + 4096.0 <= (double)ctx->cap;
     }
     ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
+    const bool trace = getenv("LGC_TRACE_SYNC") != nullptr;   // diagnostic: synchronise and report after each stage
+    auto mark = [&](const char *what) {
+        if (!trace) return;
+        fprintf(stderr, "[lgc] %s enqueued ...", what); fflush(stderr);
+        hipError_t e = hipStreamSynchronize(st);
+        fprintf(stderr, " done (%s)\n", hipGetErrorString(e)); fflush(stderr);
+    };
     if (fast) {
         a.reverse = ctx->pingpong ? (ctx->calls++ & 1) : 0;
         launch_sample(a, batch, fused, vec, st);   // also clears the next call's state set
+        mark("sample+estimate");
         profile_begin(ctx, st);
         launch_candidates(a, batch, fused, vec, st);
         profile_end(ctx, st);
+        mark("candidates");
         launch_gather(a, batch, st);
+        mark("gather");
         launch_output_from_candidates(a, batch, expected_candidates((double)n, (double)k) <= 131072.0, st);
+        mark("output");
         a.force = 0;
     } else {
         launch_clear(a.next_state, a.next_words, st);

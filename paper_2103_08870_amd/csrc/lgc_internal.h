@@ -19,7 +19,6 @@ constexpr uint32_t kSample = 65536;             // sampled keys per node
 constexpr uint32_t kSampleGroups = kSample / 4; // sampled in groups of 4 neighbours
 constexpr int kSampleBins = 2048;               // first level: key >> 20
 constexpr uint32_t kMinFastN = 1u << 20;        // below this the exact path is used directly
-constexpr uint64_t kMaxVerifiedN = 1ull << 27;  // largest n per node the selection is enabled for
 
 // ---- histogram of the candidates above the estimate -------------------------
 constexpr int kFineBins = 4096;
@@ -39,16 +38,23 @@ constexpr int kRowWords = 16;
 // call clears the set of the next one.
 struct Sel {
     uint32_t t_est;       // fast path: candidates are the elements with key >= t_est
-    uint32_t cand_total;  // number of candidates found
+    uint32_t cand_total;  // number of candidates found (atomic adds in the gather kernel only)
     uint32_t thr;         // exact k-th largest key T*
     uint32_t quota;       // how many elements with key == T* are taken (lowest indices first)
     uint32_t fast_ok;     // 1: the fast path produced this node's output
-    uint32_t fast_failed; // reserved
-    uint32_t barrier;     // exact path: arrivals at the node's barrier
-    uint32_t ticket[1];   // chunk tickets of the compaction over the candidates
-    uint32_t pad[8];
+    uint32_t pad[11];
 };
 static_assert(sizeof(Sel) == 64, "Sel is one 64-byte record");
+
+// Words that blocks of one kernel update with device-scope atomics while the kernel runs.  They
+// live in a cache line of their own: a line that receives atomics from several XCDs must not
+// also receive plain stores in the same kernel (each XCD has its own, non-coherent L2).
+struct Ctr {
+    uint32_t ticket;      // chunk tickets of the look-back compaction over the candidates
+    uint32_t barrier;     // exact path: arrivals at the node's barrier
+    uint32_t pad[30];
+};
+static_assert(sizeof(Ctr) == 128, "Ctr is one 128-byte line");
 
 struct Stats {
     uint32_t fast, fallback, errors, pad;
@@ -74,6 +80,7 @@ struct SelArgs {
     Stats *stats;
     // current state set
     Sel *sel;
+    Ctr *ctr;
     uint32_t *sample_hist;    // [batch][kSampleBins]
     uint32_t *fine_hist;      // [batch][kFineBins]
     uint32_t *level2_hist;    // [batch][kFineBins]

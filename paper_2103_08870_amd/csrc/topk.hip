@@ -20,6 +20,9 @@
 //  The two output compactions (over the candidates; over v in the exact path) use one look-back
 //  chain over 4096-element chunks; chunk ids are handed out by an atomic ticket, so a chunk
 //  only ever waits for chunks that already run.
+#include <stdio.h>
+#include <stdlib.h>
+
 #include "lgc_internal.h"
 
 namespace lgc {
@@ -531,7 +534,7 @@ __device__ bool find_threshold(const SelArgs &a, int node, uint32_t total, uint3
                                uint32_t *wave_tmp, uint32_t *res, uint32_t &thr, uint32_t &quota) {
     const Sel *s = a.sel + node;
     const int tid = threadIdx.x, nt = blockDim.x;
-    if (s->fast_failed || total < a.k || total > a.cap) return false;
+    if (total < a.k || total > a.cap) return false;
     const uint32_t t_est = s->t_est;
     for (int i = tid; i < kFineBins; i += nt) hist[i] = a.fine_hist[node * kFineBins + i];
     __syncthreads();
@@ -563,7 +566,7 @@ __global__ __launch_bounds__(1024) void k_select_level2(SelArgs a) {
     const int node = blockIdx.y, tid = threadIdx.x;
     const Sel *s = a.sel + node;
     const uint32_t total = s->cand_total;
-    if (s->fast_failed || total < a.k || total > a.cap) return;
+    if (total < a.k || total > a.cap) return;
     const uint32_t t_est = s->t_est;
     for (int i = tid; i < kFineBins; i += 1024) hist[i] = a.fine_hist[node * kFineBins + i];
     __syncthreads();
@@ -601,7 +604,7 @@ __global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
     const uint32_t *cidx = a.cand_idx + (size_t)node * a.cap;
     const uint32_t *cval = a.cand_val + (size_t)node * a.cap;
     const uint32_t base = blockIdx.x * 4096u, e0 = base + tid * 4;
-    bool ok = !s->fast_failed && total >= a.k && total <= a.cap;
+    bool ok = total >= a.k && total <= a.cap;
     const uint32_t n4 = ok ? (total + 3) / 4 : 0u;   // 16-byte groups (the list's capacity is a multiple of 4)
 
     // independent loads first: the keys, my four positions, the fine histogram
@@ -756,10 +759,12 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
     for (uint32_t it = 0;; ++it) {
         __syncthreads();
         if (SRC == SRC_CAND) {
-            if (tid == 0) sh_chunk = atomicAdd(&s->ticket[0], 1u);
+            if (tid == 0) sh_chunk = atomicAdd(&a.ctr[node].ticket, 1u);
             __syncthreads();
         }
-        const uint32_t chunk = (SRC == SRC_CAND) ? sh_chunk : blockIdx.x + it * gridDim.x;
+        // block-uniform values are made wave-uniform for the compiler, so that every branch that
+        // leaves or repeats this loop (which contains barriers) is a scalar branch
+        const uint32_t chunk = __builtin_amdgcn_readfirstlane((SRC == SRC_CAND) ? sh_chunk : blockIdx.x + it * gridDim.x);
         if (chunk >= nchunks) break;
         const uint32_t base = chunk * (uint32_t)kChunk;
 
@@ -859,15 +864,16 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
             if (lane == 0) { sh_prefix[0] = pg; sh_prefix[1] = pe; sh_prefix[2] = failed; }
         }
         __syncthreads();
-        if (sh_prefix[2]) break;   // the output is invalid anyway: stop, the error is reported by lgc_stats
+        if (__builtin_amdgcn_readfirstlane(sh_prefix[2])) break;   // output invalid anyway; lgc_stats reports the error
         const uint32_t pre_gt = sh_prefix[0], pre_eq = sh_prefix[1];
 
         if (tid == 0 && chunk == nchunks - 1) {
             const uint32_t te = pre_eq + blk_eq;
             if (pre_gt + blk_gt + (te < quota ? te : quota) != a.k) atomicAdd(&a.stats->errors, 1u);
         }
-        if ((gtm | eqm) == 0) continue;
-
+        // No thread-dependent `continue` here: a second back-edge taken by only some lanes makes the
+        // compiler re-enter the loop head (barriers, ticket) for those lanes alone.
+        if ((gtm | eqm) != 0) {
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
             uint32_t cg = pre_gt + off_gt[r] + lane_gt[r];
@@ -886,6 +892,7 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
                 }
                 cg += fg; ce += fe;
             }
+        }
         }
     }
 }
@@ -919,6 +926,11 @@ void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hip
     uint32_t blocks = (a.cap + 16383) / 16384;
     if (blocks > 256) blocks = 256;
     hipLaunchKernelGGL(k_select_level2, dim3(blocks, batch), dim3(1024), 0, st, a);
+    if (getenv("LGC_TRACE_SYNC")) {
+        fprintf(stderr, "[lgc]   select_level2 (%u blocks) ...", blocks); fflush(stderr);
+        hipError_t e = hipStreamSynchronize(st);
+        fprintf(stderr, " done (%s)\n", hipGetErrorString(e)); fflush(stderr);
+    }
     blocks = (a.cap + kChunk - 1) / kChunk;
     if (blocks > 256) blocks = 256;
     hipLaunchKernelGGL(k_emit_candidates, dim3(blocks, batch), dim3(kBlock), 0, st, a);
@@ -929,7 +941,7 @@ void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hip
 // Barrier over the blocks of one node.  All of them are resident (the host sizes the grid by
 // the kernel's occupancy), so the wait ends; it is bounded all the same, and a failure of any
 // wait in the library ends every other wait within a few polls.
-__device__ __forceinline__ bool node_barrier(const SelArgs &a, Sel *s, uint32_t &epoch) {
+__device__ __forceinline__ bool node_barrier(const SelArgs &a, Ctr *s, uint32_t &epoch) {
     __shared__ uint32_t sh_ok;
     __threadfence();
     __syncthreads();
@@ -946,7 +958,7 @@ __device__ __forceinline__ bool node_barrier(const SelArgs &a, Sel *s, uint32_t 
         sh_ok = ok;
     }
     __syncthreads();
-    return sh_ok != 0;
+    return __builtin_amdgcn_readfirstlane(sh_ok) != 0;   // wave-uniform for the compiler: callers branch on it
 }
 
 // Radix select of the exact k-th largest key over all of v (digits of 11, 10 and 10 bits: each
@@ -986,7 +998,7 @@ __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
         }
         __syncthreads();
         for (int i = tid; i < nb; i += kBlock) { const uint32_t h = hist[i]; if (h) atomicAdd(&gh[i], h); }
-        if (!node_barrier(a, s, epoch)) return;   // a wait expired somewhere: give up, lgc_stats reports it
+        if (!node_barrier(a, a.ctr + node, epoch)) return;   // a wait expired somewhere: give up, lgc_stats reports it
         for (int i = tid; i < kRadixBins; i += kBlock) hist[i] = i < nb ? ld_agent32(&gh[i]) : 0u;
         __syncthreads();
         if (pass == 0) find_rank_bin<kRadixBins>(hist, rank, wave_tmp, res);

@@ -446,18 +446,29 @@ def test_full_size_workloads(B, oracle, cfg, ratio_index, iters, nodes_checked):
     ctx.close()
 
 
-def test_vectors_above_2_27_are_rejected(B):
-    ctx = B.Context(1 << 28, 1000, 1)
-    v = torch.zeros((1 << 27) + 4, device="cuda")
-    with pytest.raises(B.LgcError) as e:
-        B.lgc_topk(ctx, v, None, 1000, torch.zeros(1000, device="cuda"),
-                   torch.zeros(1000, device="cuda", dtype=torch.int32))
-    assert e.value.status == B.LGC_EINVAL and "2^27" in str(e.value)
-    ctx.close()
-
-
-@pytest.mark.skip(reason="the stress workload at its full size (n = 2^28) is switched off in the library: a fused "
-                         "selection call at that size did not finish within 100 s on the GPU and the cause is not "
-                         "found yet; the same workload at n = 2^21 is covered by test_fused_iterations_match_oracle")
 def test_full_size_stress_workload(B, oracle):
-    test_full_size_workloads(B, oracle, 5, 0, 1, 1)
+    """Config 5 at its full size (n = 2^28, long candidate lists, ties at the cut), both ratios."""
+    test_full_size_workloads(B, oracle, 5, 0, 2, 1)
+    test_full_size_workloads(B, oracle, 5, 1, 1, 1)
+
+
+def test_repeated_calls_with_short_last_chunk(B, oracle):
+    """Regression: many fused calls on one context with long candidate lists whose last
+    4096-candidate chunk is short (some lanes of a wavefront hold no candidate at all)."""
+    n, k = 5_000_000, 400_000
+    ctx = B.Context(n, k, 1)
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    g = torch.empty((1, n), device="cuda").normal_(0, 1e-3, generator=gen)
+    du, dv = torch.zeros((1, n), device="cuda"), torch.zeros((1, n), device="cuda")
+    u, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    gh = g[0].cpu().numpy()
+    for t in range(5):
+        vals = torch.zeros((1, k), device="cuda")
+        idx = torch.zeros((1, k), device="cuda", dtype=torch.int32)
+        B.lgc_accumulate_topk(ctx, g, du, dv, 0.9, k, vals, idx)
+        assert B.lgc_stats(ctx) == (1, 0, 0)
+        oracle.accumulate(gh, u, v, 0.9)
+        ov, oi = oracle.topk(v, u, k)
+        assert (idx[0].cpu().numpy().astype(np.uint32) == oi).all() and same_bits(vals[0], ov)
+        assert same_bits(dv[0], v) and same_bits(du[0], u)
+    ctx.close()
