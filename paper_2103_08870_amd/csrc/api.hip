@@ -26,9 +26,6 @@ struct lgc_ctx {
     uint32_t state_words = 0;
     int cur = 0;                      // set the next call will use (it is clean)
     int cus = 1;                      // compute units of the device
-    uint32_t cand_blocks = 0;
-    int pingpong = 1;                 // alternate the direction of the candidate pass
-    unsigned calls = 0;
     uint32_t rows = 0, status_cand_stride = 0, status_exact_stride = 0;
     uint32_t *samples = nullptr, *row_count = nullptr;
     unsigned long long *bitmap = nullptr;
@@ -161,9 +158,9 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     memset(&a, 0, sizeof a);
     a.g = g; a.u = u; a.v = v;
     a.stride = stride; a.n = (uint32_t)n; a.k = (uint32_t)k; a.momentum = m;
-    a.rank = 0; a.cap = c->cap; a.rows = c->rows; a.cand_blocks = c->cand_blocks;
+    a.rank = 0; a.cap = c->cap; a.rows = c->rows;
     a.status_cand_stride = c->status_cand_stride; a.status_exact_stride = c->status_exact_stride;
-    a.spin_limit = getenv("LGC_SPIN_LIMIT") ? (uint32_t)atol(getenv("LGC_SPIN_LIMIT")) : 1u << 20;
+    a.spin_limit = 1u << 20;
     a.force = 0;
     a.stats = c->stats;
     const StateLayout L = state_layout(c->max_batch, c->status_cand_stride, c->status_exact_stride);
@@ -202,25 +199,13 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
                1.5 * expected_candidates((double)n, (double)k) + 4096.0 <= (double)ctx->cap;
     }
     ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
-    const bool trace = getenv("LGC_TRACE_SYNC") != nullptr;   // diagnostic: synchronise and report after each stage
-    auto mark = [&](const char *what) {
-        if (!trace) return;
-        fprintf(stderr, "[lgc] %s enqueued ...", what); fflush(stderr);
-        hipError_t e = hipStreamSynchronize(st);
-        fprintf(stderr, " done (%s)\n", hipGetErrorString(e)); fflush(stderr);
-    };
     if (fast) {
-        a.reverse = ctx->pingpong ? (ctx->calls++ & 1) : 0;
         launch_sample(a, batch, fused, vec, st);   // also clears the next call's state set
-        mark("sample+estimate");
         profile_begin(ctx, st);
         launch_candidates(a, batch, fused, vec, st);
         profile_end(ctx, st);
-        mark("candidates");
         launch_gather(a, batch, st);
-        mark("gather");
         launch_output_from_candidates(a, batch, expected_candidates((double)n, (double)k) <= 131072.0, st);
-        mark("output");
         a.force = 0;
     } else {
         launch_clear(a.next_state, a.next_words, st);
@@ -264,8 +249,6 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
         if (pe != hipSuccess) { delete c; return fail(nullptr, LGC_EHIP, "hipGetDeviceProperties: %s", hipGetErrorString(pe)); }
         c->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
     }
-    if (const char *e = getenv("LGC_CAND_BLOCKS")) c->cand_blocks = (uint32_t)atol(e);  // tuning knob
-    if (const char *e = getenv("LGC_PINGPONG")) c->pingpong = atoi(e) != 0;             // tuning knob
     c->rows = (uint32_t)align_up((max_n + kRow - 1) / kRow, 4);
     c->status_exact_stride = (uint32_t)((max_n + kChunk - 1) / kChunk);
     c->status_cand_stride = (c->cap + kChunk - 1) / kChunk;

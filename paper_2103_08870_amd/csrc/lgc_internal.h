@@ -72,11 +72,9 @@ struct SelArgs {
     uint32_t rank;    // rank of the sample's order statistic used as estimate
     uint32_t cap;     // capacity of the gathered candidate list, per node
     uint32_t rows;    // bitmap rows per node (stride of row_count; bitmap stride is rows * kRowWords)
-    uint32_t cand_blocks;  // blocks per node of the candidate pass (0 = one wavefront per row)
     uint32_t status_cand_stride, status_exact_stride;  // status words per node
     uint32_t spin_limit;      // bound of the look-back wait
     int force;                // exact path chosen by the host (ignore fast_ok)
-    int reverse;              // candidate pass walks the data backwards (alternate calls)
     Stats *stats;
     // current state set
     Sel *sel;

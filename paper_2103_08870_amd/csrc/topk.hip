@@ -20,8 +20,6 @@
 //  The two output compactions (over the candidates; over v in the exact path) use one look-back
 //  chain over 4096-element chunks; chunk ids are handed out by an atomic ticket, so a chunk
 //  only ever waits for chunks that already run.
-#include <stdio.h>
-#include <stdlib.h>
 
 #include "lgc_internal.h"
 
@@ -108,10 +106,11 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(const float *__restrict__
         const uint32_t n4 = n >> 2;
         for (uint32_t i = tid; i < n4; i += nthreads) {
             f4 gg = __builtin_nontemporal_load((const f4 *)g + i);
-            f4 uu = ((const f4 *)u)[i], vv = ((const f4 *)v)[i];
+            f4 uu = __builtin_nontemporal_load((const f4 *)u + i), vv = __builtin_nontemporal_load((const f4 *)v + i);
 #pragma unroll
             for (int j = 0; j < 4; ++j) { float x = uu[j], y = vv[j]; accum1(gg[j], x, y, m); uu[j] = x; vv[j] = y; }
-            ((f4 *)u)[i] = uu; ((f4 *)v)[i] = vv;
+            __builtin_nontemporal_store(uu, (f4 *)u + i);
+            __builtin_nontemporal_store(vv, (f4 *)v + i);
         }
         for (uint32_t i = (n4 << 2) + tid; i < n; i += nthreads) {
             float uu = u[i], vv = v[i];
@@ -248,7 +247,9 @@ void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_
 // ------------------------------------------------------------------ candidate pass (the streaming kernel)
 
 // One full row of a wavefront: 4 x 256 consecutive elements, lane l holds elements 4l..4l+3 of
-// each 256.  All twelve 16-byte loads are issued before anything depends on them.
+// each 256.  All twelve 16-byte loads are issued before anything depends on them.  In the fused
+// pass every stream is touched once per call, so all loads and stores are non-temporal: on this
+// part that alone lifts the kernel from about 60 % to 72-77 % of the HBM peak.
 template <bool FUSED>
 __device__ __forceinline__ void full_row(const float *__restrict__ g, float *__restrict__ u, float *__restrict__ v,
                                          const float m, uint32_t (&bits)[4][4]) {
@@ -257,17 +258,17 @@ __device__ __forceinline__ void full_row(const float *__restrict__ g, float *__r
     for (int s = 0; s < 4; ++s) {
         if (FUSED) {
             gg[s] = __builtin_nontemporal_load((const f4 *)(g + s * 256));
-            uu[s] = *(const f4 *)(u + s * 256);
+            uu[s] = __builtin_nontemporal_load((const f4 *)(u + s * 256));
         }
-        vv[s] = *(const f4 *)(v + s * 256);
+        vv[s] = FUSED ? __builtin_nontemporal_load((const f4 *)(v + s * 256)) : *(const f4 *)(v + s * 256);
     }
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         if (FUSED) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) { float x = uu[s][j], y = vv[s][j]; accum1(gg[s][j], x, y, m); uu[s][j] = x; vv[s][j] = y; }
-            *(f4 *)(u + s * 256) = uu[s];
-            *(f4 *)(v + s * 256) = vv[s];
+            __builtin_nontemporal_store(uu[s], (f4 *)(u + s * 256));
+            __builtin_nontemporal_store(vv[s], (f4 *)(v + s * 256));
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) bits[s][j] = __float_as_uint(vv[s][j]);
@@ -280,10 +281,7 @@ __device__ __forceinline__ void full_row(const float *__restrict__ g, float *__r
 // row's candidate count as one word.  No barrier, no LDS, no atomics, nothing shared.
 template <bool FUSED, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
-    // a.reverse: walk nodes and rows backwards, so that a call starts on the data the previous
-    // (forward) call touched last, which the memory-side cache may still hold
-    const int node = a.reverse ? (int)gridDim.y - 1 - (int)blockIdx.y : (int)blockIdx.y;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int node = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t off = (size_t)node * a.stride;
     const float *__restrict__ g = a.g + off;
     float *__restrict__ u = a.u + off;
@@ -293,8 +291,7 @@ __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
     const uint32_t nrows = (a.n + kRow - 1) / kRow;
     unsigned long long *bitmap = a.bitmap + (size_t)node * a.rows * kRowWords;
     uint32_t *row_count = a.row_count + (size_t)node * a.rows;
-    for (uint32_t r0 = blockIdx.x * kWaves + wave; r0 < nrows; r0 += gridDim.x * kWaves) {
-        const uint32_t r = a.reverse ? nrows - 1 - r0 : r0;
+    for (uint32_t r = blockIdx.x * kWaves + wave; r < nrows; r += gridDim.x * kWaves) {
         const uint32_t row = r * (uint32_t)kRow;
         const uint32_t end = (a.n - row > (uint32_t)kRow) ? row + kRow : a.n;
         uint32_t bits[4][4];
@@ -351,9 +348,7 @@ __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
 
 void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st) {
     const uint32_t nrows = (a.n + kRow - 1) / kRow;
-    uint32_t blocks = (nrows + kWaves - 1) / kWaves;
-    if (a.cand_blocks && blocks > a.cand_blocks) blocks = a.cand_blocks;
-    dim3 grid(blocks, batch);
+    dim3 grid((nrows + kWaves - 1) / kWaves, batch);
     if (fused) {
         if (vec) hipLaunchKernelGGL((k_candidates<true, true>), grid, dim3(kBlock), 0, st, a);
         else hipLaunchKernelGGL((k_candidates<true, false>), grid, dim3(kBlock), 0, st, a);
@@ -926,11 +921,6 @@ void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hip
     uint32_t blocks = (a.cap + 16383) / 16384;
     if (blocks > 256) blocks = 256;
     hipLaunchKernelGGL(k_select_level2, dim3(blocks, batch), dim3(1024), 0, st, a);
-    if (getenv("LGC_TRACE_SYNC")) {
-        fprintf(stderr, "[lgc]   select_level2 (%u blocks) ...", blocks); fflush(stderr);
-        hipError_t e = hipStreamSynchronize(st);
-        fprintf(stderr, " done (%s)\n", hipGetErrorString(e)); fflush(stderr);
-    }
     blocks = (a.cap + kChunk - 1) / kChunk;
     if (blocks > 256) blocks = 256;
     hipLaunchKernelGGL(k_emit_candidates, dim3(blocks, batch), dim3(kBlock), 0, st, a);
