@@ -137,10 +137,12 @@ lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, uint6
  * written back at the selected positions:
  *        dense[idx[b][j]] <- dense[idx[b][j]] + scale*vals[b][j]
  * for nodes b = 0..batch-1 applied strictly in that order (product and sum
- * rounded separately).  idx must be distinct within one node (lgc_topk's
- * output is); across nodes they may repeat.  vals, idx: [batch][k];
- * dense: [n], zero-filled by the caller beforehand.  An index >= n is skipped
- * and counted as a device error (lgc_stats).
+ * rounded separately).  Within one node idx must be strictly ascending (which
+ * lgc_topk's output is); across nodes positions may repeat.  vals, idx:
+ * [batch][k]; dense: [n], normally zero-filled by the caller beforehand.  An
+ * index >= n is skipped and counted as a device error (lgc_stats); so is,
+ * for batch > 1, a position that is not above its predecessor (the result is
+ * then unspecified at positions that several nodes hold).
  */
 lgc_status lgc_scatter(lgc_ctx *ctx, const float *vals, const uint32_t *idx, uint64_t k, int batch,
                        float scale, float *dense, uint64_t n, void *stream);

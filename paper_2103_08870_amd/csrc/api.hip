@@ -505,6 +505,12 @@ extern "C" lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *va
     hipStream_t st = (hipStream_t)stream;
     std::vector<uint64_t> len = enc_lengths(ae, k);
     const size_t nl = ae->enc.size();
+    if (nl == 2 && launch_encoder2(vals, latent, ae->enc_dev[0], ae->enc_dev[1], (uint32_t)len[0], (uint32_t)len[1],
+                                   (uint32_t)len[2], batch, ae->slope, st)) {
+        hipError_t e2 = hipGetLastError();
+        if (e2 != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e2));
+        return LGC_OK;
+    }
     size_t need = 0;
     for (size_t l = 0; l + 1 < nl; ++l) {
         size_t f = (size_t)batch * ae->enc[l].c_out * len[l + 1];
@@ -534,6 +540,12 @@ extern "C" lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *la
     std::vector<uint64_t> out_len = dec_lengths(ae, k);
     uint64_t in_len = enc_lengths(ae, k).back();
     const size_t nl = ae->dec.size();
+    if (nl == 2 && launch_decoder2(latent, rec, ae->dec_dev[0], ae->dec_dev[1], (uint32_t)in_len, (uint32_t)out_len[0],
+                                   (uint32_t)out_len[1], batch, ae->slope, st)) {
+        hipError_t e2 = hipGetLastError();
+        if (e2 != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e2));
+        return LGC_OK;
+    }
     size_t need = 0;
     for (size_t l = 0; l + 1 < nl; ++l) {
         size_t f = (size_t)batch * ae->dec[l].c_out * out_len[l];
@@ -566,9 +578,12 @@ extern "C" lgc_status lgc_scatter(lgc_ctx *ctx, const float *vals, const uint32_
     if (!aligned(vals, 4) || !aligned(idx, 4) || !aligned(dense, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
-    for (int b = 0; b < batch; ++b)
-        launch_scatter(vals + (size_t)b * k, idx + (size_t)b * k, (uint32_t)k, scale, dense, (uint32_t)n, ctx->stats,
-                       (hipStream_t)stream);
+    // up to 8 nodes go through one launch; more are applied by one launch per node, in order
+    if (batch == 1 ||
+        !launch_scatter_nodes(vals, idx, (uint32_t)k, batch, scale, dense, (uint32_t)n, ctx->stats, (hipStream_t)stream))
+        for (int b = 0; b < batch; ++b)
+            launch_scatter(vals + (size_t)b * k, idx + (size_t)b * k, (uint32_t)k, scale, dense, (uint32_t)n, ctx->stats,
+                           (hipStream_t)stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
     return LGC_OK;

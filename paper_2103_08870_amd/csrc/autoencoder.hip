@@ -114,6 +114,144 @@ void launch_conv_transpose1d(const float *in, float *out, const LayerDev &l, uin
                            l.c_out, l.stride, l_in, l_out, (int)act, slope);
 }
 
+// ---- two-layer stacks in one launch ------------------------------------------------------------
+// The benchmark autoencoders (1 -> C1 -> C2, both layers kernel 3 / stride 2) are latency-bound
+// as separate launches; here one thread produces one latent position (encoder) or four output
+// positions (decoder) and recomputes the hidden positions it needs in registers (1.5x the hidden
+// layer's arithmetic, no intermediate tensor).  The order of the multiply-adds per output is the
+// one of the per-layer kernels above.
+
+// z[b][co][p] = b2[co] + sum_c sum_t w2[co][c][t] * h[c][2p-1+t],
+// h[c][s] = act(b1[c] + sum_t w1[c][0][t] * x[b][2s-1+t]); taps outside [0, L) contribute 0.
+template <int C1, int C2>
+__global__ __launch_bounds__(256) void k_encoder2(const float *__restrict__ x, float *__restrict__ z,
+                                                  const float *__restrict__ w1, const float *__restrict__ b1,
+                                                  const float *__restrict__ w2, const float *__restrict__ b2,
+                                                  uint32_t l0, uint32_t l1, uint32_t l2, float slope) {
+    const uint32_t p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= l2) return;
+    x += (size_t)blockIdx.y * l0;
+    z += (size_t)blockIdx.y * C2 * l2;
+    float xv[7];   // x[4p-3 .. 4p+3]
+#pragma unroll
+    for (int i = 0; i < 7; ++i) {
+        const long long q = 4ll * p - 3 + i;
+        xv[i] = (q >= 0 && q < (long long)l0) ? x[q] : 0.f;
+    }
+    bool ok[3];    // hidden positions 2p-1, 2p, 2p+1 that exist
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        const long long hp = 2ll * p - 1 + s;
+        ok[s] = hp >= 0 && hp < (long long)l1;
+    }
+    float acc[C2];
+#pragma unroll
+    for (int co = 0; co < C2; ++co) acc[co] = b2[co];
+#pragma unroll
+    for (int c = 0; c < C1; ++c) {
+        float h[3];
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            float a = b1[c];
+#pragma unroll
+            for (int t = 0; t < 3; ++t) a = fmaf(w1[c * 3 + t], xv[2 * s + t], a);
+            h[s] = ok[s] ? leaky(a, slope) : 0.f;
+        }
+#pragma unroll
+        for (int co = 0; co < C2; ++co)
+#pragma unroll
+            for (int t = 0; t < 3; ++t) acc[co] = fmaf(w2[(co * C1 + c) * 3 + t], h[t], acc[co]);
+    }
+#pragma unroll
+    for (int co = 0; co < C2; ++co) z[(size_t)co * l2 + p] = acc[co];
+}
+
+// y[b][q] = b4 + sum_c sum_{(s,t): 2s-1+t = q} w4[c][0][t] * h[c][s],
+// h[c][s] = act(b3[c] + sum_cz sum_{(r,t): 2r-1+t = s} w3[cz][c][t] * z[b][cz][r]).
+// Thread r4 writes y[4 r4 .. 4 r4 + 3]; these use h at 2 r4, 2 r4 + 1, 2 r4 + 2 and z at r4, r4 + 1.
+template <int CZ, int CH>
+__global__ __launch_bounds__(256) void k_decoder2(const float *__restrict__ z, float *__restrict__ y,
+                                                  const float *__restrict__ w3, const float *__restrict__ b3,
+                                                  const float *__restrict__ w4, const float *__restrict__ b4,
+                                                  uint32_t l2, uint32_t l1, uint32_t l0, float slope) {
+    const uint32_t r = blockIdx.x * 256 + threadIdx.x;
+    if (4ull * r >= l0) return;
+    z += (size_t)blockIdx.y * CZ * l2;
+    y += (size_t)blockIdx.y * l0;
+    const bool z0 = r < l2, z1 = r + 1 < l2;
+    float za[CZ], zb[CZ];
+#pragma unroll
+    for (int cz = 0; cz < CZ; ++cz) {
+        za[cz] = z0 ? z[(size_t)cz * l2 + r] : 0.f;
+        zb[cz] = z1 ? z[(size_t)cz * l2 + r + 1] : 0.f;
+    }
+    const uint32_t s0 = 2 * r;
+    const bool h0 = s0 < l1, h1 = s0 + 1 < l1, h2 = s0 + 2 < l1;
+    const float bias = b4[0];
+    float y0 = bias, y1 = bias, y2 = bias, y3 = bias;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        // hidden position 2r (even): tap 1 from z[r]; 2r+1 (odd): tap 0 from z[r+1], tap 2 from z[r];
+        // 2r+2 (even): tap 1 from z[r+1].  Taps that do not reach a position add nothing.
+        float a0 = b3[c], a1 = b3[c], a2 = b3[c];
+#pragma unroll
+        for (int cz = 0; cz < CZ; ++cz) {
+            const float t0 = w3[(cz * CH + c) * 3 + 0], t1 = w3[(cz * CH + c) * 3 + 1], t2 = w3[(cz * CH + c) * 3 + 2];
+            a0 = fmaf(t1, za[cz], a0);
+            a1 = fmaf(t0, zb[cz], a1);
+            a1 = fmaf(t2, za[cz], a1);
+            a2 = fmaf(t1, zb[cz], a2);
+        }
+        const float g0 = h0 ? leaky(a0, slope) : 0.f;
+        const float g1 = h1 ? leaky(a1, slope) : 0.f;
+        const float g2 = h2 ? leaky(a2, slope) : 0.f;
+        const float u0 = w4[c * 3 + 0], u1 = w4[c * 3 + 1], u2 = w4[c * 3 + 2];
+        y0 = fmaf(u1, g0, y0);                       // q = 4r   : tap 1 from h[2r]
+        y1 = fmaf(u0, g1, y1);                       // q = 4r+1 : tap 0 from h[2r+1], tap 2 from h[2r]
+        y1 = fmaf(u2, g0, y1);
+        y2 = fmaf(u1, g1, y2);                       // q = 4r+2 : tap 1 from h[2r+1]
+        y3 = fmaf(u0, g2, y3);                       // q = 4r+3 : tap 0 from h[2r+2], tap 2 from h[2r+1]
+        y3 = fmaf(u2, g1, y3);
+    }
+    const uint64_t q = 4ull * r;
+    y[q] = y0;
+    if (q + 1 < l0) y[q + 1] = y1;
+    if (q + 2 < l0) y[q + 2] = y2;
+    if (q + 3 < l0) y[q + 3] = y3;
+}
+
+static bool two_layer_shape(const LayerDev &a, const LayerDev &b) {
+    return a.ksize == 3 && a.stride == 2 && b.ksize == 3 && b.stride == 2;
+}
+
+bool launch_encoder2(const float *x, float *z, const LayerDev &a, const LayerDev &b, uint32_t l0, uint32_t l1,
+                     uint32_t l2, int batch, float slope, hipStream_t st) {
+    if (!two_layer_shape(a, b) || a.c_in != 1 || a.c_out != b.c_in) return false;
+    if (l2 == 0) return true;
+    dim3 grid((l2 + 255) / 256, batch);
+    if (a.c_out == 8 && b.c_out == 4)
+        hipLaunchKernelGGL((k_encoder2<8, 4>), grid, dim3(256), 0, st, x, z, a.w, a.b, b.w, b.b, l0, l1, l2, slope);
+    else if (a.c_out == 16 && b.c_out == 8)
+        hipLaunchKernelGGL((k_encoder2<16, 8>), grid, dim3(256), 0, st, x, z, a.w, a.b, b.w, b.b, l0, l1, l2, slope);
+    else
+        return false;
+    return true;
+}
+
+bool launch_decoder2(const float *z, float *y, const LayerDev &a, const LayerDev &b, uint32_t l2, uint32_t l1,
+                     uint32_t l0, int batch, float slope, hipStream_t st) {
+    if (!two_layer_shape(a, b) || b.c_out != 1 || a.c_out != b.c_in) return false;
+    if (l0 == 0) return true;
+    dim3 grid(((l0 + 3) / 4 + 255) / 256, batch);
+    if (a.c_in == 4 && a.c_out == 8)
+        hipLaunchKernelGGL((k_decoder2<4, 8>), grid, dim3(256), 0, st, z, y, a.w, a.b, b.w, b.b, l2, l1, l0, slope);
+    else if (a.c_in == 8 && a.c_out == 16)
+        hipLaunchKernelGGL((k_decoder2<8, 16>), grid, dim3(256), 0, st, z, y, a.w, a.b, b.w, b.b, l2, l1, l0, slope);
+    else
+        return false;
+    return true;
+}
+
 // dense[idx[j]] <- dense[idx[j]] + scale*vals[j]; indices are distinct within one launch, so no
 // atomics are needed and the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void k_scatter(const float *__restrict__ vals, const uint32_t *__restrict__ idx,
@@ -130,6 +268,68 @@ void launch_scatter(const float *vals, const uint32_t *idx, uint32_t k, float sc
                     Stats *stats, hipStream_t st) {
     if (k == 0) return;
     hipLaunchKernelGGL(k_scatter, dim3((k + 255) / 256), dim3(256), 0, st, vals, idx, k, scale, dense, n, stats);
+}
+
+// All nodes in one launch, same result as one k_scatter per node in node order.  Needs every
+// node's positions in ascending order.  The thread of (node b, entry j) looks its position up in
+// every other node's list (binary searches, one probe of each list in flight at a time); the
+// thread of the first node that holds the position owns it and adds the contributions of all
+// holders in node order; the other holders' threads leave it alone.  No atomics, no waiting.
+constexpr int kScatterNodes = 8;
+
+__global__ __launch_bounds__(256) void k_scatter_nodes(const float *__restrict__ vals,
+                                                       const uint32_t *__restrict__ idx, uint32_t k, int batch,
+                                                       float scale, float *__restrict__ dense, uint32_t n,
+                                                       uint32_t steps, Stats *stats) {
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
+    const int b = blockIdx.y;
+    if (j >= k) return;
+    const uint32_t i = idx[(size_t)b * k + j];
+    if (j > 0 && idx[(size_t)b * k + j - 1] >= i) atomicAdd(&stats->errors, 1u);   // not ascending
+    if (i >= n) { atomicAdd(&stats->errors, 1u); return; }
+    uint32_t lo[kScatterNodes], hi[kScatterNodes];
+#pragma unroll
+    for (int o = 0; o < kScatterNodes; ++o) { lo[o] = 0; hi[o] = (o < batch && o != b) ? k : 0; }
+    for (uint32_t s = 0; s < steps; ++s) {
+        uint32_t probe[kScatterNodes];
+#pragma unroll
+        for (int o = 0; o < kScatterNodes; ++o) {
+            const uint32_t mid = (lo[o] + hi[o]) >> 1;
+            probe[o] = lo[o] < hi[o] ? idx[(size_t)o * k + mid] : 0u;
+        }
+#pragma unroll
+        for (int o = 0; o < kScatterNodes; ++o) {
+            const uint32_t mid = (lo[o] + hi[o]) >> 1;
+            if (lo[o] < hi[o]) {
+                if (probe[o] < i) lo[o] = mid + 1; else hi[o] = mid;
+            }
+        }
+    }
+    // lo[o] = first entry of node o that is >= i (k if none)
+    bool held[kScatterNodes];
+#pragma unroll
+    for (int o = 0; o < kScatterNodes; ++o)
+        held[o] = o < batch && o != b && lo[o] < k && idx[(size_t)o * k + lo[o]] == i;
+    bool owner = true;
+#pragma unroll
+    for (int o = 0; o < kScatterNodes; ++o) owner = owner && !(o < b && held[o]);
+    if (!owner) return;
+    float acc = __fadd_rn(dense[i], __fmul_rn(scale, vals[(size_t)b * k + j]));
+#pragma unroll
+    for (int o = 0; o < kScatterNodes; ++o)
+        if (o > b && held[o]) acc = __fadd_rn(acc, __fmul_rn(scale, vals[(size_t)o * k + lo[o]]));
+    dense[i] = acc;
+}
+
+bool launch_scatter_nodes(const float *vals, const uint32_t *idx, uint32_t k, int batch, float scale, float *dense,
+                          uint32_t n, Stats *stats, hipStream_t st) {
+    if (batch > kScatterNodes) return false;
+    if (k == 0) return true;
+    uint32_t steps = 0;
+    while ((1ull << steps) <= k) ++steps;   // a binary search over k entries ends within this many halvings
+    hipLaunchKernelGGL(k_scatter_nodes, dim3((k + 255) / 256, batch), dim3(256), 0, st, vals, idx, k, batch, scale,
+                       dense, n, steps, stats);
+    return true;
 }
 
 }  // namespace lgc

@@ -117,7 +117,16 @@ void launch_conv1d(const float *in, float *out, const LayerDev &l, uint32_t l_in
                    int batch, bool act, float slope, hipStream_t st);
 void launch_conv_transpose1d(const float *in, float *out, const LayerDev &l, uint32_t l_in,
                              uint32_t l_out, int batch, bool act, float slope, hipStream_t st);
+// whole two-layer stacks in one launch; false = shape not covered (nothing launched)
+bool launch_encoder2(const float *x, float *z, const LayerDev &a, const LayerDev &b, uint32_t l0, uint32_t l1,
+                     uint32_t l2, int batch, float slope, hipStream_t st);
+bool launch_decoder2(const float *z, float *y, const LayerDev &a, const LayerDev &b, uint32_t l2, uint32_t l1,
+                     uint32_t l0, int batch, float slope, hipStream_t st);
 void launch_scatter(const float *vals, const uint32_t *idx, uint32_t k, float scale, float *dense,
                     uint32_t n, Stats *stats, hipStream_t st);
+
+// all nodes in one launch (positions ascending within each node); false = batch too large for it
+bool launch_scatter_nodes(const float *vals, const uint32_t *idx, uint32_t k, int batch, float scale, float *dense,
+                          uint32_t n, Stats *stats, hipStream_t st);
 
 }  // namespace lgc

@@ -95,43 +95,40 @@ __device__ void find_rank_bin(const uint32_t *hist, uint32_t rank, uint32_t *wav
 
 // ------------------------------------------------------------------ plain accumulation
 
+template <bool FUSED>
+__device__ __forceinline__ void full_row(const float *__restrict__ g, float *__restrict__ u, float *__restrict__ v,
+                                         const float m, uint32_t (&bits)[4][4]);
+
+// Same traversal as the fused candidate pass below: one wavefront per row of 1024 elements,
+// all twelve 16-byte loads of a row in flight before anything depends on them, non-temporal.
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_accumulate(const float *__restrict__ g, float *__restrict__ u,
                                                        float *__restrict__ v, uint32_t n, uint64_t stride,
                                                        float m) {
     const size_t off = (size_t)blockIdx.y * stride;
     g += off; u += off; v += off;
-    const uint32_t tid = blockIdx.x * kBlock + threadIdx.x, nthreads = gridDim.x * kBlock;
-    if (VEC) {
-        const uint32_t n4 = n >> 2;
-        for (uint32_t i = tid; i < n4; i += nthreads) {
-            f4 gg = __builtin_nontemporal_load((const f4 *)g + i);
-            f4 uu = __builtin_nontemporal_load((const f4 *)u + i), vv = __builtin_nontemporal_load((const f4 *)v + i);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { float x = uu[j], y = vv[j]; accum1(gg[j], x, y, m); uu[j] = x; vv[j] = y; }
-            __builtin_nontemporal_store(uu, (f4 *)u + i);
-            __builtin_nontemporal_store(vv, (f4 *)v + i);
-        }
-        for (uint32_t i = (n4 << 2) + tid; i < n; i += nthreads) {
-            float uu = u[i], vv = v[i];
-            accum1(g[i], uu, vv, m);
-            u[i] = uu; v[i] = vv;
-        }
-    } else {
-        for (uint32_t i = tid; i < n; i += nthreads) {
-            float uu = u[i], vv = v[i];
-            accum1(g[i], uu, vv, m);
-            u[i] = uu; v[i] = vv;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t nrows = (n + kRow - 1) / kRow;
+    for (uint32_t r = blockIdx.x * kWaves + wave; r < nrows; r += gridDim.x * kWaves) {
+        const uint32_t row = r * (uint32_t)kRow;
+        const uint32_t end = (n - row > (uint32_t)kRow) ? row + kRow : n;
+        if (VEC && row + 1024 <= end) {
+            uint32_t bits[4][4];
+            full_row<true>(g + row + lane * 4, u + row + lane * 4, v + row + lane * 4, m, bits);
+        } else {
+            for (uint32_t e = row + lane; e < end; e += 64) {
+                float uu = u[e], vv = v[e];
+                accum1(g[e], uu, vv, m);
+                u[e] = uu; v[e] = vv;
+            }
         }
     }
 }
 
 void launch_accumulate(const float *g, float *u, float *v, uint32_t n, int batch, uint64_t stride,
                        float momentum, bool vec, hipStream_t st) {
-    uint32_t blocks = (uint32_t)(((uint64_t)n + kChunk - 1) / kChunk);
-    if (blocks > 8192) blocks = 8192;
-    if (blocks == 0) blocks = 1;
-    dim3 grid(blocks, batch);
+    const uint32_t nrows = (n + kRow - 1) / kRow;
+    dim3 grid((nrows + kWaves - 1) / kWaves, batch);
     if (vec) hipLaunchKernelGGL(k_accumulate<true>, grid, dim3(kBlock), 0, st, g, u, v, n, stride, momentum);
     else hipLaunchKernelGGL(k_accumulate<false>, grid, dim3(kBlock), 0, st, g, u, v, n, stride, momentum);
 }

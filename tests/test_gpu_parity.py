@@ -301,31 +301,51 @@ def test_paper_size_autoencoder_small_input(B, oracle):
 
 # ------------------------------------------------------------------------------ a5
 
-def test_scatter_nodes_in_order(B, oracle):
-    n, k, K = 100_000, 3000, 4
-    rng = np.random.default_rng(3)
+@pytest.mark.parametrize("K,k", [(1, 3000), (2, 1), (3, 257), (4, 3001), (8, 25_600), (9, 700)])
+def test_scatter_nodes_in_order(B, oracle, K, k):
+    # up to 8 nodes go through one launch, more through one launch per node: same result
+    n = 100_000
+    rng = np.random.default_rng(3 + K)
     ctx = B.Context(n, k, K)
     common = rng.choice(n, k // 2, replace=False)          # positions that several nodes picked
-    idx = np.stack([np.sort(np.unique(np.concatenate([common, rng.choice(n, k, replace=False)]))[:k])
+    idx = np.stack([np.sort(rng.permutation(np.unique(np.concatenate([common, rng.choice(n, k, replace=False)])))[:k])
                     for _ in range(K)]).astype(np.uint32)
     vals = rng.standard_normal((K, k)).astype(np.float32)
-    dense = torch.zeros(n, device="cuda")
+    start = (rng.standard_normal(n) * 0.1).astype(np.float32)      # dense need not start at zero
+    dense = dev(start)
     B.lgc_scatter(ctx, dev(vals), dev(idx.astype(np.int32)), 1.0 / 3.0, dense)
-    ref = np.zeros(n, np.float32)
+    ref = start.copy()
     for b in range(K):
         oracle.scatter(vals[b], idx[b], 1.0 / 3.0, ref)
     assert B.lgc_stats(ctx)[2] == 0
     assert same_bits(dense, ref)
-    # out-of-range index: skipped and counted, nothing else disturbed
-    bad = idx[0].astype(np.int64).copy()
-    bad[5] = n + 17
-    dense2 = torch.zeros(n, device="cuda")
-    B.lgc_scatter(ctx, dev(vals[0]), dev(bad.astype(np.int32)), 1.0, dense2)
+    ctx.close()
+
+
+def test_scatter_bad_positions_are_counted(B, oracle):
+    n, k = 100_000, 3000
+    rng = np.random.default_rng(5)
+    ctx = B.Context(n, k, 2)
+    idx = np.stack([np.sort(rng.choice(n, k, replace=False)) for _ in range(2)]).astype(np.uint32)
+    vals = rng.standard_normal((2, k)).astype(np.float32)
+    for batch in (1, 2):
+        # out-of-range position (the largest, so the list stays ascending): skipped and counted
+        bad = idx[:batch].astype(np.int64).copy()
+        bad[0, k - 1] = n + 17
+        dense = torch.zeros(n, device="cuda")
+        B.lgc_scatter(ctx, dev(vals[:batch]), dev(bad.astype(np.int32)), 1.0, dense)
+        assert B.lgc_stats(ctx, check=False)[2] == 1
+        ref = np.zeros(n, np.float32)
+        oracle.scatter(vals[0][:k - 1], idx[0][:k - 1], 1.0, ref)
+        for b in range(1, batch):
+            oracle.scatter(vals[b], idx[b], 1.0, ref)
+        assert same_bits(dense, ref)
+    # several nodes in one call need ascending positions: a descent is counted
+    swapped = idx.copy()
+    swapped[1, [10, 11]] = swapped[1, [11, 10]]
+    dense = torch.zeros(n, device="cuda")
+    B.lgc_scatter(ctx, dev(vals), dev(swapped.astype(np.int32)), 1.0, dense)
     assert B.lgc_stats(ctx, check=False)[2] == 1
-    ref2 = np.zeros(n, np.float32)
-    keep = np.arange(k) != 5
-    oracle.scatter(vals[0][keep], idx[0][keep], 1.0, ref2)
-    assert same_bits(dense2, ref2)
     ctx.close()
 
 
