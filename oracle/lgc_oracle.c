@@ -265,3 +265,113 @@ int oracle_scatter(const float *vals, const uint32_t *idx, size_t k, float scale
     }
     return 0;
 }
+
+/* ------------------------------------------------------ per-layer selection */
+
+/*
+ * Per-layer top-k — Sec. V-A and the layer loop of Alg. 1 / Alg. 2: the
+ * gradient of every layer l (a contiguous segment of n_l elements of the flat
+ * vector) is thresholded on its own, mu_l values are kept, and the kept values
+ * of all layers are concatenated in layer order.
+ *
+ * offsets[0..n_seg]: segment l is [offsets[l], offsets[l+1]); offsets[0] = 0,
+ * offsets[n_seg] = n.  ks[l] = mu_l <= n_l.  Each segment is selected exactly
+ * like the flat vector in oracle_topk (same key, same tie rule); positions are
+ * reported in the flat vector's numbering, so the concatenation is ascending.
+ * out_vals / out_idx hold sum(ks) entries.
+ */
+int oracle_topk_segmented(float *v, float *u, size_t n, size_t n_seg,
+                          const uint64_t *offsets, const uint64_t *ks,
+                          float *out_vals, uint32_t *out_idx)
+{
+    if (n_seg == 0 || offsets[0] != 0 || offsets[n_seg] != n) return -1;
+    size_t o = 0;
+    for (size_t l = 0; l < n_seg; ++l) {
+        if (offsets[l + 1] < offsets[l]) return -1;
+        size_t lo = (size_t)offsets[l], len = (size_t)(offsets[l + 1] - offsets[l]);
+        size_t k = (size_t)ks[l];
+        if (oracle_topk(v + lo, u ? u + lo : NULL, len, k, out_vals + o, out_idx + o) != 0)
+            return -1;
+        for (size_t j = 0; j < k; ++j) out_idx[o + j] += (uint32_t)lo;
+        o += k;
+    }
+    return 0;
+}
+
+/* --------------------------------------- ring-allreduce: shared positions */
+
+/*
+ * Values at positions chosen by another node — Sec. V-A, ring-allreduce
+ * pattern: one node selects, sends its positions, and every other node builds
+ * its own g~ from the SAME positions.  The mask / residual lines of Alg. 2 then
+ * apply with that mask: what is sent leaves the residual (and, with the
+ * momentum correction, the momentum buffer).
+ *     vals[j] = v[idx[j]] ; v[idx[j]] = +0 ; u[idx[j]] = +0
+ * idx must be distinct.  u may be NULL.
+ */
+int oracle_gather(float *v, float *u, size_t n, const uint32_t *idx, size_t k, float *out_vals)
+{
+    for (size_t j = 0; j < k; ++j) {
+        if (idx[j] >= n) return -1;
+        out_vals[j] = v[idx[j]];
+        v[idx[j]] = 0.0f;
+        if (u) u[idx[j]] = 0.0f;
+    }
+    return 0;
+}
+
+/*
+ * Average of the nodes' compressed representations — Sec. V-C / Alg. 2:
+ * g^avg = (1/K) sum_k g^c_k.  Reading taken for the rounding: like the
+ * scatter, every term is scaled first and the terms are added in node order,
+ *     out[i] = (..((0 + scale*x_0[i]) + scale*x_1[i]) + ...) + scale*x_{K-1}[i],
+ * each product and each sum rounded to fp32 on its own.  x: [batch][len].
+ */
+void oracle_average(const float *x, size_t batch, size_t len, float scale, float *out)
+{
+    for (size_t i = 0; i < len; ++i) {
+        float acc = 0.0f;
+        for (size_t b = 0; b < batch; ++b) {
+            volatile float s = scale * x[b * len + i];
+            volatile float a = acc + s;
+            acc = a;
+        }
+        out[i] = acc;
+    }
+}
+
+/* ------------------------------------------- parameter server: innovation */
+
+/*
+ * Innovation component — Alg. 1 (threshold_inv, mask_inv, g~^I = g~ .* mask_inv)
+ * and Sec. IV-C: a vector of the size of g~ holding the top-magnitude values
+ * of g~ and zeros elsewhere.  Alg. 1 forms it inside the layer loop, so it is
+ * taken per layer: segment l of g~ is [offsets[l], offsets[l+1]) and keeps
+ * ks[l] values (same key and tie rule as the selection itself, exactly ks[l]
+ * kept).  One segment covering everything gives the flat form.
+ * vals is not modified.  out: [k], +0 where nothing is kept.
+ */
+int oracle_innovation(const float *vals, size_t k, size_t n_seg, const uint64_t *offsets,
+                      const uint64_t *ks, float *out)
+{
+    if (n_seg == 0 || offsets[0] != 0 || offsets[n_seg] != k) return -1;
+    for (size_t j = 0; j < k; ++j) out[j] = 0.0f;
+    for (size_t l = 0; l < n_seg; ++l) {
+        if (offsets[l + 1] < offsets[l]) return -1;
+        size_t lo = (size_t)offsets[l], len = (size_t)(offsets[l + 1] - offsets[l]);
+        size_t kk = (size_t)ks[l];
+        if (kk > len) return -1;
+        if (kk == 0) continue;
+        uint64_t *ord = (uint64_t *)malloc(len * sizeof(uint64_t));
+        if (!ord) return -1;
+        for (size_t i = 0; i < len; ++i)
+            ord[i] = ((uint64_t)mag_key(vals[lo + i]) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)i);
+        qsort(ord, len, sizeof(uint64_t), cmp_u64_desc);
+        for (size_t j = 0; j < kk; ++j) {
+            size_t i = 0xFFFFFFFFu - (uint32_t)(ord[j] & 0xFFFFFFFFu);
+            out[lo + i] = vals[lo + i];
+        }
+        free(ord);
+    }
+    return 0;
+}

@@ -67,6 +67,15 @@ def _load():
         lib.oracle_decode.restype = C.c_int
         lib.oracle_scatter.argtypes = [fp, u32p, C.c_size_t, C.c_float, fp, C.c_size_t]
         lib.oracle_scatter.restype = C.c_int
+        u64p = C.POINTER(C.c_uint64)
+        lib.oracle_topk_segmented.argtypes = [fp, fp, C.c_size_t, C.c_size_t, u64p, u64p, fp, u32p]
+        lib.oracle_topk_segmented.restype = C.c_int
+        lib.oracle_gather.argtypes = [fp, fp, C.c_size_t, u32p, C.c_size_t, fp]
+        lib.oracle_gather.restype = C.c_int
+        lib.oracle_average.argtypes = [fp, C.c_size_t, C.c_size_t, C.c_float, fp]
+        lib.oracle_average.restype = None
+        lib.oracle_innovation.argtypes = [fp, C.c_size_t, C.c_size_t, u64p, u64p, fp]
+        lib.oracle_innovation.restype = C.c_int
         _lib = lib
     return _lib
 
@@ -200,3 +209,75 @@ def scatter(vals: np.ndarray, idx: np.ndarray, scale: float, dense: np.ndarray) 
     rc = _load().oracle_scatter(_f(vals), _u(idx), vals.size, np.float32(scale), _f(dense), dense.size)
     if rc != 0:
         raise ValueError("oracle_scatter: index out of range")
+
+
+# ------------------------------------------------------ per-layer selection
+def _u64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.uint64))
+
+
+def topk_segmented(v: np.ndarray, u, offsets, ks):
+    """Per-layer top-k (Sec. V-A; layer loop of Alg. 1 / Alg. 2): segment l =
+    [offsets[l], offsets[l+1]) keeps ks[l] values; results concatenated in layer
+    order, positions in the flat numbering.  Zeroes v (and u) where selected."""
+    off, kk = _u64(offsets), _u64(ks)
+    assert off.size == kk.size + 1
+    total = int(kk.sum())
+    vals = np.zeros(total, dtype=np.float32)
+    idx = np.zeros(total, dtype=np.uint32)
+    u64p = C.POINTER(C.c_uint64)
+    rc = _load().oracle_topk_segmented(_f(v), _f(u) if u is not None else None, v.size, kk.size,
+                                       off.ctypes.data_as(u64p), kk.ctypes.data_as(u64p), _f(vals), _u(idx))
+    if rc != 0:
+        raise ValueError("oracle_topk_segmented: bad arguments")
+    return vals, idx
+
+
+# --------------------------------------------------- ring-allreduce variant
+def gather(v: np.ndarray, u, idx: np.ndarray) -> np.ndarray:
+    """Values at positions another node selected (Sec. V-A, ring-allreduce); the
+    positions leave the residual v and the momentum buffer u."""
+    vals = np.zeros(idx.size, dtype=np.float32)
+    rc = _load().oracle_gather(_f(v), _f(u) if u is not None else None, v.size, _u(idx), idx.size, _f(vals))
+    if rc != 0:
+        raise ValueError("oracle_gather: index out of range")
+    return vals
+
+
+def average(x: np.ndarray, scale: float) -> np.ndarray:
+    """x [K][len] -> sum over nodes, in node order, of scale*x_k (Alg. 2: g^avg)."""
+    assert x.ndim == 2
+    out = np.zeros(x.shape[1], dtype=np.float32)
+    _load().oracle_average(_f(x), x.shape[0], x.shape[1], np.float32(scale), _f(out))
+    return out
+
+
+# ------------------------------------------------ parameter server: innovation
+def innovation(vals: np.ndarray, offsets, ks) -> np.ndarray:
+    """g~^I of Alg. 1: per segment of g~ the ks[l] top-magnitude values, zeros elsewhere."""
+    off, kk = _u64(offsets), _u64(ks)
+    out = np.zeros(vals.size, dtype=np.float32)
+    u64p = C.POINTER(C.c_uint64)
+    rc = _load().oracle_innovation(_f(vals), vals.size, kk.size, off.ctypes.data_as(u64p),
+                                   kk.ctypes.data_as(u64p), _f(out))
+    if rc != 0:
+        raise ValueError("oracle_innovation: bad arguments")
+    return out
+
+
+def decode_with_innovation(latent: np.ndarray, innov: np.ndarray, k: int, enc: Sequence[Layer],
+                           dec: Sequence[Layer], w: Sequence[np.ndarray], b: Sequence[np.ndarray],
+                           slope: float = 0.0) -> np.ndarray:
+    """D_c(g^c, g~^I) of Sec. IV-C / Sec. V-B: all decoder layers but the last run as in
+    decode(); their output (length k) gets the innovation vector as one more
+    channel, appended last; the final stride-1 layer maps the C+1 channels to 1."""
+    assert dec[-1][3] == 1 and dec[-1][0] == dec[-2][1] + 1 and dec[-1][1] == 1
+    out_len = decoder_lengths(k, enc, dec)
+    x = np.ascontiguousarray(latent, dtype=np.float32)
+    l_in = x.shape[1]
+    for (ci, co, ks, st), wl, bl, lo in zip(dec[:-1], w[:-1], b[:-1], out_len[:-1]):
+        x = conv_transpose1d(x, wl, bl, ks, st, lo, True, slope)
+    assert x.shape[1] == k == innov.size
+    x = np.concatenate([x, innov.reshape(1, k).astype(np.float32)], axis=0)
+    ci, co, ks, st = dec[-1]
+    return conv_transpose1d(x, w[-1], b[-1], ks, st, k, False, slope)[0]
