@@ -35,6 +35,9 @@ def parse():
     p.add_argument("--workload", type=int, default=2, help="1..5 (default 2: ResNet50-sized)")
     p.add_argument("--ratio-index", type=int, default=-1, help="which of the workload's ratios")
     p.add_argument("--grad-sets", type=int, default=0, help="distinct gradient sets kept in HBM (0 = workload's)")
+    p.add_argument("--pattern", choices=["ps", "rar"], default="ps",
+                   help="ps: every node selects (default, the headline); rar: ring-allreduce pattern, one "
+                        "rotating node selects and the others take the values at its positions (Alg. 2)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-kernel-events", action="store_true",
                    help="do not bracket the streaming kernel with HIP events (roofline.achieved = null)")
@@ -108,11 +111,26 @@ def main():
     rec = torch.zeros((K, k), device="cuda")
     dense = torch.zeros(n, device="cuda")
 
-    def step(t):
+    def step_ps(t):
         B.lgc_accumulate_topk(ctx, grads[t % sets], u, v, w.momentum, k, vals, idx)
         B.lgc_encode(ctx, ae, vals, lat)
         B.lgc_decode(ctx, ae, lat, rec)
         B.lgc_scatter(ctx, rec, idx, 1.0 / K, dense)
+
+    lat_avg = torch.zeros((1, lat.shape[1]), device="cuda")
+
+    def step_rar(t):
+        g, L = grads[t % sets], t % K                 # node L selects in this iteration
+        B.lgc_accumulate_topk(ctx, g[L], u[L], v[L], w.momentum, k, vals[L], idx[0])
+        for lo, hi in ((0, L), (L + 1, K)):
+            if hi > lo:
+                B.lgc_accumulate_gather(ctx, g[lo:hi], u[lo:hi], v[lo:hi], w.momentum, idx[0], vals[lo:hi])
+        B.lgc_encode(ctx, ae, vals, lat)
+        B.lgc_average(ctx, lat, 1.0 / K, lat_avg[0])
+        B.lgc_decode(ctx, ae, lat_avg, rec[:1])
+        B.lgc_scatter(ctx, rec[:1], idx[:1], 1.0, dense)
+
+    step = step_ps if args.pattern == "ps" else step_rar
 
     for t in range(args.warmup):
         step(t)
@@ -159,9 +177,15 @@ def main():
                 "traffic": MEASURED_TRAFFIC.get(w.cfg) if args.ratio_index in (-1, len(w.ks) - 1) else None, "kernel": "lgc::k_candidates<true, true> (fused accumulate + candidate bitmap, all nodes in one launch)",
                 "algorithmic_bytes_per_launch": ALGO_BYTES_PER_ELEM * K * n}
     if kern_launches:
-        avg_ms = kern_ms / kern_launches
-        ach = ALGO_BYTES_PER_ELEM * K * n / (avg_ms * 1e-3) / 1e9
-        roofline.update(achieved=ach, frac=ach / HBM_PEAK_GBS, kernel_avg_ms=avg_ms, launches=kern_launches)
+        # ps: one streaming launch per step covers all K nodes; rar: the selecting node's launch and
+        # the other nodes' launches together cover them, so the bytes are counted per step
+        per_step_ms = kern_ms / args.steps
+        ach = ALGO_BYTES_PER_ELEM * K * n / (per_step_ms * 1e-3) / 1e9
+        roofline.update(achieved=ach, frac=ach / HBM_PEAK_GBS, kernel_avg_ms=kern_ms / kern_launches,
+                        launches=kern_launches)
+        if args.pattern == "rar":
+            roofline.update(kernel="lgc::k_candidates<true, true> (selecting node) + lgc::k_accumulate<true> "
+                                   "(other nodes): the streaming launches of one step", traffic=None)
 
     out = {
         "metric": "gradient elements/sec compressed (accumulate+top-k+AE encode); % of HBM peak",
@@ -171,7 +195,10 @@ def main():
         "config": {"workload": f"config {w.cfg} ({w.name}-sized): {K} nodes x {n} fp32 elements, k={k}/node, "
                                f"momentum {w.momentum}, autoencoder {'->'.join(map(str, w.ae_channels))}, "
                                f"{sets} gradient sets resident in HBM",
-                   "step": "accumulate+top-k (fused, all nodes in one call) + encode + decode + scatter"},
+                   "step": "accumulate+top-k (fused, all nodes in one call) + encode + decode + scatter"
+                           if args.pattern == "ps" else
+                           "ring-allreduce pattern: accumulate+top-k on the selecting node, accumulate+gather at "
+                           "its positions on the others, encode (all), average, decode (once), scatter (once)"},
         "whole_step_hbm_frac": ALGO_BYTES_PER_ELEM * value / (HBM_PEAK_GBS * 1e9),
         "whole_step_algorithmic_GBps": ALGO_BYTES_PER_ELEM * value / 1e9,
         "select_path": {"fast": fast, "fallback": fallback},

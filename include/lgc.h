@@ -147,6 +147,37 @@ lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, uint6
 lgc_status lgc_scatter(lgc_ctx *ctx, const float *vals, const uint32_t *idx, uint64_t k, int batch,
                        float scale, float *dense, uint64_t n, void *stream);
 
+/* ---- ring-allreduce pattern (Sec. V-A, Sec. V-C, Alg. 2) ---- */
+
+/*
+ * Values at positions another node selected — Sec. V-A: under ring-allreduce
+ * one node selects and shares its positions; every other node builds its g~
+ * from the same positions, and the mask / residual lines of Alg. 2 apply with
+ * that mask.  For every node b and j < k:
+ *        out_vals[b][j] = v[b][idx[j]] ;  v[b][idx[j]] = +0 ;  u[b][idx[j]] = +0
+ * idx: [k] device uint32, ONE list shared by all `batch` nodes, distinct
+ * (lgc_topk's out_idx of the selecting node); u may be NULL.  A position >= n
+ * yields 0 and is counted as a device error (lgc_stats).
+ */
+lgc_status lgc_gather(lgc_ctx *ctx, float *v, float *u /* nullable */, uint64_t n, int batch,
+                      uint64_t stride, const uint32_t *idx, uint64_t k, float *out_vals, void *stream);
+
+/* lgc_accumulate (a1) followed by lgc_gather: the whole per-iteration work of a
+ * node that does not select (one streaming pass, no selection at all). */
+lgc_status lgc_accumulate_gather(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n, int batch,
+                                 uint64_t stride, float momentum, const uint32_t *idx, uint64_t k,
+                                 float *out_vals, void *stream);
+
+/*
+ * Average of the nodes' compressed representations — Alg. 2 / Sec. V-C,
+ * g^avg = (1/K) sum_k g^c_k:
+ *        out[i] = (..((0 + scale*x[0][i]) + scale*x[1][i]) + ..) + scale*x[batch-1][i]
+ * every product and sum rounded to fp32 on its own, nodes in order (the same
+ * convention as lgc_scatter).  x: [batch][len]; out: [len], may not alias x.
+ */
+lgc_status lgc_average(lgc_ctx *ctx, const float *x, uint64_t len, int batch, float scale, float *out,
+                       void *stream);
+
 /* ---- diagnostics (never needed on the hot path) ---- */
 
 /* LGC_OPT_SELECT_PATH: 0 = automatic (sampled-threshold fast path with the

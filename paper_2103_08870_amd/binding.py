@@ -24,6 +24,7 @@ EXPORTS = [
     "lgc_accumulate", "lgc_topk", "lgc_accumulate_topk",
     "lgc_ae_create", "lgc_ae_destroy", "lgc_latent_len", "lgc_encode", "lgc_decode",
     "lgc_scatter", "lgc_set_option", "lgc_stats", "lgc_profile_read",
+    "lgc_gather", "lgc_accumulate_gather", "lgc_average",
 ]
 
 
@@ -77,6 +78,12 @@ def lib() -> C.CDLL:
     l.lgc_decode.restype = i32
     l.lgc_scatter.argtypes = [vp, vp, vp, u64, i32, f32, vp, u64, vp]
     l.lgc_scatter.restype = i32
+    l.lgc_gather.argtypes = [vp, vp, vp, u64, i32, u64, vp, u64, vp, vp]
+    l.lgc_gather.restype = i32
+    l.lgc_accumulate_gather.argtypes = [vp, vp, vp, vp, u64, i32, u64, f32, vp, u64, vp, vp]
+    l.lgc_accumulate_gather.restype = i32
+    l.lgc_average.argtypes = [vp, vp, u64, i32, f32, vp, vp]
+    l.lgc_average.restype = i32
     l.lgc_set_option.argtypes = [vp, i32, C.c_int64]
     l.lgc_set_option.restype = i32
     l.lgc_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]
@@ -224,6 +231,35 @@ def lgc_scatter(ctx: Context, vals: torch.Tensor, idx: torch.Tensor, scale: floa
     batch, k = (1, vals.shape[0]) if vals.dim() == 1 else vals.shape
     _check(lib().lgc_scatter(ctx.h, _ptr(vals, torch.float32), _ptr(idx, torch.int32), k, batch, scale,
                              _ptr(dense, torch.float32), dense.numel(), _stream()), ctx.h)
+
+
+def lgc_gather(ctx: Context, v: torch.Tensor, u: Optional[torch.Tensor], idx: torch.Tensor,
+               out_vals: torch.Tensor) -> None:
+    """Values of every node at the shared positions idx [k]; v, u zeroed there.  out_vals [batch][k]."""
+    n, batch, stride = _layout(v)
+    assert u is None or _layout(u) == (n, batch, stride)
+    k = idx.numel()
+    assert idx.is_contiguous() and out_vals.is_contiguous() and out_vals.numel() == batch * k
+    _check(lib().lgc_gather(ctx.h, _ptr(v, torch.float32), _ptr(u, torch.float32), n, batch, stride,
+                            _ptr(idx, torch.int32), k, _ptr(out_vals, torch.float32), _stream()), ctx.h)
+
+
+def lgc_accumulate_gather(ctx: Context, g: torch.Tensor, u: torch.Tensor, v: torch.Tensor, momentum: float,
+                          idx: torch.Tensor, out_vals: torch.Tensor) -> None:
+    n, batch, stride = _layout(v)
+    assert _layout(g) == _layout(u) == (n, batch, stride)
+    k = idx.numel()
+    assert idx.is_contiguous() and out_vals.is_contiguous() and out_vals.numel() == batch * k
+    _check(lib().lgc_accumulate_gather(ctx.h, _ptr(g, torch.float32), _ptr(u, torch.float32), _ptr(v, torch.float32),
+                                       n, batch, stride, momentum, _ptr(idx, torch.int32), k,
+                                       _ptr(out_vals, torch.float32), _stream()), ctx.h)
+
+
+def lgc_average(ctx: Context, x: torch.Tensor, scale: float, out: torch.Tensor) -> None:
+    """x [batch][len] -> out [len]: sum over nodes, in order, of scale*x."""
+    assert x.dim() == 2 and x.is_contiguous() and out.is_contiguous() and out.numel() == x.shape[1]
+    _check(lib().lgc_average(ctx.h, _ptr(x, torch.float32), x.shape[1], x.shape[0], scale,
+                             _ptr(out, torch.float32), _stream()), ctx.h)
 
 
 def lgc_set_option(ctx: Context, opt: int, value: int) -> None:

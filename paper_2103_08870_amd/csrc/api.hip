@@ -589,6 +589,60 @@ extern "C" lgc_status lgc_scatter(lgc_ctx *ctx, const float *vals, const uint32_
     return LGC_OK;
 }
 
+// ------------------------------------------------------------------ ring-allreduce pattern
+
+static lgc_status gather_common(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n, int batch,
+                                uint64_t stride, float momentum, const uint32_t *idx, uint64_t k, float *out_vals,
+                                void *stream) {
+    lgc_status s = check_common(ctx, n, batch, stride);
+    if (s != LGC_OK) return s;
+    if (!v || (g && !u)) return fail(ctx, LGC_EINVAL, "v (and, with g, u) must not be NULL");
+    if (k > n) return fail(ctx, LGC_EINVAL, "k > n");
+    if (k > 0 && (!idx || !out_vals)) return fail(ctx, LGC_EINVAL, "idx and out_vals must not be NULL");
+    if (!aligned(g, 4) || !aligned(u, 4) || !aligned(v, 4) || !aligned(idx, 4) || !aligned(out_vals, 4))
+        return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    hipStream_t st = (hipStream_t)stream;
+    if (g) {
+        const bool vec = aligned(v, 16) && aligned(u, 16) && aligned(g, 16) && (batch == 1 || stride % 4 == 0);
+        profile_begin(ctx, st);
+        launch_accumulate(g, u, v, (uint32_t)n, batch, stride, momentum, vec, st);
+        profile_end(ctx, st);
+    }
+    launch_gather_at(v, u, stride, (uint32_t)n, batch, idx, (uint32_t)k, out_vals, ctx->stats, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return LGC_OK;
+}
+
+extern "C" lgc_status lgc_gather(lgc_ctx *ctx, float *v, float *u, uint64_t n, int batch, uint64_t stride,
+                                 const uint32_t *idx, uint64_t k, float *out_vals, void *stream) {
+    return gather_common(ctx, nullptr, u, v, n, batch, stride, 0.f, idx, k, out_vals, stream);
+}
+
+extern "C" lgc_status lgc_accumulate_gather(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n, int batch,
+                                            uint64_t stride, float momentum, const uint32_t *idx, uint64_t k,
+                                            float *out_vals, void *stream) {
+    if (ctx && !g) return fail(ctx, LGC_EINVAL, "g must not be NULL");
+    return gather_common(ctx, g, u, v, n, batch, stride, momentum, idx, k, out_vals, stream);
+}
+
+extern "C" lgc_status lgc_average(lgc_ctx *ctx, const float *x, uint64_t len, int batch, float scale, float *out,
+                                  void *stream) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    if (batch < 1 || batch > ctx->max_batch) return fail(ctx, LGC_EINVAL, "batch = %d outside [1, %d]", batch, ctx->max_batch);
+    if (len >= (1ull << 32)) return fail(ctx, LGC_EINVAL, "len must be below 2^32");
+    if (len > 0 && (!x || !out)) return fail(ctx, LGC_EINVAL, "NULL data pointer");
+    if (!aligned(x, 4) || !aligned(out, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    launch_average(x, (uint32_t)len, batch, scale, out, (hipStream_t)stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return LGC_OK;
+}
+
 // ------------------------------------------------------------------ diagnostics
 
 extern "C" lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value) {

@@ -332,4 +332,43 @@ bool launch_scatter_nodes(const float *vals, const uint32_t *idx, uint32_t k, in
     return true;
 }
 
+// ---- ring-allreduce pattern ---------------------------------------------------------------------
+
+// out[b][j] = v[b][idx[j]]; v[b][idx[j]] = u[b][idx[j]] = +0.  The positions are shared by the nodes
+// and distinct, so every element is touched by one thread only.
+__global__ __launch_bounds__(256) void k_gather_at(float *__restrict__ v, float *__restrict__ u, uint64_t stride,
+                                                   uint32_t n, const uint32_t *__restrict__ idx, uint32_t k,
+                                                   float *__restrict__ out, Stats *stats) {
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= k) return;
+    const size_t off = (size_t)blockIdx.y * stride;
+    const uint32_t i = idx[j];
+    float *o = out + (size_t)blockIdx.y * k + j;
+    if (i >= n) { *o = 0.f; atomicAdd(&stats->errors, 1u); return; }
+    *o = v[off + i];
+    v[off + i] = 0.f;
+    if (u) u[off + i] = 0.f;
+}
+
+void launch_gather_at(float *v, float *u, uint64_t stride, uint32_t n, int batch, const uint32_t *idx, uint32_t k,
+                      float *out, Stats *stats, hipStream_t st) {
+    if (k == 0) return;
+    hipLaunchKernelGGL(k_gather_at, dim3((k + 255) / 256, batch), dim3(256), 0, st, v, u, stride, n, idx, k, out, stats);
+}
+
+// out[i] = (..((0 + scale*x[0][i]) + scale*x[1][i]) + ..), products and sums rounded one by one
+__global__ __launch_bounds__(256) void k_average(const float *__restrict__ x, uint32_t len, int batch, float scale,
+                                                 float *__restrict__ out) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= len) return;
+    float acc = 0.f;
+    for (int b = 0; b < batch; ++b) acc = __fadd_rn(acc, __fmul_rn(scale, x[(size_t)b * len + i]));
+    out[i] = acc;
+}
+
+void launch_average(const float *x, uint32_t len, int batch, float scale, float *out, hipStream_t st) {
+    if (len == 0) return;
+    hipLaunchKernelGGL(k_average, dim3((len + 255) / 256), dim3(256), 0, st, x, len, batch, scale, out);
+}
+
 }  // namespace lgc

@@ -129,4 +129,8 @@ void launch_scatter(const float *vals, const uint32_t *idx, uint32_t k, float sc
 bool launch_scatter_nodes(const float *vals, const uint32_t *idx, uint32_t k, int batch, float scale, float *dense,
                           uint32_t n, Stats *stats, hipStream_t st);
 
+void launch_gather_at(float *v, float *u, uint64_t stride, uint32_t n, int batch, const uint32_t *idx, uint32_t k,
+                      float *out, Stats *stats, hipStream_t st);
+void launch_average(const float *x, uint32_t len, int batch, float scale, float *out, hipStream_t st);
+
 }  // namespace lgc

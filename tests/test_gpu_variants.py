@@ -1,0 +1,126 @@
+"""GPU parity of the ring-allreduce pattern's calls (values at shared positions, average of the
+compressed representations) and of the whole ring-allreduce iteration, through the C ABI, against
+the CPU oracle: bit-exact for values, residual, momentum buffer and average; autoencoder outputs
+within 1e-4 relative L2."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2103_08870_amd import synth
+from test_gpu_parity import B, REL_L2_TOL, dev, make_ae, rel_l2, same_bits  # noqa: F401  (B is a fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("n,batch,pad,k", [(5, 1, 0, 2), (4097, 2, 3, 100), (1_000_003, 3, 1, 5000), (2_000_000, 4, 0, 0)])
+def test_gather_and_accumulate_gather(B, oracle, n, batch, pad, k):
+    rng = np.random.default_rng(n + k)
+    stride = n + pad
+    ctx = B.Context(n, max(k, 1), batch)
+    u = rng.standard_normal((batch, stride)).astype(np.float32)
+    v = rng.standard_normal((batch, stride)).astype(np.float32)
+    du, dv = dev(u), dev(v)
+    for t in range(3):
+        idx = np.sort(rng.choice(n, k, replace=False)).astype(np.uint32)
+        didx = dev(idx.astype(np.int32))
+        out = torch.full((batch, k), 7.0, device="cuda")
+        if t == 1:      # plain gather, without the momentum buffer on the odd iteration
+            B.lgc_gather(ctx, dv[:, :n], None, didx, out)
+            ref = [oracle.gather(v[b, :n], None, idx) for b in range(batch)]
+        else:
+            g = (rng.standard_normal((batch, stride)) * 0.1).astype(np.float32)
+            B.lgc_accumulate_gather(ctx, dev(g)[:, :n], du[:, :n], dv[:, :n], 0.9, didx, out)
+            ref = []
+            for b in range(batch):
+                oracle.accumulate(g[b, :n].copy(), u[b, :n], v[b, :n], 0.9)
+                ref.append(oracle.gather(v[b, :n], u[b, :n], idx))
+        assert B.lgc_stats(ctx)[2] == 0
+        for b in range(batch):
+            assert same_bits(out[b], ref[b])
+        assert same_bits(dv, v) and same_bits(du, u)          # padding untouched too
+    ctx.close()
+
+
+def test_gather_position_out_of_range_is_counted(B, oracle):
+    n, k = 1000, 10
+    ctx = B.Context(n, k, 1)
+    v = np.arange(n, dtype=np.float32)
+    dv = dev(v)
+    idx = np.arange(0, 100, 10).astype(np.int64)
+    idx[3] = n + 5
+    out = torch.full((1, k), 7.0, device="cuda")
+    B.lgc_gather(ctx, dv, None, dev(idx.astype(np.int32)), out)
+    assert B.lgc_stats(ctx, check=False)[2] == 1
+    keep = np.arange(k) != 3
+    ref = oracle.gather(v, None, idx[keep].astype(np.uint32))
+    o = out[0].cpu().numpy()
+    assert (o[keep] == ref).all() and o[3] == 0.0
+    assert same_bits(dv, v)
+    ctx.close()
+
+
+@pytest.mark.parametrize("K,length", [(1, 1), (3, 1000), (4, 25_600), (8, 89_001)])
+def test_average(B, oracle, K, length):
+    rng = np.random.default_rng(K + length)
+    ctx = B.Context(16, 1, K)
+    x = rng.standard_normal((K, length)).astype(np.float32)
+    out = torch.zeros(length, device="cuda")
+    for scale in (1.0 / K, 1.0 / 3.0):
+        B.lgc_average(ctx, dev(x), scale, out)
+        assert same_bits(out, oracle.average(x, scale))
+    ctx.close()
+
+
+@pytest.mark.parametrize("cfg,n", [(2, 1_300_000), (3, 1_100_000)])
+def test_ring_allreduce_iterations(B, oracle, cfg, n):
+    """Alg. 2 with the selecting node rotating: the selecting node runs accumulate + top-k, the
+    others accumulate and take the values at its positions; all encode, the compressed
+    representations are averaged, decoded once and placed once.  Every stage is compared."""
+    w = synth.workload(cfg, n=n)
+    K, k = w.nodes, w.k
+    ae, enc, dec, (ew, eb, dw, db) = make_ae(B, w.ae_channels)
+    ctx = B.Context(n, k, K)
+    u = np.zeros((K, n), np.float32); v = np.zeros((K, n), np.float32)
+    du, dv = dev(u), dev(v)
+    vals = torch.zeros((K, k), device="cuda")
+    idx = torch.zeros(k, device="cuda", dtype=torch.int32)
+    lat_len = B.lgc_latent_len(ae, k)
+    lat = torch.zeros((K, lat_len), device="cuda")
+    avg = torch.zeros((1, lat_len), device="cuda")
+    rec = torch.zeros((1, k), device="cuda")
+    for t in range(4):
+        g = synth.gradients(w, t, device="cpu").numpy()
+        dg = dev(g)
+        L = (t * 3 + 1) % K                                   # the selecting node of this iteration
+        B.lgc_accumulate_topk(ctx, dg[L], du[L], dv[L], w.momentum, k, vals[L], idx)
+        for lo, hi in ((0, L), (L + 1, K)):
+            if hi > lo:
+                B.lgc_accumulate_gather(ctx, dg[lo:hi], du[lo:hi], dv[lo:hi], w.momentum, idx, vals[lo:hi])
+        B.lgc_encode(ctx, ae, vals, lat)
+        B.lgc_average(ctx, lat, 1.0 / K, avg[0])
+        B.lgc_decode(ctx, ae, avg, rec)
+        dense = torch.zeros(n, device="cuda")
+        B.lgc_scatter(ctx, rec, idx.view(1, k), 1.0, dense)
+        assert B.lgc_stats(ctx)[2] == 0
+        # oracle
+        for b in range(K):
+            oracle.accumulate(g[b], u[b], v[b], w.momentum)
+        ovals = np.zeros((K, k), np.float32)
+        ovals[L], oidx = oracle.topk(v[L], u[L], k)
+        for b in range(K):
+            if b != L:
+                ovals[b] = oracle.gather(v[b], u[b], oidx)
+        assert (idx.cpu().numpy().astype(np.uint32) == oidx).all()
+        assert same_bits(vals, ovals) and same_bits(dv, v) and same_bits(du, u)
+        olat = np.stack([oracle.encode(ovals[b], enc, ew, eb).ravel() for b in range(K)])
+        for b in range(K):
+            assert rel_l2(lat[b], olat[b]) <= REL_L2_TOL
+        lat_h = lat.cpu().numpy()
+        assert same_bits(avg[0], oracle.average(lat_h, 1.0 / K))              # exact on the same input
+        oavg = oracle.average(olat, 1.0 / K)
+        orec = oracle.decode(oavg.reshape(w.ae_channels[-1], -1), k, enc, dec, dw, db)
+        assert rel_l2(rec[0], orec) <= 2 * REL_L2_TOL
+        ref = np.zeros(n, np.float32)
+        oracle.scatter(rec[0].cpu().numpy(), oidx, 1.0, ref)
+        assert same_bits(dense, ref)
+    ctx.close(); ae.close()
