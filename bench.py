@@ -38,13 +38,16 @@ def parse():
     p.add_argument("--pattern", choices=["ps", "rar"], default="ps",
                    help="ps: every node selects (default, the headline); rar: ring-allreduce pattern, one "
                         "rotating node selects and the others take the values at its positions (Alg. 2)")
+    p.add_argument("--selection", choices=["flat", "layers"], default="flat",
+                   help="flat: one top-k over the whole vector (default, the headline); layers: per-layer "
+                        "top-k over the workload's layers, mu_l = max(1, floor(ratio n_l)) (Sec. V-A)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-kernel-events", action="store_true",
                    help="do not bracket the streaming kernel with HIP events (roofline.achieved = null)")
     return p.parse_args()
 
 
-def cpu_baseline(w, k, enc, dec, host_w, g_host, momentum):
+def cpu_baseline(w, k, enc, dec, host_w, g_host, momentum, plan=None):
     """The oracle, as it stands, on one iteration of the same workload: accumulate + top-k +
     encode + decode + scatter for every node, nodes on separate threads (the only parallelism
     that cannot change its results)."""
@@ -58,7 +61,7 @@ def cpu_baseline(w, k, enc, dec, host_w, g_host, momentum):
         u = np.zeros(n, np.float32)
         v = np.zeros(n, np.float32)
         oracle.accumulate(g_host[b], u, v, momentum)
-        vals, idx = oracle.topk(v, u, k)
+        vals, idx = oracle.topk(v, u, k) if plan is None else oracle.topk_segmented(v, u, plan[0], plan[1])
         lat = oracle.encode(vals, enc, ew, eb)
         rec = oracle.decode(lat, k, enc, dec, dw, db)
         return rec, idx
@@ -96,6 +99,12 @@ def main():
     w = synth.workload(args.workload)
     K, n = w.nodes, w.n
     k = w.ks[args.ratio_index]
+    seg = None
+    if args.selection == "layers":
+        assert w.kind == "laplace_segments" and args.pattern == "ps", "--selection layers: workloads 2-4, pattern ps"
+        seg_off, seg_ks = synth.layer_plan(w, w.ratios[args.ratio_index])
+        seg = B.Segments(seg_off, seg_ks)
+        k = seg.total_k
     sets = args.grad_sets or w.iters
     enc, dec = synth.mirrored_ae(w.ae_channels)
     ew, eb, dw, db = synth.ae_weights(enc, dec, device="cuda")
@@ -111,8 +120,14 @@ def main():
     rec = torch.zeros((K, k), device="cuda")
     dense = torch.zeros(n, device="cuda")
 
+    def select(t):
+        if seg is None:
+            B.lgc_accumulate_topk(ctx, grads[t % sets], u, v, w.momentum, k, vals, idx)
+        else:
+            B.lgc_accumulate_topk_segmented(ctx, seg, grads[t % sets], u, v, w.momentum, vals, idx)
+
     def step_ps(t):
-        B.lgc_accumulate_topk(ctx, grads[t % sets], u, v, w.momentum, k, vals, idx)
+        select(t)
         B.lgc_encode(ctx, ae, vals, lat)
         B.lgc_decode(ctx, ae, lat, rec)
         B.lgc_scatter(ctx, rec, idx, 1.0 / K, dense)
@@ -163,10 +178,11 @@ def main():
         torch.cuda.synchronize()
         return ev0.elapsed_time(ev1) / args.steps
 
-    fused_ms = timed(lambda t: B.lgc_accumulate_topk(ctx, grads[t % sets], u, v, w.momentum, k, vals, idx))
+    fused_ms = timed(select)
     stages = {
         "a1_accumulate": timed(lambda t: B.lgc_accumulate(ctx, grads[t % sets], u, v, w.momentum)),
-        "a2_topk": timed(lambda t: B.lgc_topk(ctx, v, u, k, vals, idx)),
+        "a2_topk": timed((lambda t: B.lgc_topk(ctx, v, u, k, vals, idx)) if seg is None else
+                         (lambda t: B.lgc_topk_segmented(ctx, seg, v, u, vals, idx))),
         "a1a2_fused": fused_ms,
         "a3_encode": timed(lambda t: B.lgc_encode(ctx, ae, vals, lat)),
         "a4_decode": timed(lambda t: B.lgc_decode(ctx, ae, lat, rec)),
@@ -174,7 +190,7 @@ def main():
     }
     B.lgc_stats(ctx)
     roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
-                "traffic": MEASURED_TRAFFIC.get(w.cfg) if args.ratio_index in (-1, len(w.ks) - 1) else None, "kernel": "lgc::k_candidates<true, true> (fused accumulate + candidate bitmap, all nodes in one launch)",
+                "traffic": MEASURED_TRAFFIC.get(w.cfg) if args.ratio_index in (-1, len(w.ks) - 1) and seg is None else None, "kernel": f"lgc::k_candidates<true, true, {'false' if seg is None else 'true'}> (fused accumulate + candidate bitmap, all nodes in one launch)",
                 "algorithmic_bytes_per_launch": ALGO_BYTES_PER_ELEM * K * n}
     if kern_launches:
         # ps: one streaming launch per step covers all K nodes; rar: the selecting node's launch and
@@ -184,7 +200,7 @@ def main():
         roofline.update(achieved=ach, frac=ach / HBM_PEAK_GBS, kernel_avg_ms=kern_ms / kern_launches,
                         launches=kern_launches)
         if args.pattern == "rar":
-            roofline.update(kernel="lgc::k_candidates<true, true> (selecting node) + lgc::k_accumulate<true> "
+            roofline.update(kernel="lgc::k_candidates<true, true, false> (selecting node) + lgc::k_accumulate<true> "
                                    "(other nodes): the streaming launches of one step", traffic=None)
 
     out = {
@@ -195,7 +211,10 @@ def main():
         "config": {"workload": f"config {w.cfg} ({w.name}-sized): {K} nodes x {n} fp32 elements, k={k}/node, "
                                f"momentum {w.momentum}, autoencoder {'->'.join(map(str, w.ae_channels))}, "
                                f"{sets} gradient sets resident in HBM",
-                   "step": "accumulate+top-k (fused, all nodes in one call) + encode + decode + scatter"
+                   "step": ("accumulate+top-k (fused, all nodes in one call) + encode + decode + scatter"
+                            if seg is None else
+                            f"accumulate + per-layer top-k over {len(seg_ks)} layers (fused, all nodes in one call) "
+                            "+ encode + decode + scatter")
                            if args.pattern == "ps" else
                            "ring-allreduce pattern: accumulate+top-k on the selecting node, accumulate+gather at "
                            "its positions on the others, encode (all), average, decode (once), scatter (once)"},
@@ -211,7 +230,8 @@ def main():
 
     if not args.no_cpu_baseline:
         host_w = [[t.cpu().numpy() for t in xs] for xs in (ew, eb, dw, db)]
-        out["cpu_baseline"] = cpu_baseline(w, k, enc, dec, host_w, grads[0].cpu().numpy(), w.momentum)
+        out["cpu_baseline"] = cpu_baseline(w, k, enc, dec, host_w, grads[0].cpu().numpy(), w.momentum,
+                                           None if seg is None else (seg_off, seg_ks))
     print(json.dumps(out))
 
 

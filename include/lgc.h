@@ -147,6 +147,45 @@ lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, uint6
 lgc_status lgc_scatter(lgc_ctx *ctx, const float *vals, const uint32_t *idx, uint64_t k, int batch,
                        float scale, float *dense, uint64_t n, void *stream);
 
+/* ---- per-layer selection (Sec. V-A; layer loop of Alg. 1 / Alg. 2) ---- */
+
+/*
+ * The paper selects per layer: the flat vector is the concatenation of the
+ * layers' gradients, layer l keeps its own mu_l = alpha/100 * n_l largest
+ * magnitudes, and the kept values of all layers are concatenated in layer
+ * order.  A segment plan describes the layers once (the model does not change
+ * between iterations):
+ *   offsets: HOST array [n_seg + 1], offsets[0] = 0 < ... < offsets[n_seg] = n
+ *            (segment l is [offsets[l], offsets[l+1]), none empty)
+ *   ks:      HOST array [n_seg], ks[l] <= n_l values kept in segment l (0 allowed)
+ * Both are read during the call only.  The plan lives on `device`.
+ */
+typedef struct lgc_segments lgc_segments;
+lgc_status lgc_segments_create(lgc_segments **out, int device, uint64_t n, uint64_t n_seg,
+                               const uint64_t *offsets, const uint64_t *ks);
+void lgc_segments_destroy(lgc_segments *seg);
+uint64_t lgc_segments_total_k(const lgc_segments *seg); /* sum of ks: outputs per node */
+
+/*
+ * Per-layer exact top-k with residual update.  Every segment is selected
+ * exactly like the flat vector in lgc_topk (same key, same tie rule, exactly
+ * ks[l] positions).  Outputs per node b, K = lgc_segments_total_k(seg):
+ *   out_idx [b*K ..)  positions in the flat numbering: segment 0's (ascending),
+ *                     then segment 1's, ... — ascending overall
+ *   out_vals[b*K ..)  v at those positions, bit-exact
+ * then v <- +0 and (unless u is NULL) u <- +0 there.  n is the plan's n; it and
+ * K must fit the context (max_n, max_k).  The first call with a plan grows the
+ * context's scratch (device allocation); later calls allocate nothing.
+ */
+lgc_status lgc_topk_segmented(lgc_ctx *ctx, const lgc_segments *seg, float *v, float *u /* nullable */,
+                              int batch, uint64_t stride, float *out_vals, uint32_t *out_idx, void *stream);
+
+/* lgc_accumulate followed by lgc_topk_segmented, in one pass over g, u, v;
+ * bit-identical to that pair. */
+lgc_status lgc_accumulate_topk_segmented(lgc_ctx *ctx, const lgc_segments *seg, const float *g, float *u,
+                                         float *v, int batch, uint64_t stride, float momentum,
+                                         float *out_vals, uint32_t *out_idx, void *stream);
+
 /* ---- ring-allreduce pattern (Sec. V-A, Sec. V-C, Alg. 2) ---- */
 
 /*

@@ -25,6 +25,8 @@ EXPORTS = [
     "lgc_ae_create", "lgc_ae_destroy", "lgc_latent_len", "lgc_encode", "lgc_decode",
     "lgc_scatter", "lgc_set_option", "lgc_stats", "lgc_profile_read",
     "lgc_gather", "lgc_accumulate_gather", "lgc_average",
+    "lgc_segments_create", "lgc_segments_destroy", "lgc_segments_total_k",
+    "lgc_topk_segmented", "lgc_accumulate_topk_segmented",
 ]
 
 
@@ -84,6 +86,16 @@ def lib() -> C.CDLL:
     l.lgc_accumulate_gather.restype = i32
     l.lgc_average.argtypes = [vp, vp, u64, i32, f32, vp, vp]
     l.lgc_average.restype = i32
+    l.lgc_segments_create.argtypes = [C.POINTER(vp), i32, u64, u64, C.POINTER(u64), C.POINTER(u64)]
+    l.lgc_segments_create.restype = i32
+    l.lgc_segments_destroy.argtypes = [vp]
+    l.lgc_segments_destroy.restype = None
+    l.lgc_segments_total_k.argtypes = [vp]
+    l.lgc_segments_total_k.restype = u64
+    l.lgc_topk_segmented.argtypes = [vp, vp, vp, vp, i32, u64, vp, vp, vp]
+    l.lgc_topk_segmented.restype = i32
+    l.lgc_accumulate_topk_segmented.argtypes = [vp, vp, vp, vp, vp, i32, u64, f32, vp, vp, vp]
+    l.lgc_accumulate_topk_segmented.restype = i32
     l.lgc_set_option.argtypes = [vp, i32, C.c_int64]
     l.lgc_set_option.restype = i32
     l.lgc_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]
@@ -174,6 +186,31 @@ class Autoencoder:
             pass
 
 
+class Segments:
+    """lgc_segments*: the layers of the flat vector (offsets [n_seg+1]) and the values kept per layer."""
+
+    def __init__(self, offsets: Sequence[int], ks: Sequence[int], device: int = 0):
+        n_seg = len(ks)
+        assert len(offsets) == n_seg + 1
+        off = (C.c_uint64 * (n_seg + 1))(*[int(x) for x in offsets])
+        kk = (C.c_uint64 * n_seg)(*[int(x) for x in ks])
+        self.h = C.c_void_p()
+        _check(lib().lgc_segments_create(C.byref(self.h), device, int(offsets[-1]), n_seg, off, kk), None)
+        self.n = int(offsets[-1])
+        self.total_k = int(lib().lgc_segments_total_k(self.h))
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().lgc_segments_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 # ---------------------------------------------------------------------------- entry points
 
 def lgc_accumulate(ctx: Context, g: torch.Tensor, u: torch.Tensor, v: torch.Tensor, momentum: float) -> None:
@@ -231,6 +268,28 @@ def lgc_scatter(ctx: Context, vals: torch.Tensor, idx: torch.Tensor, scale: floa
     batch, k = (1, vals.shape[0]) if vals.dim() == 1 else vals.shape
     _check(lib().lgc_scatter(ctx.h, _ptr(vals, torch.float32), _ptr(idx, torch.int32), k, batch, scale,
                              _ptr(dense, torch.float32), dense.numel(), _stream()), ctx.h)
+
+
+def lgc_topk_segmented(ctx: Context, seg: Segments, v: torch.Tensor, u: Optional[torch.Tensor],
+                       out_vals: torch.Tensor, out_idx: torch.Tensor) -> None:
+    n, batch, stride = _layout(v)
+    assert n == seg.n and (u is None or _layout(u) == (n, batch, stride))
+    assert out_vals.is_contiguous() and out_idx.is_contiguous()
+    assert out_vals.numel() == out_idx.numel() == batch * seg.total_k
+    _check(lib().lgc_topk_segmented(ctx.h, seg.h, _ptr(v, torch.float32), _ptr(u, torch.float32), batch, stride,
+                                    _ptr(out_vals, torch.float32), _ptr(out_idx, torch.int32), _stream()), ctx.h)
+
+
+def lgc_accumulate_topk_segmented(ctx: Context, seg: Segments, g: torch.Tensor, u: torch.Tensor, v: torch.Tensor,
+                                  momentum: float, out_vals: torch.Tensor, out_idx: torch.Tensor) -> None:
+    n, batch, stride = _layout(v)
+    assert n == seg.n and _layout(g) == _layout(u) == (n, batch, stride)
+    assert out_vals.is_contiguous() and out_idx.is_contiguous()
+    assert out_vals.numel() == out_idx.numel() == batch * seg.total_k
+    _check(lib().lgc_accumulate_topk_segmented(ctx.h, seg.h, _ptr(g, torch.float32), _ptr(u, torch.float32),
+                                               _ptr(v, torch.float32), batch, stride, momentum,
+                                               _ptr(out_vals, torch.float32), _ptr(out_idx, torch.int32),
+                                               _stream()), ctx.h)
 
 
 def lgc_gather(ctx: Context, v: torch.Tensor, u: Optional[torch.Tensor], idx: torch.Tensor,

@@ -9,8 +9,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblgc.so")
-SOURCES = ["api.hip", "topk.hip", "autoencoder.hip"]
-HEADERS = [os.path.join(CSRC, "lgc_internal.h"),
+SOURCES = ["api.hip", "topk.hip", "segmented.hip", "autoencoder.hip"]
+HEADERS = [os.path.join(CSRC, "lgc_internal.h"), os.path.join(CSRC, "device_helpers.h"),
            os.path.join(os.path.dirname(HERE), "include", "lgc.h")]
 
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",

@@ -32,10 +32,21 @@ struct lgc_ctx {
     uint32_t *cand_idx = nullptr, *cand_val = nullptr;
     float *act[2] = {nullptr, nullptr};  // autoencoder activations (ping-pong), grown on demand
     size_t act_floats = 0;
+    // per-layer selection: thresholds [max_batch][n_seg] and a candidate list of its own, grown on demand
+    uint32_t *seg_t = nullptr, *seg_cand = nullptr, *seg_row_prefix = nullptr;
+    size_t seg_t_words = 0, seg_cand_words = 0;
     int opt_path = 0, opt_profile = 0;
     std::vector<hipEvent_t> ev;  // pairs: start, stop
     size_t ev_used = 0;
     char err[256] = {0};
+};
+
+struct lgc_segments {
+    int device = 0;
+    uint64_t n = 0, total_k = 0;
+    uint32_t n_seg = 0, n_sampled = 0, rows = 0, cap = 0;
+    uint32_t *dev = nullptr;  // one device allocation holding the five arrays below
+    uint32_t *off = nullptr, *k = nullptr, *out = nullptr, *rank = nullptr, *row_seg = nullptr;
 };
 
 struct lgc_ae {
@@ -299,6 +310,9 @@ extern "C" void lgc_destroy(lgc_ctx *ctx) {
     (void)hipDeviceSynchronize();
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     if (ctx->act[0]) (void)hipFree(ctx->act[0]);
+    if (ctx->seg_t) (void)hipFree(ctx->seg_t);
+    if (ctx->seg_cand) (void)hipFree(ctx->seg_cand);
+    if (ctx->seg_row_prefix) (void)hipFree(ctx->seg_row_prefix);
     if (ctx->scratch) (void)hipFree(ctx->scratch);
     delete ctx;
 }
@@ -587,6 +601,176 @@ extern "C" lgc_status lgc_scatter(lgc_ctx *ctx, const float *vals, const uint32_
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
     return LGC_OK;
+}
+
+// ------------------------------------------------------------------ per-layer selection
+
+constexpr uint32_t kSegSampleKeys = 16384;   // keys sampled per sampled segment (1024 threads x 16)
+constexpr uint64_t kSegMinSampled = 16384;   // smaller segments are selected from v directly
+
+extern "C" lgc_status lgc_segments_create(lgc_segments **out, int device, uint64_t n, uint64_t n_seg,
+                                          const uint64_t *offsets, const uint64_t *ks) {
+    if (!out) return fail(nullptr, LGC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!offsets || !ks) return fail(nullptr, LGC_EINVAL, "offsets and ks must not be NULL");
+    if (n == 0 || n >= (1ull << 31)) return fail(nullptr, LGC_EINVAL, "n must be in [1, 2^31)");
+    if (n_seg == 0 || n_seg > (1ull << 20) || n_seg > n) return fail(nullptr, LGC_EINVAL, "n_seg must be in [1, min(n, 2^20)]");
+    if (offsets[0] != 0 || offsets[n_seg] != n) return fail(nullptr, LGC_EINVAL, "offsets must start at 0 and end at n");
+    int ndev = 0;
+    HIP_TRY(nullptr, hipGetDeviceCount(&ndev));
+    if (device < 0 || device >= ndev) return fail(nullptr, LGC_EINVAL, "no HIP device %d", device);
+    const uint32_t rows = (uint32_t)((n + kRow - 1) / kRow);
+    std::vector<uint32_t> h_off(n_seg + 1), h_k(n_seg), h_out(n_seg + 1), h_rank(n_seg), h_row(rows);
+    uint64_t total = 0;
+    double expected = 0.0;
+    uint32_t n_sampled = 0;
+    for (uint64_t l = 0; l < n_seg; ++l) {
+        if (offsets[l + 1] <= offsets[l]) return fail(nullptr, LGC_EINVAL, "segment %llu is empty or offsets descend", (unsigned long long)l);
+        const uint64_t len = offsets[l + 1] - offsets[l];
+        if (ks[l] > len) return fail(nullptr, LGC_EINVAL, "ks[%llu] exceeds the segment's length", (unsigned long long)l);
+        h_off[l] = (uint32_t)offsets[l]; h_k[l] = (uint32_t)ks[l]; h_out[l] = (uint32_t)total;
+        total += ks[l];
+        // sampled: the candidate threshold is the rank-th largest of S sampled keys, S about n_l / 64
+        // (whole 128-byte lines of 32 elements, at most 16 K keys), with six standard deviations of
+        // head-room above the expected rank of the k-th key (see choose_rank)
+        h_rank[l] = 0;
+        if (len >= kSegMinSampled && ks[l] > 0) {
+            uint64_t samples = (len / 64 + 31) / 32 * 32;
+            if (samples < 2048) samples = 2048;
+            if (samples > kSegSampleKeys) samples = kSegSampleKeys;
+            const double rk = (double)ks[l] * (double)samples / (double)len;
+            const double r = ceil(rk + 6.0 * sqrt(rk) + 8.0);
+            if (r <= (double)samples / 4) {
+                h_rank[l] = (uint32_t)r | ((uint32_t)(samples / 16) << 16);
+                expected += (double)len * r / (double)samples;
+                ++n_sampled;
+            }
+        }
+    }
+    h_off[n_seg] = (uint32_t)n; h_out[n_seg] = (uint32_t)total;
+    if (total >= (1ull << 31)) return fail(nullptr, LGC_EINVAL, "sum of ks too large");
+    {
+        uint64_t l = 0;
+        for (uint32_t r = 0; r < rows; ++r) {
+            const uint64_t first = (uint64_t)r * kRow, end = first + kRow < n ? first + kRow : n;
+            while (offsets[l + 1] <= first) ++l;
+            h_row[r] = (uint32_t)l | (offsets[l + 1] < end ? 0x80000000u : 0u);
+        }
+    }
+    DeviceGuard guard(device);
+    if (!guard.ok) return fail(nullptr, LGC_EHIP, "cannot select device %d", device);
+    lgc_segments *sg = new (std::nothrow) lgc_segments;
+    if (!sg) return fail(nullptr, LGC_ENOMEM, "out of host memory");
+    sg->device = device; sg->n = n; sg->total_k = total; sg->n_seg = (uint32_t)n_seg; sg->n_sampled = n_sampled;
+    sg->rows = rows;
+    double cap = 1.5 * expected + 16384.0;
+    if (cap > 2.0e9) cap = 2.0e9;
+    sg->cap = (uint32_t)align_up((size_t)cap, 4);
+    const size_t words = (n_seg + 1) + n_seg + (n_seg + 1) + n_seg + rows;
+    hipError_t e = hipMalloc((void **)&sg->dev, words * 4);
+    if (e != hipSuccess) { delete sg; return fail(nullptr, LGC_ENOMEM, "hipMalloc of the segment plan: %s", hipGetErrorString(e)); }
+    uint32_t *p = sg->dev;
+    auto put = [&](uint32_t *&dst, const std::vector<uint32_t> &src) {
+        dst = p;
+        if (e == hipSuccess) e = hipMemcpy(p, src.data(), src.size() * 4, hipMemcpyHostToDevice);
+        p += src.size();
+    };
+    put(sg->off, h_off); put(sg->k, h_k); put(sg->out, h_out); put(sg->rank, h_rank); put(sg->row_seg, h_row);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipFree(sg->dev);
+        delete sg;
+        return fail(nullptr, LGC_EHIP, "copying the segment plan: %s", hipGetErrorString(e));
+    }
+    *out = sg;
+    return LGC_OK;
+}
+
+extern "C" void lgc_segments_destroy(lgc_segments *seg) {
+    if (!seg) return;
+    DeviceGuard guard(seg->device);
+    (void)hipDeviceSynchronize();
+    if (seg->dev) (void)hipFree(seg->dev);
+    delete seg;
+}
+
+extern "C" uint64_t lgc_segments_total_k(const lgc_segments *seg) { return seg ? seg->total_k : 0; }
+
+static lgc_status ensure_seg_scratch(lgc_ctx *ctx, const lgc_segments *seg) {
+    const size_t t_words = (size_t)ctx->max_batch * seg->n_seg;
+    if (t_words > ctx->seg_t_words) {
+        if (ctx->seg_t) { HIP_TRY(ctx, hipDeviceSynchronize()); HIP_TRY(ctx, hipFree(ctx->seg_t)); ctx->seg_t = nullptr; ctx->seg_t_words = 0; }
+        HIP_TRY(ctx, hipMalloc((void **)&ctx->seg_t, t_words * 4));
+        ctx->seg_t_words = t_words;
+    }
+    if (!ctx->seg_row_prefix)
+        HIP_TRY(ctx, hipMalloc((void **)&ctx->seg_row_prefix, (size_t)ctx->max_batch * ctx->rows * 4));
+    const size_t c_words = 2 * (size_t)ctx->max_batch * seg->cap;
+    if (c_words > ctx->seg_cand_words) {
+        if (ctx->seg_cand) { HIP_TRY(ctx, hipDeviceSynchronize()); HIP_TRY(ctx, hipFree(ctx->seg_cand)); ctx->seg_cand = nullptr; ctx->seg_cand_words = 0; }
+        HIP_TRY(ctx, hipMalloc((void **)&ctx->seg_cand, c_words * 4));
+        ctx->seg_cand_words = c_words;
+    }
+    return LGC_OK;
+}
+
+static lgc_status run_segmented(lgc_ctx *ctx, const lgc_segments *seg, const float *g, float *u, float *v, int batch,
+                                uint64_t stride, float m, float *out_vals, uint32_t *out_idx, void *stream) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    if (!seg) return fail(ctx, LGC_EINVAL, "segments is NULL");
+    if (seg->device != ctx->device) return fail(ctx, LGC_EINVAL, "segment plan and context live on different devices");
+    lgc_status s = check_common(ctx, seg->n, batch, stride);
+    if (s != LGC_OK) return s;
+    if (!v || (g && !u)) return fail(ctx, LGC_EINVAL, "v (and, with g, u) must not be NULL");
+    if (!aligned(g, 4) || !aligned(u, 4) || !aligned(v, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    if ((s = check_select(ctx, seg->n, seg->total_k, out_vals, out_idx)) != LGC_OK) return s;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    hipStream_t st = (hipStream_t)stream;
+    const bool fused = g != nullptr;
+    const bool vec = aligned(v, 16) && (!u || aligned(u, 16)) && (!g || aligned(g, 16)) &&
+                     (batch == 1 || stride % 4 == 0);
+    if (seg->total_k == 0) {
+        if (fused) launch_accumulate(g, u, v, (uint32_t)seg->n, batch, stride, m, vec, st);
+        return LGC_OK;
+    }
+    if ((s = ensure_seg_scratch(ctx, seg)) != LGC_OK) return s;
+    SelArgs a = make_args(ctx, g, u, v, seg->n, stride, m, seg->total_k, out_vals, out_idx);
+    a.n_seg = seg->n_seg; a.seg_off = seg->off; a.seg_k = seg->k; a.seg_out = seg->out; a.seg_rank = seg->rank;
+    a.row_seg = seg->row_seg; a.seg_t = ctx->seg_t; a.row_prefix = ctx->seg_row_prefix;
+    a.cap = seg->cap;
+    a.cand_idx = ctx->seg_cand; a.cand_val = ctx->seg_cand + (size_t)ctx->max_batch * seg->cap;
+    ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
+    if (seg->n_sampled) {
+        launch_seg_estimate(a, batch, fused, vec, st);   // also clears the next call's state set
+        profile_begin(ctx, st);
+        launch_candidates(a, batch, fused, vec, st);
+        profile_end(ctx, st);
+        launch_gather(a, batch, st);
+    } else {
+        launch_clear(a.next_state, a.next_words, st);
+        if (fused) {
+            profile_begin(ctx, st);
+            launch_accumulate(g, u, v, (uint32_t)seg->n, batch, stride, m, vec, st);
+            profile_end(ctx, st);
+        }
+    }
+    launch_seg_select(a, batch, vec, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return LGC_OK;
+}
+
+extern "C" lgc_status lgc_topk_segmented(lgc_ctx *ctx, const lgc_segments *seg, float *v, float *u, int batch,
+                                         uint64_t stride, float *out_vals, uint32_t *out_idx, void *stream) {
+    return run_segmented(ctx, seg, nullptr, u, v, batch, stride, 0.f, out_vals, out_idx, stream);
+}
+
+extern "C" lgc_status lgc_accumulate_topk_segmented(lgc_ctx *ctx, const lgc_segments *seg, const float *g, float *u,
+                                                    float *v, int batch, uint64_t stride, float momentum,
+                                                    float *out_vals, uint32_t *out_idx, void *stream) {
+    if (ctx && !g) return fail(ctx, LGC_EINVAL, "g must not be NULL");
+    return run_segmented(ctx, seg, g, u, v, batch, stride, momentum, out_vals, out_idx, stream);
 }
 
 // ------------------------------------------------------------------ ring-allreduce pattern

@@ -96,6 +96,16 @@ struct SelArgs {
     uint32_t *cand_val;
     float *out_vals;          // [batch][k]
     uint32_t *out_idx;        // [batch][k]
+    // per-layer selection (null / 0 otherwise): the segment plan and the per-call thresholds
+    uint32_t n_seg;
+    const uint32_t *seg_off;  // [n_seg + 1] first element of every segment, then n
+    const uint32_t *seg_k;    // [n_seg]     values kept per segment
+    const uint32_t *seg_out;  // [n_seg + 1] first output slot of every segment (prefix sums of seg_k)
+    const uint32_t *seg_rank; // [n_seg]     0 = not sampled; else rank of the sample's order statistic (low 16
+                              //             bits) and the number of sampling threads (high 16 bits)
+    const uint32_t *row_seg;  // [rows]      segment of the row's first element | bit 31: crosses a boundary
+    uint32_t *seg_t;          // [batch][n_seg] candidate thresholds of this call
+    uint32_t *row_prefix;     // [batch][rows]  candidates listed before each row (written by the gather kernel)
 };
 
 // launchers (topk.hip) — all asynchronous on `st`
@@ -107,6 +117,9 @@ void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStr
 void launch_gather(const SelArgs &a, int batch, hipStream_t st);
 void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hipStream_t st);
 void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st);
+// per-layer selection (segmented.hip)
+void launch_seg_estimate(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
+void launch_seg_select(const SelArgs &a, int batch, bool vec, hipStream_t st);
 
 // autoencoder.hip
 struct LayerDev {

@@ -21,77 +21,11 @@
 //  chain over 4096-element chunks; chunk ids are handed out by an atomic ticket, so a chunk
 //  only ever waits for chunks that already run.
 
-#include "lgc_internal.h"
+#include "device_helpers.h"
 
 namespace lgc {
 
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-
 enum { SRC_FUSED = 0, SRC_PLAIN = 1, SRC_CAND = 2 };
-
-// ------------------------------------------------------------------ small helpers
-
-__device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7fffffffu; }
-
-__device__ __forceinline__ uint32_t lanes_below(unsigned long long m) {
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-}
-
-__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
-    return x;
-}
-
-__device__ __forceinline__ unsigned long long ld_agent(const unsigned long long *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_agent(unsigned long long *p, unsigned long long x) {
-    __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint32_t ld_agent32(const uint32_t *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// accumulation step: three separately rounded fp32 operations, never contracted
-__device__ __forceinline__ void accum1(float g, float &u, float &v, float m) {
-    u = __fadd_rn(__fmul_rn(m, u), g);
-    v = __fadd_rn(v, u);
-}
-
-// Block-wide search in a histogram held in LDS: finds the bin b such that
-// count(bins > b) < rank <= count(bins >= b).  Every thread owns NB/blockDim.x consecutive bins.
-// Result through LDS: res[0] = b (or 0xffffffff if the histogram holds fewer than rank), res[1] =
-// count(bins > b).  All threads must call; contains barriers.
-template <int NB>
-__device__ void find_rank_bin(const uint32_t *hist, uint32_t rank, uint32_t *wave_tmp, uint32_t *res) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
-    const int per = NB / blockDim.x;
-    uint32_t part = 0;
-    for (int i = 0; i < per; ++i) part += hist[tid * per + i];
-    // inclusive suffix sum inside the wave
-    uint32_t incl = part;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        uint32_t y = __shfl_down(incl, d, 64);
-        if (lane + d < 64) incl += y;
-    }
-    if (tid == 0) { res[0] = 0xffffffffu; res[1] = 0; }
-    if (lane == 0) wave_tmp[wave] = incl;
-    __syncthreads();
-    uint32_t above = incl - part;
-    for (int w = wave + 1; w < nw; ++w) above += wave_tmp[w];
-    if (above < rank && rank <= above + part) {
-        uint32_t acc = above;
-        for (int i = per - 1; i >= 0; --i) {
-            uint32_t h = hist[tid * per + i];
-            if (acc + h >= rank) { res[0] = tid * per + i; res[1] = acc; break; }
-            acc += h;
-        }
-    }
-    __syncthreads();
-}
 
 // ------------------------------------------------------------------ plain accumulation
 
@@ -276,14 +210,18 @@ __device__ __forceinline__ void full_row(const float *__restrict__ g, float *__r
 // One wavefront per row of 1024 elements.  The flags "key >= t_est" of the row go out as one
 // full 128-byte line of the candidate bitmap (dense, coalesced: no partial-line writes), the
 // row's candidate count as one word.  No barrier, no LDS, no atomics, nothing shared.
-template <bool FUSED, bool VEC>
+// SEG: per-layer selection; the threshold of an element is that of its segment (a.seg_t, one per
+// node and segment; 0xffffffff flags nothing).  a.row_seg names the segment of a row's first
+// element, with bit 31 set when the row runs into further segments.
+template <bool FUSED, bool VEC, bool SEG>
 __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
     const int node = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t off = (size_t)node * a.stride;
     const float *__restrict__ g = a.g + off;
     float *__restrict__ u = a.u + off;
     float *__restrict__ v = a.v + off;
-    const uint32_t t_est = a.sel[node].t_est;
+    const uint32_t t_est = SEG ? 0u : a.sel[node].t_est;
+    const uint32_t *seg_t = SEG ? a.seg_t + (size_t)node * a.n_seg : nullptr;
     const float m = a.momentum;
     const uint32_t nrows = (a.n + kRow - 1) / kRow;
     unsigned long long *bitmap = a.bitmap + (size_t)node * a.rows * kRowWords;
@@ -292,6 +230,26 @@ __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
         const uint32_t row = r * (uint32_t)kRow;
         const uint32_t end = (a.n - row > (uint32_t)kRow) ? row + kRow : a.n;
         uint32_t bits[4][4];
+        uint32_t thr[4][4];
+        if (SEG) {
+            const uint32_t rs = a.row_seg[r];
+            uint32_t l = rs & 0x7fffffffu;
+            const uint32_t t0 = seg_t[l];
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) thr[s][j] = t0;
+            if (rs >> 31) {   // wave-uniform: the row crosses into the next segment(s)
+                for (++l; l < a.n_seg && a.seg_off[l] < end; ++l) {
+                    const uint32_t ol = a.seg_off[l], tl = seg_t[l];
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (row + s * 256 + lane * 4 + j >= ol) thr[s][j] = tl;
+                }
+            }
+        }
         if (VEC && row + 1024 <= end) {
             full_row<FUSED>(g + row + lane * 4, u + row + lane * 4, v + row + lane * 4, m, bits);
         } else {
@@ -331,7 +289,7 @@ __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t e = row + s * 256 + lane * 4 + j;
-                const unsigned long long mk = __ballot(e < end && (bits[s][j] & 0x7fffffffu) >= t_est);
+                const unsigned long long mk = __ballot(e < end && (bits[s][j] & 0x7fffffffu) >= (SEG ? thr[s][j] : t_est));
                 count += (uint32_t)__popcll(mk);
                 const bool mine = lane == s * 4 + j;
                 lo = mine ? (uint32_t)mk : lo;
@@ -346,16 +304,19 @@ __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
 void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st) {
     const uint32_t nrows = (a.n + kRow - 1) / kRow;
     dim3 grid((nrows + kWaves - 1) / kWaves, batch);
-    if (fused) {
-        if (vec) hipLaunchKernelGGL((k_candidates<true, true>), grid, dim3(kBlock), 0, st, a);
-        else hipLaunchKernelGGL((k_candidates<true, false>), grid, dim3(kBlock), 0, st, a);
+    const bool seg = a.seg_t != nullptr;
+#define LGC_CAND(F, V, S) hipLaunchKernelGGL((k_candidates<F, V, S>), grid, dim3(kBlock), 0, st, a)
+    if (seg) {
+        if (fused) { if (vec) LGC_CAND(true, true, true); else LGC_CAND(true, false, true); }
+        else       { if (vec) LGC_CAND(false, true, true); else LGC_CAND(false, false, true); }
     } else {
-        if (vec) hipLaunchKernelGGL((k_candidates<false, true>), grid, dim3(kBlock), 0, st, a);
-        else hipLaunchKernelGGL((k_candidates<false, false>), grid, dim3(kBlock), 0, st, a);
+        if (fused) { if (vec) LGC_CAND(true, true, false); else LGC_CAND(true, false, false); }
+        else       { if (vec) LGC_CAND(false, true, false); else LGC_CAND(false, false, false); }
     }
+#undef LGC_CAND
 }
 
-// ------------------------------------------------------------------ gather the candidates
+// ------------------------------------------------------------------ gather of the candidates
 
 __device__ __forceinline__ uint32_t block_sum_1024(uint32_t x, uint32_t *tmp /*[16]*/) {
     x = wave_sum(x);
@@ -376,8 +337,9 @@ __device__ __forceinline__ uint32_t block_sum_1024(uint32_t x, uint32_t *tmp /*[
 // then of the bit inside the row), whatever the spread of the candidates.
 constexpr int kGatherRows = 256;
 
+template <bool HIST>
 __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
-    __shared__ uint32_t hist[kFineBins];
+    __shared__ uint32_t hist[HIST ? kFineBins : 1];
     __shared__ unsigned long long rows_lds[kGatherRows * kRowWords];
     __shared__ uint32_t offs[kGatherRows];
     __shared__ uint32_t tmp[16];
@@ -399,7 +361,7 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
         const uint32_t w2 = q * 1024 + tid;   // pair of words
         bm[q] = (w2 * 2 < mine * kRowWords) ? *(const ulonglong2 *)(bitmap + (size_t)w2 * 2) : ulonglong2{0ull, 0ull};
     }
-    const uint32_t t_est = s->t_est;
+    const uint32_t t_est = HIST ? s->t_est : 0u;
     uint32_t part = 0;
     for (uint32_t i0 = tid * 4; i0 < first; i0 += 4096 * 4) {   // first and the row stride are multiples of 4
         u4 x[4];
@@ -413,7 +375,7 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
         rows_lds[(q * 1024 + tid) * 2] = bm[q].x;
         rows_lds[(q * 1024 + tid) * 2 + 1] = bm[q].y;
     }
-    for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
+    if (HIST) for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
     const uint32_t before = block_sum_1024(part, tmp);   // contains barriers: LDS is filled for all
     // exclusive scan of c over the first kGatherRows threads
     uint32_t incl = c;
@@ -429,6 +391,8 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
 #pragma unroll
     for (int w = 0; w < kGatherRows / 64; ++w) { if (w < wave) excl += tmp[w]; block_total += tmp[w]; }
     if (tid < kGatherRows) offs[tid] = excl;
+    // per-layer selection: where each row's candidates start in the list
+    if (!HIST && (uint32_t)tid < mine) a.row_prefix[(size_t)node * a.rows + first + tid] = before + excl;
     if (tid == 0 && block_total) atomicAdd(&s->cand_total, block_total);
     __syncthreads();
 
@@ -470,17 +434,24 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
         const uint32_t vb = ix < a.n ? __float_as_uint(v[ix]) : 0u;
         const uint32_t q = before + p;
         if (q < a.cap) { cidx[q] = ix; cval[q] = vb; }
-        const uint32_t d = ((vb & 0x7fffffffu) - t_est) >> kFineShift;
-        atomicAdd(&hist[d < (uint32_t)kFineBins - 1 ? d : (uint32_t)kFineBins - 1], 1u);
+        if (HIST) {
+            const uint32_t d = ((vb & 0x7fffffffu) - t_est) >> kFineShift;
+            atomicAdd(&hist[d < (uint32_t)kFineBins - 1 ? d : (uint32_t)kFineBins - 1], 1u);
+        }
     }
-    __syncthreads();
-    uint32_t *fine = a.fine_hist + node * kFineBins;
-    for (int i = tid; i < kFineBins; i += 1024) { const uint32_t h = hist[i]; if (h) atomicAdd(&fine[i], h); }
+    if (HIST) {
+        __syncthreads();
+        uint32_t *fine = a.fine_hist + node * kFineBins;
+        for (int i = tid; i < kFineBins; i += 1024) { const uint32_t h = hist[i]; if (h) atomicAdd(&fine[i], h); }
+    }
 }
 
 void launch_gather(const SelArgs &a, int batch, hipStream_t st) {
     const uint32_t nrows = (a.n + kRow - 1) / kRow;
-    hipLaunchKernelGGL(k_gather, dim3((nrows + kGatherRows - 1) / kGatherRows, batch), dim3(1024), 0, st, a);
+    const dim3 grid((nrows + kGatherRows - 1) / kGatherRows, batch);
+    // the per-layer selection has one threshold per segment, so no histogram above "the" estimate
+    if (a.seg_t) hipLaunchKernelGGL(k_gather<false>, grid, dim3(1024), 0, st, a);
+    else hipLaunchKernelGGL(k_gather<true>, grid, dim3(1024), 0, st, a);
 }
 
 // Adds, for every candidate i < total that passes `member`, one count to hist[digit(d)], where

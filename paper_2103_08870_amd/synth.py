@@ -117,6 +117,18 @@ def segment_layout(w: Workload) -> Tuple[torch.Tensor, torch.Tensor]:
     return sizes, torch.exp(lb)
 
 
+def layer_plan(w: Workload, ratio: Optional[float] = None) -> Tuple[List[int], List[int]]:
+    """The workload's layers as a segment plan for per-layer selection (Sec. V-A):
+    (offsets [segments + 1], ks [segments]) with mu_l = max(1, floor(ratio * n_l))."""
+    sizes, _ = segment_layout(w)
+    r = w.ratios[-1] if ratio is None else ratio
+    offsets = [0]
+    for sz in sizes.tolist():
+        offsets.append(offsets[-1] + int(sz))
+    ks = [max(1, int(math.floor(r * int(sz)))) for sz in sizes.tolist()]
+    return offsets, ks
+
+
 def _laplace(shape, scale: torch.Tensor, gen: torch.Generator, device) -> torch.Tensor:
     u = torch.rand(shape, generator=gen, device=device, dtype=torch.float32) - 0.5
     return -scale * torch.sign(u) * torch.log1p(-2.0 * u.abs().clamp(max=0.49999997))
