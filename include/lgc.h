@@ -102,7 +102,10 @@ lgc_status lgc_accumulate_topk(lgc_ctx *ctx, const float *g, float *u, float *v,
  * hold the same number of stride-2 layers).  Leaky-ReLU with `slope`
  * (0 = ReLU) follows every layer except the last of each stack.
  * enc[0].c_in = 1 and dec[n_dec-1].c_out = 1: the input is one node's vector
- * of k selected values.  dec[0].c_in = enc[n_enc-1].c_out.
+ * of k selected values.  dec[0].c_in = enc[n_enc-1].c_out.  Consecutive layers
+ * must agree in channels, except that the last decoder layer, if it has stride
+ * 1, may take one channel more than the layer before it produces: that makes
+ * the decoder of the parameter-server pattern (see lgc_decode_innovation).
  * Weights (device pointers, read and COPIED during this call, which
  * synchronises the device once):
  *   enc_w[l]: [c_out][c_in][ksize]   enc_b[l]: [c_out]
@@ -185,6 +188,35 @@ lgc_status lgc_topk_segmented(lgc_ctx *ctx, const lgc_segments *seg, float *v, f
 lgc_status lgc_accumulate_topk_segmented(lgc_ctx *ctx, const lgc_segments *seg, const float *g, float *u,
                                          float *v, int batch, uint64_t stride, float momentum,
                                          float *out_vals, uint32_t *out_idx, void *stream);
+
+/* ---- parameter-server pattern: innovation component (Alg. 1, Sec. IV-C, Sec. V-B) ---- */
+
+/*
+ * Innovation component g~^I — Alg. 1 (threshold_inv, mask_inv, g~^I = g~ .*
+ * mask_inv): a vector of the size of g~ holding the top-magnitude values of g~
+ * and +0 elsewhere.  Alg. 1 forms it inside the layer loop, so it is taken per
+ * segment of g~: `seg` is a plan over the vector of selected values (n = its
+ * length, offsets = where each layer's values start, ks = values kept per
+ * layer; one segment covering everything gives the flat form).  Key and tie
+ * rule as in lgc_topk; exactly ks[l] values are kept per segment.
+ * vals: [batch][n], not modified;  out: [batch][n], must not alias vals.
+ * One block works on one segment of one node, which suits the paper's layers;
+ * a single segment of millions of values is correct but slow.
+ */
+lgc_status lgc_innovation(lgc_ctx *ctx, const lgc_segments *seg, const float *vals, int batch, float *out,
+                          void *stream);
+
+/*
+ * Decoder of the parameter-server pattern, g^rec = D_c(g^c, g~^I) — Sec. IV-C:
+ * before the final layer the intermediate representation (length k) is
+ * concatenated with the innovation component as one more channel, appended
+ * last.  The autoencoder must have been created with a decoder whose last
+ * layer has stride 1 and c_in = (c_out of the layer before) + 1; lgc_decode
+ * rejects such an autoencoder and this call rejects any other.
+ * innov: [batch][k] (lgc_innovation's output);  rec: [batch][k].
+ */
+lgc_status lgc_decode_innovation(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, const float *innov,
+                                 uint64_t k, int batch, float *rec, void *stream);
 
 /* ---- ring-allreduce pattern (Sec. V-A, Sec. V-C, Alg. 2) ---- */
 

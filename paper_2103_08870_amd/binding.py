@@ -27,6 +27,7 @@ EXPORTS = [
     "lgc_gather", "lgc_accumulate_gather", "lgc_average",
     "lgc_segments_create", "lgc_segments_destroy", "lgc_segments_total_k",
     "lgc_topk_segmented", "lgc_accumulate_topk_segmented",
+    "lgc_innovation", "lgc_decode_innovation",
 ]
 
 
@@ -96,6 +97,10 @@ def lib() -> C.CDLL:
     l.lgc_topk_segmented.restype = i32
     l.lgc_accumulate_topk_segmented.argtypes = [vp, vp, vp, vp, vp, i32, u64, f32, vp, vp, vp]
     l.lgc_accumulate_topk_segmented.restype = i32
+    l.lgc_innovation.argtypes = [vp, vp, vp, i32, vp, vp]
+    l.lgc_innovation.restype = i32
+    l.lgc_decode_innovation.argtypes = [vp, vp, vp, vp, u64, i32, vp, vp]
+    l.lgc_decode_innovation.restype = i32
     l.lgc_set_option.argtypes = [vp, i32, C.c_int64]
     l.lgc_set_option.restype = i32
     l.lgc_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]
@@ -290,6 +295,24 @@ def lgc_accumulate_topk_segmented(ctx: Context, seg: Segments, g: torch.Tensor, 
                                                _ptr(v, torch.float32), batch, stride, momentum,
                                                _ptr(out_vals, torch.float32), _ptr(out_idx, torch.int32),
                                                _stream()), ctx.h)
+
+
+def lgc_innovation(ctx: Context, seg: Segments, vals: torch.Tensor, out: torch.Tensor) -> None:
+    """vals [batch][k] -> out [batch][k]: per segment of the plan the top-magnitude values, +0 elsewhere."""
+    assert vals.dim() == 2 and vals.is_contiguous() and out.is_contiguous() and out.shape == vals.shape
+    assert vals.shape[1] == seg.n
+    _check(lib().lgc_innovation(ctx.h, seg.h, _ptr(vals, torch.float32), vals.shape[0], _ptr(out, torch.float32),
+                                _stream()), ctx.h)
+
+
+def lgc_decode_innovation(ctx: Context, ae: Autoencoder, latent: torch.Tensor, innov: torch.Tensor,
+                          rec: torch.Tensor) -> None:
+    """latent [batch][...] and innovation component [batch][k] -> rec [batch][k]."""
+    assert rec.dim() == 2 and rec.is_contiguous() and latent.is_contiguous() and innov.is_contiguous()
+    batch, k = rec.shape
+    assert innov.shape == rec.shape and latent.numel() == batch * lgc_latent_len(ae, k)
+    _check(lib().lgc_decode_innovation(ctx.h, ae.h, _ptr(latent, torch.float32), _ptr(innov, torch.float32), k, batch,
+                                       _ptr(rec, torch.float32), _stream()), ctx.h)
 
 
 def lgc_gather(ctx: Context, v: torch.Tensor, u: Optional[torch.Tensor], idx: torch.Tensor,

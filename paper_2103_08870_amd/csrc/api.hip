@@ -52,6 +52,7 @@ struct lgc_segments {
 struct lgc_ae {
     int device = 0;
     float slope = 0.f;
+    bool innovation = false;  // the last decoder layer takes the innovation component as one more channel
     std::vector<lgc_layer> enc, dec;
     std::vector<LayerDev> enc_dev, dec_dev;
     float *weights = nullptr;  // device copy of all weights and biases
@@ -393,6 +394,7 @@ extern "C" lgc_status lgc_ae_create(lgc_ae **out, int device, int n_enc, const l
     if (n_enc < 1 || n_dec < 1 || n_enc > 64 || n_dec > 64 || !enc || !dec || !enc_w || !enc_b || !dec_w || !dec_b)
         return fail(nullptr, LGC_EINVAL, "bad autoencoder description");
     int strided_enc = 0, strided_dec = 0;
+    bool with_innovation = false;
     for (int l = 0; l < n_enc; ++l) {
         if (!layer_ok(enc[l]) || !enc_w[l] || !enc_b[l]) return fail(nullptr, LGC_EINVAL, "bad encoder layer %d", l);
         if (l > 0 && enc[l].c_in != enc[l - 1].c_out) return fail(nullptr, LGC_EINVAL, "encoder layer %d: channel mismatch", l);
@@ -400,7 +402,12 @@ extern "C" lgc_status lgc_ae_create(lgc_ae **out, int device, int n_enc, const l
     }
     for (int l = 0; l < n_dec; ++l) {
         if (!layer_ok(dec[l]) || !dec_w[l] || !dec_b[l]) return fail(nullptr, LGC_EINVAL, "bad decoder layer %d", l);
-        if (l > 0 && dec[l].c_in != dec[l - 1].c_out) return fail(nullptr, LGC_EINVAL, "decoder layer %d: channel mismatch", l);
+        if (l > 0 && dec[l].c_in != dec[l - 1].c_out) {
+            // decoder with the innovation component (Sec. IV-C): one more channel into the last, stride-1 layer
+            const bool concat = l == n_dec - 1 && dec[l].c_in == dec[l - 1].c_out + 1 && dec[l].stride == 1;
+            if (!concat) return fail(nullptr, LGC_EINVAL, "decoder layer %d: channel mismatch", l);
+            with_innovation = true;
+        }
         strided_dec += dec[l].stride == 2;
     }
     if (enc[0].c_in != 1 || dec[n_dec - 1].c_out != 1) return fail(nullptr, LGC_EINVAL, "input and output must have one channel");
@@ -414,7 +421,7 @@ extern "C" lgc_status lgc_ae_create(lgc_ae **out, int device, int n_enc, const l
 
     lgc_ae *ae = new (std::nothrow) lgc_ae;
     if (!ae) return fail(nullptr, LGC_ENOMEM, "out of host memory");
-    ae->device = device; ae->slope = slope;
+    ae->device = device; ae->slope = slope; ae->innovation = with_innovation;
     ae->enc.assign(enc, enc + n_enc);
     ae->dec.assign(dec, dec + n_dec);
     size_t total = 0;
@@ -543,10 +550,14 @@ extern "C" lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *va
     return LGC_OK;
 }
 
-extern "C" lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, uint64_t k, int batch,
-                                 float *rec, void *stream) {
+static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, const float *innov, uint64_t k,
+                             int batch, float *rec, void *stream) {
     lgc_status s = check_ae_call(ctx, ae, latent, rec, k, batch);
     if (s != LGC_OK) return s;
+    if (ae->innovation != (innov != nullptr))
+        return fail(ctx, LGC_EINVAL, ae->innovation ? "this autoencoder's decoder needs the innovation component: use lgc_decode_innovation"
+                                                     : "this autoencoder's decoder takes no innovation component: use lgc_decode");
+    if (!aligned(innov, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
     if (k == 0) return LGC_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
@@ -554,8 +565,9 @@ extern "C" lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *la
     std::vector<uint64_t> out_len = dec_lengths(ae, k);
     uint64_t in_len = enc_lengths(ae, k).back();
     const size_t nl = ae->dec.size();
-    if (nl == 2 && launch_decoder2(latent, rec, ae->dec_dev[0], ae->dec_dev[1], (uint32_t)in_len, (uint32_t)out_len[0],
-                                   (uint32_t)out_len[1], batch, ae->slope, st)) {
+    if (!innov && nl == 2 &&
+        launch_decoder2(latent, rec, ae->dec_dev[0], ae->dec_dev[1], (uint32_t)in_len, (uint32_t)out_len[0],
+                        (uint32_t)out_len[1], batch, ae->slope, st)) {
         hipError_t e2 = hipGetLastError();
         if (e2 != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e2));
         return LGC_OK;
@@ -571,10 +583,41 @@ extern "C" lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *la
         const bool last = l + 1 == nl;
         float *dst = last ? rec : ctx->act[l & 1];
         launch_conv_transpose1d(cur, dst, ae->dec_dev[l], (uint32_t)in_len, (uint32_t)out_len[l], batch, !last,
-                                ae->slope, st);
+                                ae->slope, st, last ? innov : nullptr);
         cur = dst;
         in_len = out_len[l];
     }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    return LGC_OK;
+}
+
+extern "C" lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, uint64_t k, int batch,
+                                 float *rec, void *stream) {
+    return run_decode(ctx, ae, latent, nullptr, k, batch, rec, stream);
+}
+
+extern "C" lgc_status lgc_decode_innovation(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, const float *innov,
+                                            uint64_t k, int batch, float *rec, void *stream) {
+    if (ctx && k > 0 && !innov) return fail(ctx, LGC_EINVAL, "innov must not be NULL");
+    if (ctx && ae && k == 0 && !innov && ae->innovation) return LGC_OK;
+    return run_decode(ctx, ae, latent, innov, k, batch, rec, stream);
+}
+
+extern "C" lgc_status lgc_innovation(lgc_ctx *ctx, const lgc_segments *seg, const float *vals, int batch, float *out,
+                                     void *stream) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    if (!seg) return fail(ctx, LGC_EINVAL, "segments is NULL");
+    if (seg->device != ctx->device) return fail(ctx, LGC_EINVAL, "segment plan and context live on different devices");
+    if (batch < 1 || batch > ctx->max_batch) return fail(ctx, LGC_EINVAL, "batch = %d outside [1, %d]", batch, ctx->max_batch);
+    if (!vals || !out) return fail(ctx, LGC_EINVAL, "NULL data pointer");
+    if (vals == out) return fail(ctx, LGC_EINVAL, "out must not alias vals");
+    if (!aligned(vals, 4) || !aligned(out, 4)) return fail(ctx, LGC_EINVAL, "pointer not 4-byte aligned");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    const bool vec = aligned(vals, 16) && (batch == 1 || seg->n % 4 == 0);
+    launch_innovation(vals, out, (uint32_t)seg->n, batch, seg->n_seg, seg->off, seg->k, vec, ctx->stats,
+                      (hipStream_t)stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
     return LGC_OK;

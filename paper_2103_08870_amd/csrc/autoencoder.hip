@@ -46,18 +46,22 @@ __global__ __launch_bounds__(256) void k_conv1d(const float *__restrict__ in, fl
 }
 
 // out[b][co][q] = bias[co] + sum_ci sum_{(p,t): p*stride - pad + t = q} w[ci][co][t] * in[b][ci][p]
+// With `extra` (decoder with the innovation component, Sec. IV-C): the last of the c_in input
+// channels is extra[b][:], the others are in[b][0 .. c_in-2][:].
 template <int COT, int KS>
 __global__ __launch_bounds__(256) void k_conv_transpose1d(const float *__restrict__ in, float *__restrict__ out,
                                                           const float *__restrict__ w,
                                                           const float *__restrict__ bias, int c_in, int c_out,
                                                           int stride, uint32_t l_in, uint32_t l_out, int act,
-                                                          float slope) {
+                                                          float slope, const float *__restrict__ extra) {
     const uint32_t q = blockIdx.x * 256 + threadIdx.x;
     if (q >= l_out) return;
     const int co0 = blockIdx.y * COT;
     const int b = blockIdx.z;
     constexpr int PAD = (KS - 1) / 2;
-    in += (size_t)b * c_in * l_in;
+    const int c_main = extra ? c_in - 1 : c_in;
+    in += (size_t)b * c_main * l_in;
+    if (extra) extra += (size_t)b * l_in;
     out += (size_t)b * c_out * l_out;
     float acc[COT];
 #pragma unroll
@@ -72,9 +76,10 @@ __global__ __launch_bounds__(256) void k_conv_transpose1d(const float *__restric
         src[t] = hit[t] ? (uint32_t)(num / stride) : 0u;
     }
     for (int ci = 0; ci < c_in; ++ci) {
+        const float *row = ci < c_main ? in + (size_t)ci * l_in : extra;
         float x[KS];
 #pragma unroll
-        for (int t = 0; t < KS; ++t) x[t] = hit[t] ? in[(size_t)ci * l_in + src[t]] : 0.f;
+        for (int t = 0; t < KS; ++t) x[t] = hit[t] ? row[src[t]] : 0.f;
 #pragma unroll
         for (int c = 0; c < COT; ++c) {
             if (co0 + c < c_out) {
@@ -103,15 +108,15 @@ void launch_conv1d(const float *in, float *out, const LayerDev &l, uint32_t l_in
 }
 
 void launch_conv_transpose1d(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out,
-                             int batch, bool act, float slope, hipStream_t st) {
+                             int batch, bool act, float slope, hipStream_t st, const float *extra) {
     if (l_out == 0) return;
     dim3 grid((l_out + 255) / 256, (l.c_out + kCot - 1) / kCot, batch);
     if (l.ksize == 3)
         hipLaunchKernelGGL((k_conv_transpose1d<kCot, 3>), grid, dim3(256), 0, st, in, out, l.w, l.b, l.c_in,
-                           l.c_out, l.stride, l_in, l_out, (int)act, slope);
+                           l.c_out, l.stride, l_in, l_out, (int)act, slope, extra);
     else
         hipLaunchKernelGGL((k_conv_transpose1d<kCot, 1>), grid, dim3(256), 0, st, in, out, l.w, l.b, l.c_in,
-                           l.c_out, l.stride, l_in, l_out, (int)act, slope);
+                           l.c_out, l.stride, l_in, l_out, (int)act, slope, extra);
 }
 
 // ---- two-layer stacks in one launch ------------------------------------------------------------

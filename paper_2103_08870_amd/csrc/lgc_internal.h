@@ -120,6 +120,8 @@ void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st
 // per-layer selection (segmented.hip)
 void launch_seg_estimate(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
 void launch_seg_select(const SelArgs &a, int batch, bool vec, hipStream_t st);
+void launch_innovation(const float *vals, float *out, uint32_t n, int batch, uint32_t n_seg, const uint32_t *seg_off,
+                       const uint32_t *seg_k, bool vec, Stats *stats, hipStream_t st);
 
 // autoencoder.hip
 struct LayerDev {
@@ -128,8 +130,10 @@ struct LayerDev {
 };
 void launch_conv1d(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out,
                    int batch, bool act, float slope, hipStream_t st);
+// extra (nullable): one more input channel per node, [batch][l_in], appended after the c_in - 1 channels of `in`
 void launch_conv_transpose1d(const float *in, float *out, const LayerDev &l, uint32_t l_in,
-                             uint32_t l_out, int batch, bool act, float slope, hipStream_t st);
+                             uint32_t l_out, int batch, bool act, float slope, hipStream_t st,
+                             const float *extra = nullptr);
 // whole two-layer stacks in one launch; false = shape not covered (nothing launched)
 bool launch_encoder2(const float *x, float *z, const LayerDev &a, const LayerDev &b, uint32_t l0, uint32_t l1,
                      uint32_t l2, int batch, float slope, hipStream_t st);

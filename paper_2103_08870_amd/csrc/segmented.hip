@@ -171,11 +171,14 @@ void launch_seg_estimate(const SelArgs &a, int batch, bool fused, bool vec, hipS
 // unrolled, register-cached variant was an order of magnitude slower (instruction fetch).
 constexpr int kSelThreads = 512;          // most segments and candidate runs are a few thousand entries
 
-template <bool ALIGNED>
+// DENSE: instead of the compact (position, value) output and the clearing of v and u, every entry p
+// of the source gets dense[p] = its value if kept, +0 otherwise (the innovation component).
+template <bool ALIGNED, bool DENSE>
 __device__ __forceinline__ void select_in_block(const uint32_t *__restrict__ bits, const uint32_t *__restrict__ pos,
                                                 const uint32_t begin, const uint32_t end, const uint32_t k,
                                                 float *__restrict__ v, float *__restrict__ u,
-                                                uint32_t *__restrict__ oidx, float *__restrict__ oval, Stats *stats,
+                                                uint32_t *__restrict__ oidx, float *__restrict__ oval,
+                                                float *__restrict__ dense, Stats *stats,
                                                 uint32_t *hist, uint32_t *wave_tmp, uint32_t *res,
                                                 uint32_t *sh_g, uint32_t *sh_e) {
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -248,9 +251,12 @@ __device__ __forceinline__ void select_in_block(const uint32_t *__restrict__ bit
         run_g += all_g; run_e += all_e;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (fg[c] || (fe[c] && ce < quota)) {
+            const bool kept = fg[c] || (fe[c] && ce < quota);
+            const uint32_t p = a0 + (g << 2) + c;
+            if (DENSE) {
+                if (inside(g, c)) dense[p] = kept ? __uint_as_float(x[c]) : 0.0f;
+            } else if (kept) {
                 const uint32_t o = cg + (ce < quota ? ce : quota);
-                const uint32_t p = a0 + (g << 2) + c;
                 const uint32_t ix = pos ? pos[p] : p;
                 if (o < k) { oidx[o] = ix; oval[o] = __uint_as_float(x[c]); }
                 else atomicAdd(&stats->errors, 1u);
@@ -319,9 +325,37 @@ __global__ __launch_bounds__(kSelThreads) void k_seg_select(SelArgs a) {
         if (threadIdx.x == 0) atomicAdd(from_list ? &a.stats->fast : &a.stats->fallback, 1u);
     }
     if (from_list)
-        select_in_block<true>(cval, cidx, p0, p1, k, v, u, oidx, oval, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+        select_in_block<true, false>(cval, cidx, p0, p1, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
     else
-        select_in_block<VEC>((const uint32_t *)v, nullptr, lo, hi, k, v, u, oidx, oval, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+        select_in_block<VEC, false>((const uint32_t *)v, nullptr, lo, hi, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+}
+
+// Innovation component (Alg. 1: threshold_inv, mask_inv; Sec. IV-C): per segment of the vector of
+// selected values the k_l largest magnitudes stay, everything else becomes +0.  The input is not
+// modified.  One block per (segment, node).
+template <bool VEC>
+__global__ __launch_bounds__(kSelThreads) void k_innovation(const float *__restrict__ vals, float *__restrict__ out,
+                                                            uint32_t n, const uint32_t *__restrict__ seg_off,
+                                                            const uint32_t *__restrict__ seg_k, Stats *stats) {
+    __shared__ uint32_t hist[4096];
+    __shared__ uint32_t wave_tmp[16], res[2], sh_g[16], sh_e[16];
+    const uint32_t l = blockIdx.x;
+    const uint32_t lo = seg_off[l], hi = seg_off[l + 1], k = seg_k[l];
+    const float *src = vals + (size_t)blockIdx.y * n;
+    float *dst = out + (size_t)blockIdx.y * n;
+    if (k == 0) {
+        for (uint32_t p = lo + threadIdx.x; p < hi; p += kSelThreads) dst[p] = 0.0f;
+        return;
+    }
+    select_in_block<VEC, true>((const uint32_t *)src, nullptr, lo, hi, k, nullptr, nullptr, nullptr, nullptr, dst, stats,
+                               hist, wave_tmp, res, sh_g, sh_e);
+}
+
+void launch_innovation(const float *vals, float *out, uint32_t n, int batch, uint32_t n_seg, const uint32_t *seg_off,
+                       const uint32_t *seg_k, bool vec, Stats *stats, hipStream_t st) {
+    dim3 grid(n_seg, batch);
+    if (vec) hipLaunchKernelGGL(k_innovation<true>, grid, dim3(kSelThreads), 0, st, vals, out, n, seg_off, seg_k, stats);
+    else hipLaunchKernelGGL(k_innovation<false>, grid, dim3(kSelThreads), 0, st, vals, out, n, seg_off, seg_k, stats);
 }
 
 void launch_seg_select(const SelArgs &a, int batch, bool vec, hipStream_t st) {

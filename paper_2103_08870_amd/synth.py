@@ -34,6 +34,20 @@ def mirrored_ae(channels: Sequence[int]) -> Tuple[List[Layer], List[Layer]]:
     return enc, dec
 
 
+def innovation_ae(channels: Sequence[int]) -> Tuple[List[Layer], List[Layer]]:
+    """Autoencoder of the parameter-server pattern (Sec. IV-C) at the benchmark's encoder shape:
+    the mirrored transposed layers bring the latent back to length k with channels[1] // 2
+    channels, then the innovation component joins as one more channel and a final kernel-1,
+    stride-1 layer maps them to the one output channel (the structure of Table II's last rows)."""
+    enc = [(channels[i], channels[i + 1], 3, 2) for i in range(len(channels) - 1)]
+    rev = list(channels)[::-1]
+    mid = max(1, channels[1] // 2)
+    dec = [(rev[i], rev[i + 1], 3, 2) for i in range(len(rev) - 2)]
+    dec.append((rev[-2], mid, 3, 2))
+    dec.append((mid + 1, 1, 1, 1))
+    return enc, dec
+
+
 def paper_ae() -> Tuple[List[Layer], List[Layer]]:
     """Layer shapes of Table I (encoder) and Table II (decoder).  Table II lists
     five stride-2 transposed layers against four stride-2 encoder layers, which
