@@ -41,6 +41,9 @@ def parse():
     p.add_argument("--selection", choices=["flat", "layers"], default="flat",
                    help="flat: one top-k over the whole vector (default, the headline); layers: per-layer "
                         "top-k over the workload's layers, mu_l = max(1, floor(ratio n_l)) (Sec. V-A)")
+    p.add_argument("--ae", choices=["config", "paper"], default="config",
+                   help="config: the workload's two-layer autoencoder (default); paper: Table I / Table II layer "
+                        "shapes (1-64-128-256-64-4 / 4-4-32-64-128-32-1, leaky slope 0.01), deep layers on the matrix cores")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-kernel-events", action="store_true",
                    help="do not bracket the streaming kernel with HIP events (roofline.achieved = null)")
@@ -78,6 +81,31 @@ def cpu_baseline(w, k, enc, dec, host_w, g_host, momentum, plan=None):
                       f"{dt:.2f} s wall on {threads} threads"}
 
 
+def ae_report(enc, dec, k, dec_batch, enc_batch, stages, which):
+    """Multiply-adds of the encoder / decoder stacks at this k and the rate they ran at (their own
+    entry-point timings): the roofline of a contraction is the fp32 MFMA peak."""
+    lens = [k]
+    for (_, _, ks, st) in enc:
+        lens.append(lens[-1] if st == 1 else (lens[-1] + 1) // 2)
+    enc_mac = sum(ci * co * ks * lens[i + 1] for i, (ci, co, ks, st) in enumerate(enc))
+    consumed = [lens[i] for i, l in enumerate(enc) if l[3] == 2]
+    cur, dec_mac = lens[-1], 0
+    for (ci, co, ks, st) in dec:
+        if st == 2:
+            nxt = consumed.pop()
+            dec_mac += ci * co * ks * cur          # every input position meets every tap once (edges aside)
+            cur = nxt
+        else:
+            dec_mac += ci * co * ks * cur
+    peak = 157.3
+    enc_tf = 2.0 * enc_mac * enc_batch / (stages["a3_encode"] * 1e-3) / 1e12
+    dec_tf = 2.0 * dec_mac * dec_batch / (stages["a4_decode"] * 1e-3) / 1e12
+    return {"shape": which, "encode_mac_per_node": enc_mac, "decode_mac_per_node": dec_mac,
+            "encode_TFLOPs": enc_tf, "decode_TFLOPs": dec_tf, "bound": "mfma", "peak": peak, "unit": "TFLOP/s",
+            "encode_frac": enc_tf / peak, "decode_frac": dec_tf / peak,
+            "note": "fp32 in, fp32 accumulate; meaningful for --ae paper (the two-layer stacks are launch-latency bound)"}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -106,9 +134,10 @@ def main():
         seg = B.Segments(seg_off, seg_ks)
         k = seg.total_k
     sets = args.grad_sets or w.iters
-    enc, dec = synth.mirrored_ae(w.ae_channels)
+    enc, dec = synth.mirrored_ae(w.ae_channels) if args.ae == "config" else synth.paper_ae()
+    slope = 0.0 if args.ae == "config" else 0.01
     ew, eb, dw, db = synth.ae_weights(enc, dec, device="cuda")
-    ae = B.Autoencoder(enc, dec, ew, eb, dw, db)
+    ae = B.Autoencoder(enc, dec, ew, eb, dw, db, slope=slope)
     ctx = B.Context(n, k, K)
 
     grads = [synth.gradients(w, t, device="cuda", k_for_ties=(k,)) for t in range(sets)]
@@ -209,7 +238,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {w.cfg} ({w.name}-sized): {K} nodes x {n} fp32 elements, k={k}/node, "
-                               f"momentum {w.momentum}, autoencoder {'->'.join(map(str, w.ae_channels))}, "
+                               f"momentum {w.momentum}, autoencoder "
+                               f"{'->'.join(map(str, w.ae_channels)) if args.ae == 'config' else 'Table I / Table II shapes'}, "
                                f"{sets} gradient sets resident in HBM",
                    "step": ("accumulate+top-k (fused, all nodes in one call) + encode + decode + scatter"
                             if seg is None else
@@ -225,6 +255,7 @@ def main():
                                  "hbm_frac": ALGO_BYTES_PER_ELEM * K * n / fused_ms / 1e6 / HBM_PEAK_GBS,
                                  "note": "same buffers, measured after the timed region"},
         "stages_ms": {name: round(ms, 5) for name, ms in stages.items()},
+        "autoencoder": ae_report(enc, dec, k, K if args.pattern == "ps" else 1, K, stages, args.ae),
         "roofline": roofline,
     }
 

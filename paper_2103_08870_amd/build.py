@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblgc.so")
-SOURCES = ["api.hip", "topk.hip", "segmented.hip", "autoencoder.hip"]
+SOURCES = ["api.hip", "topk.hip", "segmented.hip", "autoencoder.hip", "ae_mfma.hip"]
 HEADERS = [os.path.join(CSRC, "lgc_internal.h"), os.path.join(CSRC, "device_helpers.h"),
            os.path.join(os.path.dirname(HERE), "include", "lgc.h")]
 

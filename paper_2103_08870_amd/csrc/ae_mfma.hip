@@ -1,0 +1,270 @@
+// Deep autoencoder layers on the matrix cores (gfx950, wave64, v_mfma_f32_32x32x2_f32).
+//
+// The paper-size autoencoder (Sec. IV-C, Table I: 1-64-128-256-64-4; Table II: 4-4-32-64-128-32-1)
+// has layers that are dense contractions: a kernel-3 / stride-2 convolution from c_in to c_out
+// channels is, per output position, a product of a [c_out] x [3 c_in] weight matrix with the
+// 3 c_in inputs under the window (contraction depth 192 .. 768), and a kernel-3 / stride-2
+// transposed convolution is two such products (even and odd output positions, depth c_in and
+// 2 c_in).  These run here as implicit GEMMs in fp32 on the MFMA units (fp32 in, fp32 accumulate:
+// the 1e-4 parity bar against the fp64 oracle rules out bf16 / fp16 inputs).  The first and last
+// layers of each stack (1 or 4 channels on one side) stay on the per-layer vector kernels.
+//
+// Operand layout of v_mfma_f32_32x32x2_f32 (checked on the device): lane l supplies
+// A[i = l % 32][k = l / 32] and B[k = l / 32][j = l % 32]; of the 16 results of lane l, number r
+// is C[i = 8 (r / 4) + 4 (l / 32) + r % 4][j = l % 32].  Here i is the output channel, j the
+// position and k the contraction index, so each result register of a half-wavefront is 32
+// consecutive positions of one channel: coalesced stores.
+
+#include "lgc_internal.h"
+
+namespace lgc {
+
+typedef float acc16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float leaky_m(float x, float slope) { return x > 0.f ? x : slope * x; }
+
+// ---- weights in contraction-major order -----------------------------------------------------------
+// conv:  w [c_out][c_in][3]  ->  wt[(ci*3 + t)][co]
+// convT: w [c_in][c_out][3]  ->  wt[(t*c_in + ci)][co]     (tap-major: the kernel takes one tap at a time)
+__global__ void k_weights_contraction_major(const float *__restrict__ w, float *__restrict__ wt, int c_in, int c_out,
+                                            int transposed) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= c_in * c_out * 3) return;
+    if (!transposed) {
+        const int t = e % 3, ci = (e / 3) % c_in, co = e / (3 * c_in);
+        wt[(size_t)(ci * 3 + t) * c_out + co] = w[e];
+    } else {
+        const int t = e % 3, co = (e / 3) % c_out, ci = e / (3 * c_out);
+        wt[(size_t)(t * c_in + ci) * c_out + co] = w[e];
+    }
+}
+
+void launch_weights_contraction_major(const float *w, float *wt, int c_in, int c_out, bool transposed, hipStream_t st) {
+    const int total = c_in * c_out * 3;
+    hipLaunchKernelGGL(k_weights_contraction_major, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, c_in, c_out,
+                       (int)transposed);
+}
+
+// ---- convolution, kernel 3, stride 2, padding 1 -----------------------------------------------------
+// out[b][co][p] = bias[co] + sum_ci sum_t w[co][ci][t] * in[b][ci][2p - 1 + t]
+// Block: 256 threads, 64 output channels x 64 positions; wavefront (wm, wn) of 2 x 2 owns one 32 x 32
+// MFMA tile.  Small tiles on purpose: the layers are short (a few thousand positions per node), and
+// a few hundred blocks are needed to keep 256 compute units evenly busy.  The contraction runs over
+// chunks of 16 input channels staged in LDS: inputs split into odd and even positions (so that every
+// tap is a unit-stride read), weights as [48][64].  The next chunk is fetched into registers while
+// the current one is multiplied.  c_in % 16 == 0 and c_out % 64 == 0.
+constexpr int kCiChunk = 16;
+constexpr int kPosTile = 64;
+constexpr int kRowPad = 136;    // per input channel: odd positions [0..64], even positions [68..131]
+constexpr int kEvenOff = 68;
+constexpr int kXPerRow = 2 * kPosTile + 1;                           // 129 inputs per channel and tile
+constexpr int kXRegs = (kCiChunk * kXPerRow + 255) / 256;            // 9
+constexpr int kWRegs = kCiChunk * 3 * 64 / 256;                      // 12
+
+__global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ in, float *__restrict__ out,
+                                                      const float *__restrict__ wt, const float *__restrict__ bias,
+                                                      int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
+                                                      float slope) {
+    __shared__ float xs[kCiChunk * kRowPad];
+    __shared__ float ws[kCiChunk * 3 * 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, half = lane >> 5, col = lane & 31;
+    const uint32_t p0 = blockIdx.x * kPosTile;
+    const int co0 = blockIdx.y * 64;
+    in += (size_t)blockIdx.z * c_in * l_in;
+    out += (size_t)blockIdx.z * c_out * l_out;
+
+    // staging slots of this thread, fixed for the whole contraction: input slot e = tid + 256 i is
+    // (channel e / 129, r = e % 129) with r <= 64: odd[r] = in[2 (p0 + r) - 1] and
+    // r > 64: even[r - 65] = in[2 (p0 + r - 65)]; gx = offset inside a chunk of the input (or none), lx = LDS slot
+    uint32_t gx[kXRegs], gw[kWRegs];
+    int lx[kXRegs];
+#pragma unroll
+    for (int i = 0; i < kXRegs; ++i) {
+        const int e = tid + 256 * i;
+        const int ci = e / kXPerRow, r = e % kXPerRow;
+        const long long q = r <= kPosTile ? 2ll * (p0 + r) - 1 : 2ll * (p0 + (r - kPosTile - 1));
+        const bool slot = e < kCiChunk * kXPerRow;
+        gx[i] = (slot && q >= 0 && q < (long long)l_in) ? (uint32_t)(ci * (size_t)l_in + q) : 0xffffffffu;
+        lx[i] = slot ? ci * kRowPad + (r <= kPosTile ? r : kEvenOff + (r - kPosTile - 1)) : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < kWRegs; ++i) {
+        const int e = tid + 256 * i;
+        gw[i] = (uint32_t)((e >> 6) * c_out + co0 + (e & 63));
+    }
+    float xr[kXRegs], wr[kWRegs];
+    auto fetch = [&](int c0) {
+        const float *xin = in + (size_t)c0 * l_in;
+        const float *win = wt + (size_t)c0 * 3 * c_out;
+#pragma unroll
+        for (int i = 0; i < kXRegs; ++i) xr[i] = gx[i] != 0xffffffffu ? xin[gx[i]] : 0.f;
+#pragma unroll
+        for (int i = 0; i < kWRegs; ++i) wr[i] = win[gw[i]];
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < kXRegs; ++i)
+            if (lx[i] >= 0) xs[lx[i]] = xr[i];
+#pragma unroll
+        for (int i = 0; i < kWRegs; ++i) ws[tid + 256 * i] = wr[i];
+    };
+
+    acc16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+    fetch(0);
+    for (int c0 = 0; c0 < c_in; c0 += kCiChunk) {
+        __syncthreads();   // the previous chunk's readers are done
+        stage();
+        __syncthreads();
+        if (c0 + kCiChunk < c_in) fetch(c0 + kCiChunk);   // in flight during the multiplications below
+#pragma unroll
+        for (int s = 0; s < kCiChunk * 3 / 2; ++s) {
+            // contraction indices 2s (lanes 0..31) and 2s + 1 (lanes 32..63): (channel, tap) of each
+            const int kk_lo = 2 * s, kk_hi = 2 * s + 1;
+            const int off_lo = (kk_lo / 3) * kRowPad + ((kk_lo % 3) == 1 ? kEvenOff : 0) + ((kk_lo % 3) == 2 ? 1 : 0);
+            const int off_hi = (kk_hi / 3) * kRowPad + ((kk_hi % 3) == 1 ? kEvenOff : 0) + ((kk_hi % 3) == 2 ? 1 : 0);
+            const float a = ws[(2 * s + half) * 64 + wm * 32 + col];
+            const float b = xs[(half ? off_hi : off_lo) + wn * 32 + col];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+        }
+    }
+    const uint32_t p = p0 + wn * 32 + col;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int co = co0 + wm * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+        if (p < l_out) {
+            const float y = acc[r] + bias[co];
+            out[(size_t)co * l_out + p] = act ? leaky_m(y, slope) : y;
+        }
+    }
+}
+
+bool launch_conv3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
+                         bool act, float slope, hipStream_t st) {
+    if (!l.wt || l.ksize != 3 || l.stride != 2 || l.c_in % kCiChunk != 0 || l.c_out % 64 != 0) return false;
+    if ((uint64_t)l_in * kCiChunk >= (1ull << 32) || (uint64_t)l.c_in * 3 * l.c_out >= (1ull << 32)) return false;   // 32-bit offsets inside a chunk
+    if (l_out == 0) return true;
+    dim3 grid((l_out + kPosTile - 1) / kPosTile, l.c_out / 64, batch);
+    hipLaunchKernelGGL(k_conv3s2_mfma, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                       (int)act, slope);
+    return true;
+}
+
+// ---- transposed convolution, kernel 3, stride 2, padding 1 ------------------------------------------
+// out[b][co][q] = bias[co] + sum_ci sum_{(p,t): 2p - 1 + t = q} w[ci][co][t] * in[b][ci][p]
+//   even q = 2m:     sum_ci w[ci][co][1] in[ci][m]
+//   odd  q = 2m + 1: sum_ci ( w[ci][co][0] in[ci][m+1] + w[ci][co][2] in[ci][m] )
+// Block: 256 threads, 32 output channels x 128 input positions m (256 output positions); wavefront w
+// owns the 32 channels x 32 positions m = 32 w .. 32 w + 31, with one accumulator tile for the even
+// and one for the odd outputs.  Chunks of 16 input channels in LDS: inputs [16][129] (unit stride for
+// both taps), weights [3][16][32] (tap-major); the next chunk is fetched into registers during the
+// multiplications.  c_in % 16 == 0 and c_out % 32 == 0.
+constexpr int kTPosTile = 128;
+constexpr int kTRowPad = 132;
+constexpr int kTXRegs = (kCiChunk * (kTPosTile + 1) + 255) / 256;    // 9
+constexpr int kTWRegs = 3 * kCiChunk * 32 / 256;                      // 6
+
+__global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__ in, float *__restrict__ out,
+                                                       const float *__restrict__ wt, const float *__restrict__ bias,
+                                                       int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
+                                                       float slope) {
+    __shared__ float xs[kCiChunk * kTRowPad];
+    __shared__ float ws[3 * kCiChunk * 32];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const uint32_t m0 = blockIdx.x * kTPosTile;
+    const int co0 = blockIdx.y * 32;
+    in += (size_t)blockIdx.z * c_in * l_in;
+    out += (size_t)blockIdx.z * c_out * l_out;
+
+    // staging slots of this thread, fixed for the whole contraction (see the convolution above)
+    uint32_t gx[kTXRegs], gw[kTWRegs];
+    int lx[kTXRegs];
+#pragma unroll
+    for (int i = 0; i < kTXRegs; ++i) {
+        const int e = tid + 256 * i;
+        const int ci = e / (kTPosTile + 1), r = e % (kTPosTile + 1);
+        const bool slot = e < kCiChunk * (kTPosTile + 1);
+        gx[i] = (slot && m0 + r < l_in) ? (uint32_t)(ci * (size_t)l_in + m0 + r) : 0xffffffffu;
+        lx[i] = slot ? ci * kTRowPad + r : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < kTWRegs; ++i) {
+        const int e = tid + 256 * i;
+        const int t = e / (kCiChunk * 32), ci = (e / 32) % kCiChunk, co = e & 31;
+        gw[i] = (uint32_t)((t * c_in + ci) * c_out + co0 + co);
+    }
+    float xr[kTXRegs], wr[kTWRegs];
+    auto fetch = [&](int c0) {
+        const float *xin = in + (size_t)c0 * l_in;
+        const float *win = wt + (size_t)c0 * c_out;
+#pragma unroll
+        for (int i = 0; i < kTXRegs; ++i) xr[i] = gx[i] != 0xffffffffu ? xin[gx[i]] : 0.f;
+#pragma unroll
+        for (int i = 0; i < kTWRegs; ++i) wr[i] = win[gw[i]];
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < kTXRegs; ++i)
+            if (lx[i] >= 0) xs[lx[i]] = xr[i];
+#pragma unroll
+        for (int i = 0; i < kTWRegs; ++i) ws[tid + 256 * i] = wr[i];
+    };
+
+    acc16 even, odd;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { even[r] = 0.f; odd[r] = 0.f; }
+
+    fetch(0);
+    for (int c0 = 0; c0 < c_in; c0 += kCiChunk) {
+        __syncthreads();
+        stage();
+        __syncthreads();
+        if (c0 + kCiChunk < c_in) fetch(c0 + kCiChunk);
+#pragma unroll
+        for (int s = 0; s < kCiChunk / 2; ++s) {
+            const int ci = 2 * s + half;                      // this half-wavefront's input channel
+            const float x0 = xs[ci * kTRowPad + wave * 32 + col];        // in[ci][m]
+            const float x1 = xs[ci * kTRowPad + wave * 32 + col + 1];    // in[ci][m + 1]
+            const float w0 = ws[(0 * kCiChunk + ci) * 32 + col];
+            const float w1 = ws[(1 * kCiChunk + ci) * 32 + col];
+            const float w2 = ws[(2 * kCiChunk + ci) * 32 + col];
+            even = __builtin_amdgcn_mfma_f32_32x32x2f32(w1, x0, even, 0, 0, 0);
+            odd = __builtin_amdgcn_mfma_f32_32x32x2f32(w0, x1, odd, 0, 0, 0);
+            odd = __builtin_amdgcn_mfma_f32_32x32x2f32(w2, x0, odd, 0, 0, 0);
+        }
+    }
+    const uint32_t m = m0 + wave * 32 + col;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int co = co0 + (r >> 2) * 8 + half * 4 + (r & 3);
+        const float bv = bias[co];
+        const uint64_t q = 2ull * m;
+        if (q < l_out) {
+            const float y = even[r] + bv;
+            out[(size_t)co * l_out + q] = act ? leaky_m(y, slope) : y;
+        }
+        if (q + 1 < l_out) {
+            const float y = odd[r] + bv;
+            out[(size_t)co * l_out + q + 1] = act ? leaky_m(y, slope) : y;
+        }
+    }
+}
+
+bool launch_convt3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
+                          bool act, float slope, hipStream_t st) {
+    if (!l.wt || l.ksize != 3 || l.stride != 2 || l.c_in % kCiChunk != 0 || l.c_out % 32 != 0) return false;
+    if ((uint64_t)l_in * kCiChunk >= (1ull << 32) || (uint64_t)l.c_in * 3 * l.c_out >= (1ull << 32)) return false;   // 32-bit offsets inside a chunk
+    if (l_out == 0) return true;
+    // input positions that reach an output: m < ceil(l_out / 2) (and the odd tap of m = that - 1 reads m + 1)
+    const uint32_t m_count = (l_out + 1) / 2;
+    dim3 grid((m_count + kTPosTile - 1) / kTPosTile, l.c_out / 32, batch);
+    hipLaunchKernelGGL(k_convt3s2_mfma, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                       (int)act, slope);
+    return true;
+}
+
+}  // namespace lgc

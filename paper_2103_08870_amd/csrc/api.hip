@@ -56,6 +56,7 @@ struct lgc_ae {
     std::vector<lgc_layer> enc, dec;
     std::vector<LayerDev> enc_dev, dec_dev;
     float *weights = nullptr;  // device copy of all weights and biases
+    float *weights_t = nullptr;  // contraction-major copies for the layers that run on the matrix cores
 };
 
 static thread_local char g_err[256] = "";
@@ -445,8 +446,35 @@ extern "C" lgc_status lgc_ae_create(lgc_ae **out, int device, int n_enc, const l
     };
     for (int l = 0; l < n_enc && e == hipSuccess; ++l) e = take(enc[l], enc_w[l], enc_b[l], ae->enc_dev);
     for (int l = 0; l < n_dec && e == hipSuccess; ++l) e = take(dec[l], dec_w[l], dec_b[l], ae->dec_dev);
+    if (e == hipSuccess) {
+        // deep kernel-3 / stride-2 layers run on the matrix cores from a contraction-major copy of their weights
+        auto deep = [](const lgc_layer &l, int co_multiple) {
+            return l.ksize == 3 && l.stride == 2 && l.c_in % 16 == 0 && l.c_out % co_multiple == 0;
+        };
+        size_t t_total = 0;
+        for (auto &l : ae->enc) if (deep(l, 64)) t_total += wsize(l);
+        for (auto &l : ae->dec) if (deep(l, 32)) t_total += wsize(l);
+        if (t_total) {
+            e = hipMalloc((void **)&ae->weights_t, t_total * 4);
+            size_t t_off = 0;
+            for (size_t l = 0; l < ae->enc.size() && e == hipSuccess; ++l)
+                if (deep(ae->enc[l], 64)) {
+                    launch_weights_contraction_major(ae->enc_dev[l].w, ae->weights_t + t_off, ae->enc[l].c_in, ae->enc[l].c_out, false, nullptr);
+                    ae->enc_dev[l].wt = ae->weights_t + t_off;
+                    t_off += wsize(ae->enc[l]);
+                }
+            for (size_t l = 0; l < ae->dec.size() && e == hipSuccess; ++l)
+                if (deep(ae->dec[l], 32) && !(with_innovation && l + 1 == ae->dec.size())) {
+                    launch_weights_contraction_major(ae->dec_dev[l].w, ae->weights_t + t_off, ae->dec[l].c_in, ae->dec[l].c_out, true, nullptr);
+                    ae->dec_dev[l].wt = ae->weights_t + t_off;
+                    t_off += wsize(ae->dec[l]);
+                }
+            if (e == hipSuccess) e = hipGetLastError();
+        }
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
+        if (ae->weights_t) (void)hipFree(ae->weights_t);
         (void)hipFree(ae->weights);
         delete ae;
         return fail(nullptr, LGC_EHIP, "copying autoencoder weights: %s", hipGetErrorString(e));
@@ -460,6 +488,7 @@ extern "C" void lgc_ae_destroy(lgc_ae *ae) {
     DeviceGuard guard(ae->device);
     (void)hipDeviceSynchronize();
     if (ae->weights) (void)hipFree(ae->weights);
+    if (ae->weights_t) (void)hipFree(ae->weights_t);
     delete ae;
 }
 
@@ -542,7 +571,8 @@ extern "C" lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *va
     for (size_t l = 0; l < nl; ++l) {
         const bool last = l + 1 == nl;
         float *dst = last ? latent : ctx->act[l & 1];
-        launch_conv1d(cur, dst, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, !last, ae->slope, st);
+        if (!launch_conv3s2_mfma(cur, dst, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, !last, ae->slope, st))
+            launch_conv1d(cur, dst, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, !last, ae->slope, st);
         cur = dst;
     }
     hipError_t e = hipGetLastError();
@@ -582,8 +612,11 @@ static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent
     for (size_t l = 0; l < nl; ++l) {
         const bool last = l + 1 == nl;
         float *dst = last ? rec : ctx->act[l & 1];
-        launch_conv_transpose1d(cur, dst, ae->dec_dev[l], (uint32_t)in_len, (uint32_t)out_len[l], batch, !last,
-                                ae->slope, st, last ? innov : nullptr);
+        const float *extra = last ? innov : nullptr;
+        if (extra || !launch_convt3s2_mfma(cur, dst, ae->dec_dev[l], (uint32_t)in_len, (uint32_t)out_len[l], batch, !last,
+                                           ae->slope, st))
+            launch_conv_transpose1d(cur, dst, ae->dec_dev[l], (uint32_t)in_len, (uint32_t)out_len[l], batch, !last,
+                                    ae->slope, st, extra);
         cur = dst;
         in_len = out_len[l];
     }

@@ -1,7 +1,8 @@
 // Autoencoder layers (Sec. IV-C, Tables I and II: 1-D convolutions / transposed convolutions,
 // kernel size 1 or 3, stride 1 or 2, padding (ksize-1)/2) and the scatter/average step
 // (Sec. V-B), for gfx950.  Generic per-layer kernels: one thread computes COT output channels
-// at one output position; weights are wave-uniform and come through the scalar cache.
+// at one output position; weights are wave-uniform and come through the scalar cache; the input
+// channels are taken in groups of G whose loads are all issued before the group's multiply-adds.
 #include "lgc_internal.h"
 
 namespace lgc {
@@ -9,7 +10,7 @@ namespace lgc {
 __device__ __forceinline__ float leaky(float x, float slope) { return x > 0.f ? x : slope * x; }
 
 // out[b][co][p] = bias[co] + sum_ci sum_t w[co][ci][t] * in[b][ci][p*stride - pad + t]
-template <int COT, int KS>
+template <int COT, int KS, int G>
 __global__ __launch_bounds__(256) void k_conv1d(const float *__restrict__ in, float *__restrict__ out,
                                                 const float *__restrict__ w, const float *__restrict__ bias,
                                                 int c_in, int c_out, int stride, uint32_t l_in,
@@ -25,18 +26,28 @@ __global__ __launch_bounds__(256) void k_conv1d(const float *__restrict__ in, fl
 #pragma unroll
     for (int c = 0; c < COT; ++c) acc[c] = (co0 + c < c_out) ? bias[co0 + c] : 0.f;
     const long long q0 = (long long)p * stride - PAD;
-    for (int ci = 0; ci < c_in; ++ci) {
-        float x[KS];
+    // input channels in groups of G: all loads of a group are issued before its multiply-adds
+    // (the order of the additions per output stays ci ascending, tap ascending)
+    for (int ci0 = 0; ci0 < c_in; ci0 += G) {
+        float x[G][KS];
 #pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            const long long q = q0 + t;
-            x[t] = (q >= 0 && q < (long long)l_in) ? in[(size_t)ci * l_in + q] : 0.f;
-        }
+        for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int c = 0; c < COT; ++c) {
-            if (co0 + c < c_out) {
+            for (int t = 0; t < KS; ++t) {
+                const long long q = q0 + t;
+                x[g][t] = (ci0 + g < c_in && q >= 0 && q < (long long)l_in) ? in[(size_t)(ci0 + g) * l_in + q] : 0.f;
+            }
 #pragma unroll
-                for (int t = 0; t < KS; ++t) acc[c] = fmaf(w[((size_t)(co0 + c) * c_in + ci) * KS + t], x[t], acc[c]);
+        for (int g = 0; g < G; ++g) {
+            if (ci0 + g < c_in) {
+#pragma unroll
+                for (int c = 0; c < COT; ++c) {
+                    if (co0 + c < c_out) {
+#pragma unroll
+                        for (int t = 0; t < KS; ++t)
+                            acc[c] = fmaf(w[((size_t)(co0 + c) * c_in + ci0 + g) * KS + t], x[g][t], acc[c]);
+                    }
+                }
             }
         }
     }
@@ -48,7 +59,7 @@ __global__ __launch_bounds__(256) void k_conv1d(const float *__restrict__ in, fl
 // out[b][co][q] = bias[co] + sum_ci sum_{(p,t): p*stride - pad + t = q} w[ci][co][t] * in[b][ci][p]
 // With `extra` (decoder with the innovation component, Sec. IV-C): the last of the c_in input
 // channels is extra[b][:], the others are in[b][0 .. c_in-2][:].
-template <int COT, int KS>
+template <int COT, int KS, int G>
 __global__ __launch_bounds__(256) void k_conv_transpose1d(const float *__restrict__ in, float *__restrict__ out,
                                                           const float *__restrict__ w,
                                                           const float *__restrict__ bias, int c_in, int c_out,
@@ -75,16 +86,26 @@ __global__ __launch_bounds__(256) void k_conv_transpose1d(const float *__restric
         hit[t] = num >= 0 && (num % stride) == 0 && (num / stride) < (long long)l_in;
         src[t] = hit[t] ? (uint32_t)(num / stride) : 0u;
     }
-    for (int ci = 0; ci < c_in; ++ci) {
-        const float *row = ci < c_main ? in + (size_t)ci * l_in : extra;
-        float x[KS];
+    for (int ci0 = 0; ci0 < c_in; ci0 += G) {
+        float x[G][KS];
 #pragma unroll
-        for (int t = 0; t < KS; ++t) x[t] = hit[t] ? row[src[t]] : 0.f;
+        for (int g = 0; g < G; ++g) {
+            const int ci = ci0 + g;
+            const float *row = ci < c_main ? in + (size_t)ci * l_in : extra;
 #pragma unroll
-        for (int c = 0; c < COT; ++c) {
-            if (co0 + c < c_out) {
+            for (int t = 0; t < KS; ++t) x[g][t] = (ci < c_in && hit[t]) ? row[src[t]] : 0.f;
+        }
 #pragma unroll
-                for (int t = 0; t < KS; ++t) acc[c] = fmaf(w[((size_t)ci * c_out + co0 + c) * KS + t], x[t], acc[c]);
+        for (int g = 0; g < G; ++g) {
+            if (ci0 + g < c_in) {
+#pragma unroll
+                for (int c = 0; c < COT; ++c) {
+                    if (co0 + c < c_out) {
+#pragma unroll
+                        for (int t = 0; t < KS; ++t)
+                            acc[c] = fmaf(w[((size_t)(ci0 + g) * c_out + co0 + c) * KS + t], x[g][t], acc[c]);
+                    }
+                }
             }
         }
     }
@@ -99,24 +120,22 @@ void launch_conv1d(const float *in, float *out, const LayerDev &l, uint32_t l_in
                    bool act, float slope, hipStream_t st) {
     if (l_out == 0) return;
     dim3 grid((l_out + 255) / 256, (l.c_out + kCot - 1) / kCot, batch);
-    if (l.ksize == 3)
-        hipLaunchKernelGGL((k_conv1d<kCot, 3>), grid, dim3(256), 0, st, in, out, l.w, l.b, l.c_in, l.c_out,
-                           l.stride, l_in, l_out, (int)act, slope);
-    else
-        hipLaunchKernelGGL((k_conv1d<kCot, 1>), grid, dim3(256), 0, st, in, out, l.w, l.b, l.c_in, l.c_out,
-                           l.stride, l_in, l_out, (int)act, slope);
+#define LGC_CONV(KS, G) hipLaunchKernelGGL((k_conv1d<kCot, KS, G>), grid, dim3(256), 0, st, in, out, l.w, l.b, l.c_in, \
+                                           l.c_out, l.stride, l_in, l_out, (int)act, slope)
+    if (l.ksize == 3) { if (l.c_in >= 16) LGC_CONV(3, 16); else if (l.c_in >= 4) LGC_CONV(3, 4); else LGC_CONV(3, 1); }
+    else              { if (l.c_in >= 16) LGC_CONV(1, 16); else if (l.c_in >= 4) LGC_CONV(1, 4); else LGC_CONV(1, 1); }
+#undef LGC_CONV
 }
 
 void launch_conv_transpose1d(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out,
                              int batch, bool act, float slope, hipStream_t st, const float *extra) {
     if (l_out == 0) return;
     dim3 grid((l_out + 255) / 256, (l.c_out + kCot - 1) / kCot, batch);
-    if (l.ksize == 3)
-        hipLaunchKernelGGL((k_conv_transpose1d<kCot, 3>), grid, dim3(256), 0, st, in, out, l.w, l.b, l.c_in,
-                           l.c_out, l.stride, l_in, l_out, (int)act, slope, extra);
-    else
-        hipLaunchKernelGGL((k_conv_transpose1d<kCot, 1>), grid, dim3(256), 0, st, in, out, l.w, l.b, l.c_in,
-                           l.c_out, l.stride, l_in, l_out, (int)act, slope, extra);
+#define LGC_CONVT(KS, G) hipLaunchKernelGGL((k_conv_transpose1d<kCot, KS, G>), grid, dim3(256), 0, st, in, out, l.w, l.b, \
+                                            l.c_in, l.c_out, l.stride, l_in, l_out, (int)act, slope, extra)
+    if (l.ksize == 3) { if (l.c_in >= 16) LGC_CONVT(3, 16); else if (l.c_in >= 4) LGC_CONVT(3, 4); else LGC_CONVT(3, 1); }
+    else              { if (l.c_in >= 16) LGC_CONVT(1, 16); else if (l.c_in >= 4) LGC_CONVT(1, 4); else LGC_CONVT(1, 1); }
+#undef LGC_CONVT
 }
 
 // ---- two-layer stacks in one launch ------------------------------------------------------------

@@ -126,7 +126,8 @@ void launch_innovation(const float *vals, float *out, uint32_t n, int batch, uin
 // autoencoder.hip
 struct LayerDev {
     int c_in, c_out, ksize, stride;
-    const float *w, *b;  // device
+    const float *w, *b;         // device
+    const float *wt = nullptr;  // device: weights in contraction-major order for the MFMA kernels, or null
 };
 void launch_conv1d(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out,
                    int batch, bool act, float slope, hipStream_t st);
@@ -146,6 +147,12 @@ void launch_scatter(const float *vals, const uint32_t *idx, uint32_t k, float sc
 bool launch_scatter_nodes(const float *vals, const uint32_t *idx, uint32_t k, int batch, float scale, float *dense,
                           uint32_t n, Stats *stats, hipStream_t st);
 
+// ae_mfma.hip: deep kernel-3 / stride-2 layers on the matrix cores; false = layer not covered (nothing launched)
+void launch_weights_contraction_major(const float *w, float *wt, int c_in, int c_out, bool transposed, hipStream_t st);
+bool launch_conv3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
+                         bool act, float slope, hipStream_t st);
+bool launch_convt3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
+                          bool act, float slope, hipStream_t st);
 void launch_gather_at(float *v, float *u, uint64_t stride, uint32_t n, int batch, const uint32_t *idx, uint32_t k,
                       float *out, Stats *stats, hipStream_t st);
 void launch_average(const float *x, uint32_t len, int batch, float scale, float *out, hipStream_t st);

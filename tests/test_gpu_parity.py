@@ -281,11 +281,12 @@ def test_encode_decode(B, oracle, channels, k, batch):
     ctx.close(); ae.close()
 
 
-def test_paper_size_autoencoder_small_input(B, oracle):
-    # Table I / Table II layer shapes (with leaky-ReLU) on a short input
+@pytest.mark.parametrize("k", [777, 25_600])
+def test_paper_size_autoencoder(B, oracle, k):
+    # Table I / Table II layer shapes (with leaky-ReLU): the deep layers run on the matrix cores;
+    # a short ragged input and the benchmark's k
     ae, enc, dec, (ew, eb, dw, db) = make_ae(B, paper=True, slope=0.01)
     ctx = B.Context(1 << 16, 1 << 16, 2)
-    k = 777
     x = np.random.default_rng(0).laplace(0, 1e-2, (2, k)).astype(np.float32)
     lat = torch.zeros((2, B.lgc_latent_len(ae, k)), device="cuda")
     rec = torch.zeros((2, k), device="cuda")
@@ -293,7 +294,7 @@ def test_paper_size_autoencoder_small_input(B, oracle):
     B.lgc_decode(ctx, ae, lat, rec)
     for b in range(2):
         ol = oracle.encode(x[b], enc, ew, eb, slope=0.01)
-        assert ol.shape == (4, 49)
+        assert ol.shape == (4, -(-k // 16))
         assert rel_l2(lat[b], ol) <= REL_L2_TOL
         assert rel_l2(rec[b], oracle.decode(ol, k, enc, dec, dw, db, slope=0.01)) <= 2 * REL_L2_TOL
     ctx.close(); ae.close()
