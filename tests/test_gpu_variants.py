@@ -124,3 +124,34 @@ def test_ring_allreduce_iterations(B, oracle, cfg, n):
         oracle.scatter(rec[0].cpu().numpy(), oidx, 1.0, ref)
         assert same_bits(dense, ref)
     ctx.close(); ae.close()
+
+
+def test_ring_allreduce_full_size_resnet50(B, oracle):
+    """The benchmark's launch configuration of the ring-allreduce pattern (4 nodes x 25.6 M, k = 25 600):
+    selected values, positions and the state of the selecting node and of one other node, bit for bit."""
+    w = synth.workload(2)
+    K, n, k = w.nodes, w.n, w.k
+    ctx = B.Context(n, k, K)
+    u = torch.zeros((K, n), device="cuda"); v = torch.zeros((K, n), device="cuda")
+    vals = torch.zeros((K, k), device="cuda"); idx = torch.zeros(k, device="cuda", dtype=torch.int32)
+    hu = np.zeros((K, n), np.float32); hv = np.zeros((K, n), np.float32)
+    for t in range(2):
+        g = synth.gradients(w, t, device="cuda")
+        L = (t + 1) % K
+        B.lgc_accumulate_topk(ctx, g[L], u[L], v[L], w.momentum, k, vals[L], idx)
+        for lo, hi in ((0, L), (L + 1, K)):
+            if hi > lo:
+                B.lgc_accumulate_gather(ctx, g[lo:hi], u[lo:hi], v[lo:hi], w.momentum, idx, vals[lo:hi])
+        assert B.lgc_stats(ctx)[2] == 0
+        gh = g.cpu().numpy()
+        for b in range(K):
+            oracle.accumulate(gh[b], hu[b], hv[b], w.momentum)
+        ovals, oidx = oracle.topk(hv[L], hu[L], k)
+        assert (idx.cpu().numpy().astype(np.uint32) == oidx).all() and same_bits(vals[L], ovals)
+        for b in range(K):
+            if b != L:
+                assert same_bits(vals[b], oracle.gather(hv[b], hu[b], oidx))
+        other = (L + 2) % K
+        for b in (L, other):
+            assert same_bits(v[b], hv[b]) and same_bits(u[b], hu[b])
+    ctx.close()
