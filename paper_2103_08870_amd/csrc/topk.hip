@@ -59,12 +59,32 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(const float *__restrict__
     }
 }
 
+// Calls launch(node0, nodes, row_begin, row_end) for shares of at most kRowsPerLaunch rows:
+// several whole nodes per launch while they fit, else one node in row ranges.
+template <typename F>
+static void for_each_share(uint32_t nrows, int batch, F launch) {
+    if ((uint64_t)nrows * batch <= kRowsPerLaunch) { launch(0u, batch, 0u, nrows); return; }
+    if (nrows <= kRowsPerLaunch) {
+        const int per = (int)(kRowsPerLaunch / nrows);
+        for (int b = 0; b < batch; b += per) launch((uint32_t)b, batch - b < per ? batch - b : per, 0u, nrows);
+        return;
+    }
+    for (int b = 0; b < batch; ++b)
+        for (uint32_t r = 0; r < nrows; r += kRowsPerLaunch)
+            launch((uint32_t)b, 1, r, nrows - r < kRowsPerLaunch ? nrows : r + kRowsPerLaunch);
+}
+
 void launch_accumulate(const float *g, float *u, float *v, uint32_t n, int batch, uint64_t stride,
                        float momentum, bool vec, hipStream_t st) {
     const uint32_t nrows = (n + kRow - 1) / kRow;
-    dim3 grid((nrows + kWaves - 1) / kWaves, batch);
-    if (vec) hipLaunchKernelGGL(k_accumulate<true>, grid, dim3(kBlock), 0, st, g, u, v, n, stride, momentum);
-    else hipLaunchKernelGGL(k_accumulate<false>, grid, dim3(kBlock), 0, st, g, u, v, n, stride, momentum);
+    for_each_share(nrows, batch, [&](uint32_t node0, int nodes, uint32_t r0, uint32_t r1) {
+        // a share is passed as shifted pointers and its own length (row ranges keep 16-byte alignment)
+        const size_t off = (size_t)node0 * stride + (size_t)r0 * kRow;
+        const uint32_t len = (r1 == nrows ? n : r1 * (uint32_t)kRow) - r0 * (uint32_t)kRow;
+        dim3 grid((r1 - r0 + kWaves - 1) / kWaves, nodes);
+        if (vec) hipLaunchKernelGGL(k_accumulate<true>, grid, dim3(kBlock), 0, st, g + off, u + off, v + off, len, stride, momentum);
+        else hipLaunchKernelGGL(k_accumulate<false>, grid, dim3(kBlock), 0, st, g + off, u + off, v + off, len, stride, momentum);
+    });
 }
 
 // ------------------------------------------------------------------ clearing of a state set
@@ -215,7 +235,7 @@ __device__ __forceinline__ void full_row(const float *__restrict__ g, float *__r
 // element, with bit 31 set when the row runs into further segments.
 template <bool FUSED, bool VEC, bool SEG>
 __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
-    const int node = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int node = a.node0 + blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t off = (size_t)node * a.stride;
     const float *__restrict__ g = a.g + off;
     float *__restrict__ u = a.u + off;
@@ -223,10 +243,9 @@ __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
     const uint32_t t_est = SEG ? 0u : a.sel[node].t_est;
     const uint32_t *seg_t = SEG ? a.seg_t + (size_t)node * a.n_seg : nullptr;
     const float m = a.momentum;
-    const uint32_t nrows = (a.n + kRow - 1) / kRow;
     unsigned long long *bitmap = a.bitmap + (size_t)node * a.rows * kRowWords;
     uint32_t *row_count = a.row_count + (size_t)node * a.rows;
-    for (uint32_t r = blockIdx.x * kWaves + wave; r < nrows; r += gridDim.x * kWaves) {
+    for (uint32_t r = a.row_begin + blockIdx.x * kWaves + wave; r < a.row_end; r += gridDim.x * kWaves) {
         const uint32_t row = r * (uint32_t)kRow;
         const uint32_t end = (a.n - row > (uint32_t)kRow) ? row + kRow : a.n;
         uint32_t bits[4][4];
@@ -301,19 +320,23 @@ __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
     }
 }
 
-void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st) {
-    const uint32_t nrows = (a.n + kRow - 1) / kRow;
-    dim3 grid((nrows + kWaves - 1) / kWaves, batch);
-    const bool seg = a.seg_t != nullptr;
+void launch_candidates(const SelArgs &args, int batch, bool fused, bool vec, hipStream_t st) {
+    const uint32_t nrows = (args.n + kRow - 1) / kRow;
+    const bool seg = args.seg_t != nullptr;
+    for_each_share(nrows, batch, [&](uint32_t node0, int nodes, uint32_t r0, uint32_t r1) {
+        SelArgs a = args;
+        a.node0 = node0; a.row_begin = r0; a.row_end = r1;
+        dim3 grid((r1 - r0 + kWaves - 1) / kWaves, nodes);
 #define LGC_CAND(F, V, S) hipLaunchKernelGGL((k_candidates<F, V, S>), grid, dim3(kBlock), 0, st, a)
-    if (seg) {
-        if (fused) { if (vec) LGC_CAND(true, true, true); else LGC_CAND(true, false, true); }
-        else       { if (vec) LGC_CAND(false, true, true); else LGC_CAND(false, false, true); }
-    } else {
-        if (fused) { if (vec) LGC_CAND(true, true, false); else LGC_CAND(true, false, false); }
-        else       { if (vec) LGC_CAND(false, true, false); else LGC_CAND(false, false, false); }
-    }
+        if (seg) {
+            if (fused) { if (vec) LGC_CAND(true, true, true); else LGC_CAND(true, false, true); }
+            else       { if (vec) LGC_CAND(false, true, true); else LGC_CAND(false, false, true); }
+        } else {
+            if (fused) { if (vec) LGC_CAND(true, true, false); else LGC_CAND(true, false, false); }
+            else       { if (vec) LGC_CAND(false, true, false); else LGC_CAND(false, false, false); }
+        }
 #undef LGC_CAND
+    });
 }
 
 // ------------------------------------------------------------------ gather of the candidates
