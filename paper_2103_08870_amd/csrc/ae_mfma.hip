@@ -65,7 +65,10 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
                                                       const float *__restrict__ wt, const float *__restrict__ bias,
                                                       int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
                                                       float slope) {
-    __shared__ float xs[kCiChunk * kRowPad];
+    // the last slot of the input buffer takes the stores of staging slots that hold nothing
+    // (a second pair of buffers, with one barrier per chunk, was tried: it costs a resident block per
+    // compute unit and gains nothing)
+    __shared__ float xs[kCiChunk * kRowPad + 1];
     __shared__ float ws[kCiChunk * 3 * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, half = lane >> 5, col = lane & 31;
@@ -76,36 +79,40 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
 
     // staging slots of this thread, fixed for the whole contraction: input slot e = tid + 256 i is
     // (channel e / 129, r = e % 129) with r <= 64: odd[r] = in[2 (p0 + r) - 1] and
-    // r > 64: even[r - 65] = in[2 (p0 + r - 65)]; gx = offset inside a chunk of the input (or none), lx = LDS slot
-    uint32_t gx[kXRegs], gw[kWRegs];
-    int lx[kXRegs];
+    // r > 64: even[r - 65] = in[2 (p0 + r - 65)].  gx = offset inside a chunk of the input (0 where
+    // there is nothing to load: the load is made anyway and its result dropped, no branches),
+    // lx = LDS slot, bit i of `live` = the slot holds a real input
+    // (the LDS slots and the weights' offsets are recomputed where they are used: registers are
+    // what limits the number of resident wavefronts here)
+    uint32_t gx[kXRegs], live = 0;
 #pragma unroll
     for (int i = 0; i < kXRegs; ++i) {
         const int e = tid + 256 * i;
         const int ci = e / kXPerRow, r = e % kXPerRow;
         const long long q = r <= kPosTile ? 2ll * (p0 + r) - 1 : 2ll * (p0 + (r - kPosTile - 1));
-        const bool slot = e < kCiChunk * kXPerRow;
-        gx[i] = (slot && q >= 0 && q < (long long)l_in) ? (uint32_t)(ci * (size_t)l_in + q) : 0xffffffffu;
-        lx[i] = slot ? ci * kRowPad + (r <= kPosTile ? r : kEvenOff + (r - kPosTile - 1)) : -1;
+        const bool ok = e < kCiChunk * kXPerRow && q >= 0 && q < (long long)l_in;
+        gx[i] = ok ? (uint32_t)(ci * (size_t)l_in + q) : 0u;
+        live |= (uint32_t)ok << i;
     }
-#pragma unroll
-    for (int i = 0; i < kWRegs; ++i) {
-        const int e = tid + 256 * i;
-        gw[i] = (uint32_t)((e >> 6) * c_out + co0 + (e & 63));
-    }
+    const uint32_t gw0 = (uint32_t)((tid >> 6) * c_out + co0 + (tid & 63));   // slot e = tid + 256 i: row (tid >> 6) + 4 i
     float xr[kXRegs], wr[kWRegs];
     auto fetch = [&](int c0) {
         const float *xin = in + (size_t)c0 * l_in;
-        const float *win = wt + (size_t)c0 * 3 * c_out;
+        const float *win = wt + (size_t)c0 * 3 * c_out + gw0;
 #pragma unroll
-        for (int i = 0; i < kXRegs; ++i) xr[i] = gx[i] != 0xffffffffu ? xin[gx[i]] : 0.f;
+        for (int i = 0; i < kXRegs; ++i) xr[i] = xin[gx[i]];
 #pragma unroll
-        for (int i = 0; i < kWRegs; ++i) wr[i] = win[gw[i]];
+        for (int i = 0; i < kWRegs; ++i) wr[i] = win[(size_t)(4 * i) * c_out];
     };
     auto stage = [&]() {
 #pragma unroll
-        for (int i = 0; i < kXRegs; ++i)
-            if (lx[i] >= 0) xs[lx[i]] = xr[i];
+        for (int i = 0; i < kXRegs; ++i) {
+            const int e = tid + 256 * i;
+            const int ci = e / kXPerRow, r = e % kXPerRow;
+            const int slot = e < kCiChunk * kXPerRow ? ci * kRowPad + (r <= kPosTile ? r : kEvenOff + (r - kPosTile - 1))
+                                                     : kCiChunk * kRowPad;
+            xs[slot] = ((live >> i) & 1u) ? xr[i] : 0.f;
+        }
 #pragma unroll
         for (int i = 0; i < kWRegs; ++i) ws[tid + 256 * i] = wr[i];
     };
@@ -120,15 +127,15 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
         stage();
         __syncthreads();
         if (c0 + kCiChunk < c_in) fetch(c0 + kCiChunk);   // in flight during the multiplications below
+        // contraction index of step s: lanes 0..31 take channel s / 3 of the chunk's first eight, lanes
+        // 32..63 the same of its last eight, tap s % 3: both halves read at the same constant offsets
+        // from their own base, so the reads of two steps pair into one LDS instruction
+        const float *xb = xs + half * (kCiChunk / 2) * kRowPad + wn * 32 + col;
+        const float *wb = ws + half * (kCiChunk * 3 / 2) * 64 + wm * 32 + col;
 #pragma unroll
         for (int s = 0; s < kCiChunk * 3 / 2; ++s) {
-            // contraction indices 2s (lanes 0..31) and 2s + 1 (lanes 32..63): (channel, tap) of each
-            const int kk_lo = 2 * s, kk_hi = 2 * s + 1;
-            const int off_lo = (kk_lo / 3) * kRowPad + ((kk_lo % 3) == 1 ? kEvenOff : 0) + ((kk_lo % 3) == 2 ? 1 : 0);
-            const int off_hi = (kk_hi / 3) * kRowPad + ((kk_hi % 3) == 1 ? kEvenOff : 0) + ((kk_hi % 3) == 2 ? 1 : 0);
-            const float a = ws[(2 * s + half) * 64 + wm * 32 + col];
-            const float b = xs[(half ? off_hi : off_lo) + wn * 32 + col];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+            const int off = (s / 3) * kRowPad + ((s % 3) == 1 ? kEvenOff : 0) + ((s % 3) == 2 ? 1 : 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wb[s * 64], xb[off], acc, 0, 0, 0);
         }
     }
     const uint32_t p = p0 + wn * 32 + col;
@@ -171,7 +178,7 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
                                                        const float *__restrict__ wt, const float *__restrict__ bias,
                                                        int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
                                                        float slope) {
-    __shared__ float xs[kCiChunk * kTRowPad];
+    __shared__ float xs[kCiChunk * kTRowPad + 1];
     __shared__ float ws[3 * kCiChunk * 32];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
@@ -181,15 +188,17 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
     out += (size_t)blockIdx.z * c_out * l_out;
 
     // staging slots of this thread, fixed for the whole contraction (see the convolution above)
-    uint32_t gx[kTXRegs], gw[kTWRegs];
+    uint32_t gx[kTXRegs], gw[kTWRegs], live = 0;
     int lx[kTXRegs];
 #pragma unroll
     for (int i = 0; i < kTXRegs; ++i) {
         const int e = tid + 256 * i;
         const int ci = e / (kTPosTile + 1), r = e % (kTPosTile + 1);
         const bool slot = e < kCiChunk * (kTPosTile + 1);
-        gx[i] = (slot && m0 + r < l_in) ? (uint32_t)(ci * (size_t)l_in + m0 + r) : 0xffffffffu;
-        lx[i] = slot ? ci * kTRowPad + r : -1;
+        const bool ok = slot && m0 + r < l_in;
+        gx[i] = ok ? (uint32_t)(ci * (size_t)l_in + m0 + r) : 0u;
+        live |= (uint32_t)ok << i;
+        lx[i] = slot ? ci * kTRowPad + r : kCiChunk * kTRowPad;
     }
 #pragma unroll
     for (int i = 0; i < kTWRegs; ++i) {
@@ -202,14 +211,13 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
         const float *xin = in + (size_t)c0 * l_in;
         const float *win = wt + (size_t)c0 * c_out;
 #pragma unroll
-        for (int i = 0; i < kTXRegs; ++i) xr[i] = gx[i] != 0xffffffffu ? xin[gx[i]] : 0.f;
+        for (int i = 0; i < kTXRegs; ++i) xr[i] = xin[gx[i]];
 #pragma unroll
         for (int i = 0; i < kTWRegs; ++i) wr[i] = win[gw[i]];
     };
     auto stage = [&]() {
 #pragma unroll
-        for (int i = 0; i < kTXRegs; ++i)
-            if (lx[i] >= 0) xs[lx[i]] = xr[i];
+        for (int i = 0; i < kTXRegs; ++i) xs[lx[i]] = ((live >> i) & 1u) ? xr[i] : 0.f;
 #pragma unroll
         for (int i = 0; i < kTWRegs; ++i) ws[tid + 256 * i] = wr[i];
     };
@@ -224,14 +232,16 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
         stage();
         __syncthreads();
         if (c0 + kCiChunk < c_in) fetch(c0 + kCiChunk);
+        // lanes 0..31 take the chunk's first eight input channels, lanes 32..63 its last eight
+        const float *xb = xs + half * (kCiChunk / 2) * kTRowPad + wave * 32 + col;
+        const float *wb = ws + half * (kCiChunk / 2) * 32 + col;
 #pragma unroll
         for (int s = 0; s < kCiChunk / 2; ++s) {
-            const int ci = 2 * s + half;                      // this half-wavefront's input channel
-            const float x0 = xs[ci * kTRowPad + wave * 32 + col];        // in[ci][m]
-            const float x1 = xs[ci * kTRowPad + wave * 32 + col + 1];    // in[ci][m + 1]
-            const float w0 = ws[(0 * kCiChunk + ci) * 32 + col];
-            const float w1 = ws[(1 * kCiChunk + ci) * 32 + col];
-            const float w2 = ws[(2 * kCiChunk + ci) * 32 + col];
+            const float x0 = xb[s * kTRowPad];          // in[ci][m]
+            const float x1 = xb[s * kTRowPad + 1];      // in[ci][m + 1]
+            const float w0 = wb[(0 * kCiChunk + s) * 32];
+            const float w1 = wb[(1 * kCiChunk + s) * 32];
+            const float w2 = wb[(2 * kCiChunk + s) * 32];
             even = __builtin_amdgcn_mfma_f32_32x32x2f32(w1, x0, even, 0, 0, 0);
             odd = __builtin_amdgcn_mfma_f32_32x32x2f32(w0, x1, odd, 0, 0, 0);
             odd = __builtin_amdgcn_mfma_f32_32x32x2f32(w2, x0, odd, 0, 0, 0);
