@@ -253,20 +253,24 @@ lgc_status lgc_average(lgc_ctx *ctx, const float *x, uint64_t len, int batch, fl
 
 /* LGC_OPT_SELECT_PATH: 0 = automatic (sampled-threshold fast path with the
  * exact radix path as on-device fall-back), 1 = always the exact radix path.
- * LGC_OPT_PROFILE: 1 = bracket the streaming kernel of lgc_accumulate /
- * lgc_topk / lgc_accumulate_topk with HIP events (read by lgc_profile_read). */
+ * LGC_OPT_PROFILE: 1 = bracket the streaming kernel launches of lgc_accumulate /
+ * lgc_topk / lgc_accumulate_topk, their per-layer forms and lgc_accumulate_gather
+ * with HIP events (read by lgc_profile_read). */
 typedef enum { LGC_OPT_SELECT_PATH = 0, LGC_OPT_PROFILE = 1 } lgc_option;
 lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value);
 
 /* Synchronises the device and reports, summed since the last call of
- * lgc_stats: node-selections served by the fast path, node-selections that
- * fell back to the exact path on the device, and device-side error count
- * (bounded waits that expired, scatter indices out of range).  Returns
- * LGC_EDEVICE if errors != 0. */
+ * lgc_stats: selections served by the fast path, selections that fell back
+ * to the exact path on the device (one selection = one node in lgc_topk /
+ * lgc_accumulate_topk, one sampled layer of one node in the per-layer calls),
+ * and the device-side error count (bounded waits that expired; positions out
+ * of range or out of order in lgc_scatter / lgc_gather).  Returns LGC_EDEVICE
+ * if errors != 0. */
 lgc_status lgc_stats(lgc_ctx *ctx, uint64_t *fast, uint64_t *fallback, uint64_t *errors);
 
 /* Synchronises, then returns the summed duration (ms) and the number of
- * bracketed streaming-kernel launches since the last read. */
+ * bracketed calls since the last read (a call's streaming work may be several
+ * launches: large inputs are streamed in shares of about 2 GB). */
 lgc_status lgc_profile_read(lgc_ctx *ctx, double *total_ms, uint64_t *launches);
 
 #ifdef __cplusplus

@@ -46,6 +46,23 @@ def test_null_context_is_rejected_without_touching_a_device(lib):
     assert lib.lgc_encode(None, None, None, 1, 1, None, None) == binding.LGC_EINVAL
     assert lib.lgc_set_option(None, 0, 0) == binding.LGC_EINVAL
     assert lib.lgc_latent_len(None, 100) == 0
+    # the entry points of the per-layer, ring-allreduce and parameter-server forms
+    assert lib.lgc_topk_segmented(None, None, None, None, 1, 10, None, None, None) == binding.LGC_EINVAL
+    assert lib.lgc_accumulate_topk_segmented(None, None, None, None, None, 1, 10, 0.9, None, None, None) == binding.LGC_EINVAL
+    assert lib.lgc_gather(None, None, None, 10, 1, 10, None, 1, None, None) == binding.LGC_EINVAL
+    assert lib.lgc_accumulate_gather(None, None, None, None, 10, 1, 10, 0.9, None, 1, None, None) == binding.LGC_EINVAL
+    assert lib.lgc_average(None, None, 10, 1, 0.5, None, None) == binding.LGC_EINVAL
+    assert lib.lgc_innovation(None, None, None, 1, None, None) == binding.LGC_EINVAL
+    assert lib.lgc_decode_innovation(None, None, None, None, 1, 1, None, None) == binding.LGC_EINVAL
+    assert lib.lgc_segments_total_k(None) == 0
+    h = C.c_void_p()
+    assert lib.lgc_segments_create(C.byref(h), 0, 10, 1, None, None) == binding.LGC_EINVAL and not h.value
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
 
 
 def test_create_argument_checks(lib):

@@ -281,7 +281,7 @@ def test_encode_decode(B, oracle, channels, k, batch):
     ctx.close(); ae.close()
 
 
-@pytest.mark.parametrize("k", [777, 25_600])
+@pytest.mark.parametrize("k", [1, 17, 130, 777, 2049, 25_600])
 def test_paper_size_autoencoder(B, oracle, k):
     # Table I / Table II layer shapes (with leaky-ReLU): the deep layers run on the matrix cores;
     # a short ragged input and the benchmark's k
