@@ -44,6 +44,8 @@ def parse():
     p.add_argument("--ae", choices=["config", "paper"], default="config",
                    help="config: the workload's two-layer autoencoder (default); paper: Table I / Table II layer "
                         "shapes (1-64-128-256-64-4 / 4-4-32-64-128-32-1, leaky slope 0.01), deep layers on the matrix cores")
+    p.add_argument("--graph", action="store_true",
+                   help="record two steps into a HIP graph and time its replays (steps must be even)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-kernel-events", action="store_true",
                    help="do not bracket the streaming kernel with HIP events (roofline.achieved = null)")
@@ -181,12 +183,26 @@ def main():
     torch.cuda.synchronize()
     B.lgc_stats(ctx)
     dense.zero_()
-    if not args.no_kernel_events:
+    graph = None
+    if args.graph:
+        # two consecutive steps per graph (the selection scratch alternates between two state sets);
+        # replays then cycle through two of the resident gradient sets only
+        assert args.steps % 2 == 0 and args.pattern == "ps", "--graph: even --steps, pattern ps"
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(0)
+            step(1)
+        torch.cuda.synchronize()
+    elif not args.no_kernel_events:
         B.lgc_set_option(ctx, B.LGC_OPT_PROFILE, 1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for t in range(args.steps):
-        step(args.warmup + t)
+    if graph is not None:
+        for t in range(args.steps // 2):
+            graph.replay()
+    else:
+        for t in range(args.steps):
+            step(args.warmup + t)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     B.lgc_set_option(ctx, B.LGC_OPT_PROFILE, 0)
@@ -251,6 +267,7 @@ def main():
         "whole_step_hbm_frac": ALGO_BYTES_PER_ELEM * value / (HBM_PEAK_GBS * 1e9),
         "whole_step_algorithmic_GBps": ALGO_BYTES_PER_ELEM * value / 1e9,
         "select_path": {"fast": fast, "fallback": fallback},
+        "hip_graph": bool(args.graph),
         "accumulate_topk_call": {"ms": fused_ms, "algorithmic_GBps": ALGO_BYTES_PER_ELEM * K * n / fused_ms / 1e6,
                                  "hbm_frac": ALGO_BYTES_PER_ELEM * K * n / fused_ms / 1e6 / HBM_PEAK_GBS,
                                  "note": "same buffers, measured after the timed region"},

@@ -24,6 +24,13 @@
  *    stride >= n).  batch = 1 is the single-node form.
  *  - A context owns only scratch memory.  One context serves one stream at a
  *    time and is not thread-safe; calls on one context that overlap race.
+ *  - The calls can be recorded into a HIP graph (stream capture) once the
+ *    context's scratch has grown to its size (one warm-up call of each kind):
+ *    they allocate nothing then, never synchronise and use no memset.  The
+ *    selection calls alternate between two sets of scratch state from call
+ *    to call, so a graph that is replayed must hold an EVEN number of
+ *    selection calls (lgc_topk, lgc_accumulate_topk and their per-layer forms)
+ *    per context.
  *  - Argument errors are detected on the host before anything is launched and
  *    reported as LGC_EINVAL (null pointer, n == 0, n >= 2^31, k > n, k, n or
  *    batch beyond what the context was created for, stride < n, pointers not

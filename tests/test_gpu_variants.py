@@ -155,3 +155,54 @@ def test_ring_allreduce_full_size_resnet50(B, oracle):
         for b in (L, other):
             assert same_bits(v[b], hv[b]) and same_bits(u[b], hu[b])
     ctx.close()
+
+
+def test_two_steps_in_a_hip_graph_replay_like_eager_calls(B, oracle):
+    """The calls only enqueue kernels (no allocation, no host synchronisation, no memset once the
+    scratch exists), so a stream capture of the path replays correctly.  The selection scratch
+    alternates between two state sets from call to call, so a graph must hold an even number of
+    selection calls.  Every replay is compared with the same steps made eagerly."""
+    w = synth.workload(1, n=1_200_000, nodes=2)
+    K, n, k = w.nodes, w.n, w.k
+    ae, enc, dec, _ = make_ae(B, w.ae_channels)
+    gs = [synth.gradients(w, t, device="cuda") for t in range(2)]
+
+    def make_state():
+        return dict(u=torch.zeros((K, n), device="cuda"), v=torch.zeros((K, n), device="cuda"),
+                    vals=torch.zeros((K, k), device="cuda"), idx=torch.zeros((K, k), device="cuda", dtype=torch.int32),
+                    lat=torch.zeros((K, B.lgc_latent_len(ae, k)), device="cuda"), rec=torch.zeros((K, k), device="cuda"),
+                    dense=torch.zeros((2, n), device="cuda"))
+
+    def two_steps(ctx, s):
+        for t in range(2):
+            B.lgc_accumulate_topk(ctx, gs[t], s["u"], s["v"], w.momentum, k, s["vals"], s["idx"])
+            B.lgc_encode(ctx, ae, s["vals"], s["lat"])
+            B.lgc_decode(ctx, ae, s["lat"], s["rec"])
+            B.lgc_scatter(ctx, s["rec"], s["idx"], 1.0 / K, s["dense"][t])
+
+    ctx_e, ctx_g = B.Context(n, k, K), B.Context(n, k, K)
+    eager, graphed = make_state(), make_state()
+    two_steps(ctx_g, graphed)                 # warm-up outside the capture: grows the activation scratch
+    for key in graphed:
+        graphed[key].zero_()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        two_steps(ctx_g, graphed)             # recorded, not run
+    for replay in range(3):
+        graph.replay()
+        two_steps(ctx_e, eager)
+        torch.cuda.synchronize()
+        for key in eager:                     # u, v carry over from replay to replay; dense accumulates
+            assert torch.equal(eager[key].view(torch.int32), graphed[key].view(torch.int32)), (replay, key)
+    assert B.lgc_stats(ctx_g)[2] == 0 and B.lgc_stats(ctx_e)[2] == 0
+    # and the eager side agrees with the oracle on the last selection (so both do)
+    hu = np.zeros((K, n), np.float32); hv = np.zeros((K, n), np.float32)
+    for rep in range(3):
+        for t in range(2):
+            gh = gs[t].cpu().numpy()
+            for b in range(K):
+                oracle.accumulate(gh[b], hu[b], hv[b], w.momentum)
+                ovals, oidx = oracle.topk(hv[b], hu[b], k)
+    assert (graphed["idx"][K - 1].cpu().numpy().astype(np.uint32) == oidx).all() and same_bits(graphed["vals"][K - 1], ovals)
+    ctx_e.close(); ctx_g.close(); ae.close()
