@@ -61,10 +61,15 @@ constexpr int kXPerRow = 2 * kPosTile + 1;                           // 129 inpu
 constexpr int kXRegs = (kCiChunk * kXPerRow + 255) / 256;            // 9
 constexpr int kWRegs = kCiChunk * 3 * 64 / 256;                      // 12
 
+// TAIL: a following kernel-1 / stride-1 layer from these 64 channels (c_out == 64: one block holds all of
+// them for its positions) to tail_c <= 4 channels is applied to the activated tile before anything is
+// stored; `out` is then that layer's output [b][tail_c][l_out] (Table I: conv4 256->64 and conv5 64->4).
+template <bool TAIL>
 __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ in, float *__restrict__ out,
                                                       const float *__restrict__ wt, const float *__restrict__ bias,
                                                       int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
-                                                      float slope) {
+                                                      float slope, const float *__restrict__ tail_w /*[tail_c][64]*/,
+                                                      const float *__restrict__ tail_b, int tail_c, int tail_act) {
     // the last slot of the input buffer takes the stores of staging slots that hold nothing
     // (a second pair of buffers, with one barrier per chunk, was tried: it costs a resident block per
     // compute unit and gains nothing)
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
     const uint32_t p0 = blockIdx.x * kPosTile;
     const int co0 = blockIdx.y * 64;
     in += (size_t)blockIdx.z * c_in * l_in;
-    out += (size_t)blockIdx.z * c_out * l_out;
+    out += (size_t)blockIdx.z * (TAIL ? tail_c : c_out) * l_out;
 
     // staging slots of this thread, fixed for the whole contraction: input slot e = tid + 256 i is
     // (channel e / 129, r = e % 129) with r <= 64: odd[r] = in[2 (p0 + r) - 1] and
@@ -139,24 +144,64 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
         }
     }
     const uint32_t p = p0 + wn * 32 + col;
+    if (!TAIL) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int co = co0 + wm * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+            if (p < l_out) {
+                const float y = acc[r] + bias[co];
+                out[(size_t)co * l_out + p] = act ? leaky_m(y, slope) : y;
+            }
+        }
+        return;
+    }
+    // this lane's 16 channels of position p, activated; their weighted sums for the tail's channels;
+    // then the other half-wavefront's 16 channels, and through LDS the other 32 channels (wm)
+    float part[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        const int co = co0 + wm * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-        if (p < l_out) {
-            const float y = acc[r] + bias[co];
-            out[(size_t)co * l_out + p] = act ? leaky_m(y, slope) : y;
-        }
+        const int co = wm * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+        const float y0 = acc[r] + bias[co];
+        const float y = act ? leaky_m(y0, slope) : y0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (c < tail_c) part[c] = fmaf(tail_w[c * 64 + co], y, part[c]);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) part[c] += __shfl_xor(part[c], 32, 64);
+    __syncthreads();                        // everyone is done with the staging buffers
+    float *red = xs;                        // [wm][c][64 positions]
+    if (half == 0) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) red[(wm * 4 + c) * 64 + wn * 32 + col] = part[c];
+    }
+    __syncthreads();
+    const int c = tid >> 6, pp = tid & 63;
+    if (c < tail_c && p0 + pp < l_out) {
+        const float z = tail_b[c] + red[c * 64 + pp] + red[(4 + c) * 64 + pp];
+        out[(size_t)c * l_out + p0 + pp] = tail_act ? leaky_m(z, slope) : z;
     }
 }
 
-bool launch_conv3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
-                         bool act, float slope, hipStream_t st) {
+bool conv3s2_mfma_covers(const LayerDev &l, uint32_t l_in) {
     if (!l.wt || l.ksize != 3 || l.stride != 2 || l.c_in % kCiChunk != 0 || l.c_out % 64 != 0) return false;
-    if ((uint64_t)l_in * kCiChunk >= (1ull << 32) || (uint64_t)l.c_in * 3 * l.c_out >= (1ull << 32)) return false;   // 32-bit offsets inside a chunk
+    return (uint64_t)l_in * kCiChunk < (1ull << 32) && (uint64_t)l.c_in * 3 * l.c_out < (1ull << 32);   // 32-bit offsets inside a chunk
+}
+
+// tail (nullable): a kernel-1 / stride-1 layer from l.c_out == 64 to at most 4 channels, applied in the same
+// launch; `out` is then the tail's output
+bool launch_conv3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
+                         bool act, float slope, hipStream_t st, const LayerDev *tail, bool tail_act) {
+    if (!conv3s2_mfma_covers(l, l_in)) return false;
+    if (tail && !(tail->ksize == 1 && tail->stride == 1 && tail->c_in == 64 && l.c_out == 64 && tail->c_out <= 4)) return false;
     if (l_out == 0) return true;
     dim3 grid((l_out + kPosTile - 1) / kPosTile, l.c_out / 64, batch);
-    hipLaunchKernelGGL(k_conv3s2_mfma, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
-                       (int)act, slope);
+    if (tail)
+        hipLaunchKernelGGL(k_conv3s2_mfma<true>, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                           (int)act, slope, tail->w, tail->b, tail->c_out, (int)tail_act);
+    else
+        hipLaunchKernelGGL(k_conv3s2_mfma<false>, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                           (int)act, slope, nullptr, nullptr, 0, 0);
     return true;
 }
 
@@ -174,10 +219,15 @@ constexpr int kTRowPad = 132;
 constexpr int kTXRegs = (kCiChunk * (kTPosTile + 1) + 255) / 256;    // 9
 constexpr int kTWRegs = 3 * kCiChunk * 32 / 256;                      // 6
 
+// TAIL: a following kernel-1 / stride-1 layer from these 32 channels (c_out == 32) to one channel is applied
+// to the activated tiles before anything is stored; `out` is then [b][1][l_out] (Table II: deconv5 128->32
+// and the last layer 32->1).
+template <bool TAIL>
 __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__ in, float *__restrict__ out,
                                                        const float *__restrict__ wt, const float *__restrict__ bias,
                                                        int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
-                                                       float slope) {
+                                                       float slope, const float *__restrict__ tail_w /*[32]*/,
+                                                       const float *__restrict__ tail_b, int tail_act) {
     __shared__ float xs[kCiChunk * kTRowPad + 1];
     __shared__ float ws[3 * kCiChunk * 32];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -185,7 +235,7 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
     const uint32_t m0 = blockIdx.x * kTPosTile;
     const int co0 = blockIdx.y * 32;
     in += (size_t)blockIdx.z * c_in * l_in;
-    out += (size_t)blockIdx.z * c_out * l_out;
+    out += (size_t)blockIdx.z * (TAIL ? 1 : c_out) * l_out;
 
     // staging slots of this thread, fixed for the whole contraction (see the convolution above)
     uint32_t gx[kTXRegs], gw[kTWRegs], live = 0;
@@ -248,6 +298,26 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
         }
     }
     const uint32_t m = m0 + wave * 32 + col;
+    if (TAIL) {
+        // weighted sums over this lane's 16 channels, then the other half-wavefront's 16
+        float se = 0.f, so = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int co = (r >> 2) * 8 + half * 4 + (r & 3);
+            const float bv = bias[co], wv = tail_w[co];
+            const float ye = even[r] + bv, yo = odd[r] + bv;
+            se = fmaf(wv, act ? leaky_m(ye, slope) : ye, se);
+            so = fmaf(wv, act ? leaky_m(yo, slope) : yo, so);
+        }
+        se += __shfl_xor(se, 32, 64);
+        so += __shfl_xor(so, 32, 64);
+        const uint64_t q = 2ull * m + half;              // lanes 0..31 store the even, lanes 32..63 the odd output
+        if (q < l_out) {
+            const float z = tail_b[0] + (half ? so : se);
+            out[q] = tail_act ? leaky_m(z, slope) : z;
+        }
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int co = co0 + (r >> 2) * 8 + half * 4 + (r & 3);
@@ -264,16 +334,22 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
     }
 }
 
+// tail (nullable): a kernel-1 / stride-1 layer from l.c_out == 32 channels to one, applied in the same launch
 bool launch_convt3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
-                          bool act, float slope, hipStream_t st) {
+                          bool act, float slope, hipStream_t st, const LayerDev *tail, bool tail_act) {
     if (!l.wt || l.ksize != 3 || l.stride != 2 || l.c_in % kCiChunk != 0 || l.c_out % 32 != 0) return false;
     if ((uint64_t)l_in * kCiChunk >= (1ull << 32) || (uint64_t)l.c_in * 3 * l.c_out >= (1ull << 32)) return false;   // 32-bit offsets inside a chunk
+    if (tail && !(tail->ksize == 1 && tail->stride == 1 && tail->c_in == 32 && l.c_out == 32 && tail->c_out == 1)) return false;
     if (l_out == 0) return true;
     // input positions that reach an output: m < ceil(l_out / 2) (and the odd tap of m = that - 1 reads m + 1)
     const uint32_t m_count = (l_out + 1) / 2;
     dim3 grid((m_count + kTPosTile - 1) / kTPosTile, l.c_out / 32, batch);
-    hipLaunchKernelGGL(k_convt3s2_mfma, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
-                       (int)act, slope);
+    if (tail)
+        hipLaunchKernelGGL(k_convt3s2_mfma<true>, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                           (int)act, slope, tail->w, tail->b, (int)tail_act);
+    else
+        hipLaunchKernelGGL(k_convt3s2_mfma<false>, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                           (int)act, slope, nullptr, nullptr, 0);
     return true;
 }
 

@@ -570,6 +570,16 @@ extern "C" lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *va
     const float *cur = vals;
     for (size_t l = 0; l < nl; ++l) {
         const bool last = l + 1 == nl;
+        if (l + 1 < nl) {   // a deep layer and the kernel-1 layer after it in one launch, where the shapes allow
+            const bool next_last = l + 2 == nl;
+            float *dst2 = next_last ? latent : ctx->act[(l + 1) & 1];
+            if (launch_conv3s2_mfma(cur, dst2, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, true, ae->slope,
+                                    st, &ae->enc_dev[l + 1], !next_last)) {
+                cur = dst2;
+                ++l;
+                continue;
+            }
+        }
         float *dst = last ? latent : ctx->act[l & 1];
         if (!launch_conv3s2_mfma(cur, dst, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, !last, ae->slope, st))
             launch_conv1d(cur, dst, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, !last, ae->slope, st);
@@ -611,6 +621,17 @@ static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent
     const float *cur = latent;
     for (size_t l = 0; l < nl; ++l) {
         const bool last = l + 1 == nl;
+        if (l + 1 < nl && !innov) {   // a deep layer and the kernel-1 layer after it in one launch, where the shapes allow
+            const bool next_last = l + 2 == nl;
+            float *dst2 = next_last ? rec : ctx->act[(l + 1) & 1];
+            if (launch_convt3s2_mfma(cur, dst2, ae->dec_dev[l], (uint32_t)in_len, (uint32_t)out_len[l], batch, true, ae->slope,
+                                     st, &ae->dec_dev[l + 1], !next_last)) {
+                cur = dst2;
+                in_len = out_len[l + 1];
+                ++l;
+                continue;
+            }
+        }
         float *dst = last ? rec : ctx->act[l & 1];
         const float *extra = last ? innov : nullptr;
         if (extra || !launch_convt3s2_mfma(cur, dst, ae->dec_dev[l], (uint32_t)in_len, (uint32_t)out_len[l], batch, !last,

@@ -155,10 +155,12 @@ bool launch_scatter_nodes(const float *vals, const uint32_t *idx, uint32_t k, in
 
 // ae_mfma.hip: deep kernel-3 / stride-2 layers on the matrix cores; false = layer not covered (nothing launched)
 void launch_weights_contraction_major(const float *w, float *wt, int c_in, int c_out, bool transposed, hipStream_t st);
+// tail (nullable): the kernel-1 / stride-1 layer that follows, applied in the same launch when its shape allows
+// (64 -> at most 4 channels after a convolution, 32 -> 1 after a transposed one); `out` is then the tail's output
 bool launch_conv3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
-                         bool act, float slope, hipStream_t st);
+                         bool act, float slope, hipStream_t st, const LayerDev *tail = nullptr, bool tail_act = false);
 bool launch_convt3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
-                          bool act, float slope, hipStream_t st);
+                          bool act, float slope, hipStream_t st, const LayerDev *tail = nullptr, bool tail_act = false);
 void launch_gather_at(float *v, float *u, uint64_t stride, uint32_t n, int batch, const uint32_t *idx, uint32_t k,
                       float *out, Stats *stats, hipStream_t st);
 void launch_average(const float *x, uint32_t len, int batch, float scale, float *out, hipStream_t st);
