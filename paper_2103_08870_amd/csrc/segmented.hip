@@ -169,11 +169,14 @@ void launch_seg_estimate(const SelArgs &a, int batch, bool fused, bool vec, hipS
 // The source is read four times (three digit passes and the output pass); a segment or a run of
 // candidates is small enough to stay in the L2 after the first.  The loops are kept rolled: an
 // unrolled, register-cached variant was an order of magnitude slower (instruction fetch).
+constexpr int kSelKeep = 8;                // 16-byte groups per thread that the register-cached path holds
 constexpr int kSelThreads = 512;          // most segments and candidate runs are a few thousand entries
 
 // DENSE: instead of the compact (position, value) output and the clearing of v and u, every entry p
 // of the source gets dense[p] = its value if kept, +0 otherwise (the innovation component).
-template <bool ALIGNED, bool DENSE>
+// SMALL: the source spans at most kSelKeep rounds (16 K entries from begin & ~3 on): it is read once
+// and kept in registers for all four sweeps (the layers' candidate runs and the small layers).
+template <bool ALIGNED, bool DENSE, bool SMALL>
 __device__ __forceinline__ void select_in_block(const uint32_t *__restrict__ bits, const uint32_t *__restrict__ pos,
                                                 const uint32_t begin, const uint32_t end, const uint32_t k,
                                                 float *__restrict__ v, float *__restrict__ u,
@@ -203,7 +206,23 @@ __device__ __forceinline__ void select_in_block(const uint32_t *__restrict__ bit
     };
     auto inside = [&](uint32_t g, int c) { const uint32_t p = a0 + (g << 2) + c; return p >= begin && p < end; };
 
+    u4 keep[SMALL ? kSelKeep : 1];
+    if (SMALL) {
+#pragma unroll
+        for (int r = 0; r < kSelKeep; ++r) keep[r] = load_group(r * T + tid);
+    }
     auto each_key = [&](auto f) {
+        if (SMALL) {
+#pragma unroll
+            for (int r = 0; r < kSelKeep; ++r) {
+                if ((uint32_t)r < rounds) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (inside(r * T + tid, c)) f(keep[r][c] & 0x7fffffffu);
+                }
+            }
+            return;
+        }
         for (uint32_t r0 = 0; r0 < rounds; r0 += 4) {        // four loads in flight
             u4 x[4];
 #pragma unroll
@@ -222,10 +241,7 @@ __device__ __forceinline__ void select_in_block(const uint32_t *__restrict__ bit
 
     // ordered output: entries are enumerated round by round, thread by thread, c = 0..3
     uint32_t run_g = 0, run_e = 0;                           // kept-or-tied entries of the earlier rounds
-    u4 x = load_group(tid);
-    for (uint32_t r = 0; r < rounds; ++r) {
-        const uint32_t g = r * T + tid;
-        const u4 nx = load_group(g + T);                 // next round's group, in flight during this one
+    auto emit_round = [&](const u4 x, const uint32_t g) {
         bool fg[4], fe[4];
         uint32_t lg = 0, le = 0, tg = 0, te = 0;
 #pragma unroll
@@ -265,7 +281,18 @@ __device__ __forceinline__ void select_in_block(const uint32_t *__restrict__ bit
             }
             cg += fg[c]; ce += fe[c];
         }
-        x = nx;
+    };
+    if (SMALL) {
+#pragma unroll
+        for (int r = 0; r < kSelKeep; ++r)
+            if ((uint32_t)r < rounds) emit_round(keep[r], r * T + tid);   // block-uniform condition
+    } else {
+        u4 x = load_group(tid);
+        for (uint32_t r = 0; r < rounds; ++r) {
+            const u4 nx = load_group((r + 1) * T + tid);     // next round's group, in flight during this one
+            emit_round(x, r * T + tid);
+            x = nx;
+        }
     }
     // every thread holds the block's totals: the selection must add up to k
     if (tid == 0 && run_g + (run_e < quota ? run_e : quota) != k) atomicAdd(&stats->errors, 1u);
@@ -324,10 +351,18 @@ __global__ __launch_bounds__(kSelThreads) void k_seg_select(SelArgs a) {
         }
         if (threadIdx.x == 0) atomicAdd(from_list ? &a.stats->fast : &a.stats->fallback, 1u);
     }
-    if (from_list)
-        select_in_block<true, false>(cval, cidx, p0, p1, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
-    else
-        select_in_block<VEC, false>((const uint32_t *)v, nullptr, lo, hi, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+    constexpr uint32_t kSmall = (uint32_t)kSelKeep * kSelThreads * 4u;
+    if (from_list) {
+        if (p1 - (p0 & ~3u) <= kSmall)
+            select_in_block<true, false, true>(cval, cidx, p0, p1, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+        else
+            select_in_block<true, false, false>(cval, cidx, p0, p1, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+    } else {
+        if (hi - (lo & ~3u) <= kSmall)
+            select_in_block<VEC, false, true>((const uint32_t *)v, nullptr, lo, hi, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+        else
+            select_in_block<VEC, false, false>((const uint32_t *)v, nullptr, lo, hi, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+    }
 }
 
 // Innovation component (Alg. 1: threshold_inv, mask_inv; Sec. IV-C): per segment of the vector of
@@ -347,8 +382,12 @@ __global__ __launch_bounds__(kSelThreads) void k_innovation(const float *__restr
         for (uint32_t p = lo + threadIdx.x; p < hi; p += kSelThreads) dst[p] = 0.0f;
         return;
     }
-    select_in_block<VEC, true>((const uint32_t *)src, nullptr, lo, hi, k, nullptr, nullptr, nullptr, nullptr, dst, stats,
-                               hist, wave_tmp, res, sh_g, sh_e);
+    if (hi - (lo & ~3u) <= (uint32_t)kSelKeep * kSelThreads * 4u)
+        select_in_block<VEC, true, true>((const uint32_t *)src, nullptr, lo, hi, k, nullptr, nullptr, nullptr, nullptr, dst, stats,
+                                         hist, wave_tmp, res, sh_g, sh_e);
+    else
+        select_in_block<VEC, true, false>((const uint32_t *)src, nullptr, lo, hi, k, nullptr, nullptr, nullptr, nullptr, dst, stats,
+                                          hist, wave_tmp, res, sh_g, sh_e);
 }
 
 void launch_innovation(const float *vals, float *out, uint32_t n, int batch, uint32_t n_seg, const uint32_t *seg_off,
