@@ -166,9 +166,9 @@ void launch_seg_estimate(const SelArgs &a, int batch, bool fused, bool vec, hipS
 // The block's source: `bits` holds raw fp32 patterns at positions [begin, end); the position of
 // entry p in the node's vector is pos[p] (candidate list) or p itself (pos == nullptr: the
 // source is v).  ALIGNED: bits + (begin & ~3) is 16-byte aligned (vector loads).
-// The source is read four times (three digit passes and the output pass); a segment or a run of
-// candidates is small enough to stay in the L2 after the first.  The loops are kept rolled: an
-// unrolled, register-cached variant was an order of magnitude slower (instruction fetch).
+// A long source is read four times (three digit passes and the output pass; it stays in the L2
+// after the first) in rolled loops: unrolling those for 64 K entries was an order of magnitude
+// slower (instruction fetch).
 constexpr int kSelKeep = 8;                // 16-byte groups per thread that the register-cached path holds
 constexpr int kSelThreads = 512;          // most segments and candidate runs are a few thousand entries
 
