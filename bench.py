@@ -214,16 +214,21 @@ def main():
     value = K * n * args.steps / dt
 
     # outside the timed region: every entry point on its own, same buffers, all nodes per call
-    def timed(fn):
+    def timed_n(fn, count):
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ev0.record()
-        for t in range(args.steps):
+        for t in range(count):
             fn(t)
         ev1.record()
         torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1) / args.steps
+        return ev0.elapsed_time(ev1) / count
+
+    def timed(fn):
+        return timed_n(fn, args.steps)
 
     fused_ms = timed(select)
+    # spread of the fused call: five more repeats of a fifth of the steps each
+    reps = sorted(timed_n(select, max(2, args.steps // 5)) for _ in range(5))
     stages = {
         "a1_accumulate": timed(lambda t: B.lgc_accumulate(ctx, grads[t % sets], u, v, w.momentum)),
         "a2_topk": timed((lambda t: B.lgc_topk(ctx, v, u, k, vals, idx)) if seg is None else
@@ -270,6 +275,7 @@ def main():
         "hip_graph": bool(args.graph),
         "accumulate_topk_call": {"ms": fused_ms, "algorithmic_GBps": ALGO_BYTES_PER_ELEM * K * n / fused_ms / 1e6,
                                  "hbm_frac": ALGO_BYTES_PER_ELEM * K * n / fused_ms / 1e6 / HBM_PEAK_GBS,
+                                 "ms_median_of_5": reps[2], "ms_min_of_5": reps[0],
                                  "note": "same buffers, measured after the timed region"},
         "stages_ms": {name: round(ms, 5) for name, ms in stages.items()},
         "autoencoder": ae_report(enc, dec, k, K if args.pattern == "ps" else 1, K, stages, args.ae),
