@@ -33,10 +33,11 @@ constexpr int kRadixBins = 2048;
 constexpr int kRow = 1024;
 constexpr int kRowWords = 16;
 
-// The streaming kernels are launched over at most this many rows (about 2 GB of g, u, v traffic):
-// measured on MI355X, launches that move more sustain 70-72 % of the HBM peak instead of 75-77 %,
-// whatever the split (more nodes per launch or longer vectors).
-constexpr uint32_t kRowsPerLaunch = 96 * 1024;
+// The streaming kernels are launched over at most this many rows (a little over 2 GB of g, u, v
+// traffic; the ResNet50-sized workload, 4 x 25 000 rows, is one launch): measured on MI355X,
+// launches that move 3.5 GB and more sustain 70-72 % of the HBM peak instead of 75-77 %, whatever
+// the split (more nodes per launch or longer vectors).
+constexpr uint32_t kRowsPerLaunch = 104 * 1024;
 
 // Per-node selection state, device memory.  It lives in a "state set" together with the
 // histograms and look-back status words; there are two sets, used by alternate calls, and each

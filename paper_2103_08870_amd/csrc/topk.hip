@@ -59,19 +59,23 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(const float *__restrict__
     }
 }
 
-// Calls launch(node0, nodes, row_begin, row_end) for shares of at most kRowsPerLaunch rows:
+// Calls launch(node0, nodes, row_begin, row_end) for equal shares of at most kRowsPerLaunch rows:
 // several whole nodes per launch while they fit, else one node in row ranges.
 template <typename F>
 static void for_each_share(uint32_t nrows, int batch, F launch) {
     if ((uint64_t)nrows * batch <= kRowsPerLaunch) { launch(0u, batch, 0u, nrows); return; }
     if (nrows <= kRowsPerLaunch) {
-        const int per = (int)(kRowsPerLaunch / nrows);
+        const int fit = (int)(kRowsPerLaunch / nrows);              // nodes that fit one launch
+        const int launches = (batch + fit - 1) / fit;
+        const int per = (batch + launches - 1) / launches;          // evened out
         for (int b = 0; b < batch; b += per) launch((uint32_t)b, batch - b < per ? batch - b : per, 0u, nrows);
         return;
     }
+    const uint32_t ranges = (nrows + kRowsPerLaunch - 1) / kRowsPerLaunch;
+    const uint32_t per = ((nrows + ranges - 1) / ranges + (uint32_t)kWaves - 1) / kWaves * kWaves;   // whole blocks
     for (int b = 0; b < batch; ++b)
-        for (uint32_t r = 0; r < nrows; r += kRowsPerLaunch)
-            launch((uint32_t)b, 1, r, nrows - r < kRowsPerLaunch ? nrows : r + kRowsPerLaunch);
+        for (uint32_t r = 0; r < nrows; r += per)
+            launch((uint32_t)b, 1, r, nrows - r < per ? nrows : r + per);
 }
 
 void launch_accumulate(const float *g, float *u, float *v, uint32_t n, int batch, uint64_t stride,
