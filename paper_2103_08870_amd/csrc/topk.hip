@@ -362,7 +362,7 @@ __device__ __forceinline__ uint32_t block_sum_1024(uint32_t x, uint32_t *tmp /*[
 // adds the block's count to the node's total.  The block's part of the bitmap is staged in LDS;
 // the work is balanced over the threads by output position (binary search of the owning row,
 // then of the bit inside the row), whatever the spread of the candidates.
-constexpr int kGatherRows = 256;
+constexpr int kGatherRows = 128;
 
 template <bool HIST>
 __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
