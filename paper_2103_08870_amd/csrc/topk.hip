@@ -597,15 +597,24 @@ __global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
     bool ok = total >= a.k && total <= a.cap;
     const uint32_t n4 = ok ? (total + 3) / 4 : 0u;   // 16-byte groups (the list's capacity is a multiple of 4)
 
-    // independent loads first: the keys, my four positions, the fine histogram
+    // independent loads first: the keys, my four positions and values, the fine histogram.
+    // The registers hold keys (sign cleared); entries past the end of the list hold 0xffffffff,
+    // which no key equals and which lies in no histogram bin.
+    auto as_keys = [&](u4 x, uint32_t g4) -> u4 {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) x[c] = g4 * 4 + c < total ? (x[c] & 0x7fffffffu) : 0xffffffffu;
+        return x;
+    };
     u4 keys[kKeep];
 #pragma unroll
     for (int r = 0; r < kKeep; ++r) {
         const uint32_t g4 = r * 1024 + tid;
         keys[r] = g4 < n4 ? *(const u4 *)(cval + (size_t)g4 * 4) : (u4){0u, 0u, 0u, 0u};
     }
-    u4 ci = {0, 0, 0, 0};
-    if (ok && e0 < total) ci = *(const u4 *)(cidx + e0);
+    u4 ci = {0, 0, 0, 0}, cv = {0u, 0u, 0u, 0u};
+    if (ok && e0 < total) { ci = *(const u4 *)(cidx + e0); cv = *(const u4 *)(cval + e0); }
+#pragma unroll
+    for (int r = 0; r < kKeep; ++r) keys[r] = as_keys(keys[r], r * 1024 + tid);
     for (int i = tid; i < kFineBins; i += 1024) hist[i] = a.fine_hist[node * kFineBins + i];
     const uint32_t t_est = s->t_est;
     __syncthreads();
@@ -619,19 +628,20 @@ __global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
         if (ok) {
             for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
             __syncthreads();
-            auto tally = [&](uint32_t key, uint32_t pos) {
-                const uint32_t d = (key & 0x7fffffffu) - t_est;
-                if (pos < total && (d >> kFineShift) == bin) atomicAdd(&hist[d & ((1u << kFineShift) - 1)], 1u);
+            const uint32_t bin_base = t_est + (bin << kFineShift);   // keys of the bin: bin_base .. bin_base + 4095
+            auto tally = [&](uint32_t key) {
+                const uint32_t d = key - bin_base;
+                if (d < (1u << kFineShift)) atomicAdd(&hist[d], 1u);
             };
 #pragma unroll
             for (int r = 0; r < kKeep; ++r) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) tally(keys[r][c], (r * 1024 + tid) * 4 + c);
+                for (int c = 0; c < 4; ++c) tally(keys[r][c]);
             }
             for (uint32_t g4 = kKeep * 1024 + tid; g4 < n4; g4 += 1024) {
-                const u4 x = *(const u4 *)(cval + (size_t)g4 * 4);
+                const u4 x = as_keys(*(const u4 *)(cval + (size_t)g4 * 4), g4);
 #pragma unroll
-                for (int c = 0; c < 4; ++c) tally(x[c], g4 * 4 + c);
+                for (int c = 0; c < 4; ++c) tally(x[c]);
             }
             __syncthreads();
             find_rank_bin<kFineBins>(hist, need, wave_tmp, res);
@@ -647,25 +657,19 @@ __global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
     if (!ok || base >= total) return;
 
     // selected-or-tied counts among the candidates before mine: groups r*1024 + tid, r < blockIdx.x
+    // (all of those lie before the end of the list, so none is the 0xffffffff filler)
     uint32_t pg = 0, pe = 0;
-    u4 cv = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int r = 0; r < kKeep; ++r) {
         if (r < (int)blockIdx.x) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) { const uint32_t key = keys[r][c] & 0x7fffffffu; pg += key > thr; pe += key == thr; }
-        } else if (r == (int)blockIdx.x) {
-            cv = keys[r];
+            for (int c = 0; c < 4; ++c) { pg += keys[r][c] > thr; pe += keys[r][c] == thr; }
         }
     }
-    for (uint32_t r = kKeep; r <= blockIdx.x; ++r) {
+    for (uint32_t r = kKeep; r < blockIdx.x; ++r) {
         const u4 x = *(const u4 *)(cval + (size_t)(r * 1024 + tid) * 4);
-        if (r < blockIdx.x) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) { const uint32_t key = x[c] & 0x7fffffffu; pg += key > thr; pe += key == thr; }
-        } else {
-            cv = x;
-        }
+        for (int c = 0; c < 4; ++c) { const uint32_t key = x[c] & 0x7fffffffu; pg += key > thr; pe += key == thr; }
     }
     pg = wave_sum(pg); pe = wave_sum(pe);
     uint32_t lg = 0, le = 0, tg = 0, te = 0;
