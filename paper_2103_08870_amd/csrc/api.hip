@@ -27,7 +27,8 @@ struct lgc_ctx {
     int cur = 0;                      // set the next call will use (it is clean)
     int cus = 1;                      // compute units of the device
     uint32_t rows = 0, status_cand_stride = 0, status_exact_stride = 0;
-    uint32_t *samples = nullptr, *row_count = nullptr;
+    uint32_t *samples = nullptr, *row_count = nullptr, *row_super = nullptr;
+    uint32_t supers = 0;
     unsigned long long *bitmap = nullptr;
     uint32_t *cand_idx = nullptr, *cand_val = nullptr;
     float *act[2] = {nullptr, nullptr};  // autoencoder activations (ping-pong), grown on demand
@@ -185,6 +186,7 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     a.status_exact = (unsigned long long *)(cur + L.status_exact);
     a.next_state = c->state[c->cur ^ 1]; a.next_words = c->state_words;
     a.samples = c->samples; a.row_count = c->row_count; a.bitmap = c->bitmap;
+    a.row_super = c->row_super; a.supers = c->supers;
     a.cand_idx = c->cand_idx; a.cand_val = c->cand_val;
     a.out_vals = out_vals; a.out_idx = out_idx;
     return a;
@@ -277,6 +279,8 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
     const size_t o_state1 = carve(L.words * 4);
     const size_t o_samples = carve(B * kSample * 4);
     const size_t o_rcount = carve(B * c->rows * 4);
+    c->supers = (c->rows + kSuperRows - 1) / kSuperRows;
+    const size_t o_rsuper = carve(B * c->supers * 4);
     const size_t o_bitmap = carve(B * (size_t)c->rows * kRowWords * 8);
     const size_t o_cidx = carve(B * (size_t)c->cap * 4);
     const size_t o_cval = carve(B * (size_t)c->cap * 4);
@@ -299,6 +303,7 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
     c->state[1] = (uint32_t *)(base + o_state1);
     c->samples = (uint32_t *)(base + o_samples);
     c->row_count = (uint32_t *)(base + o_rcount);
+    c->row_super = (uint32_t *)(base + o_rsuper);
     c->bitmap = (unsigned long long *)(base + o_bitmap);
     c->cand_idx = (uint32_t *)(base + o_cidx);
     c->cand_val = (uint32_t *)(base + o_cval);

@@ -32,6 +32,7 @@ constexpr int kRadixBins = 2048;
 // word 4s+j, bit l  <->  element  row*1024 + 256 s + 4 l + j   (s, j in 0..3, l = lane)
 constexpr int kRow = 1024;
 constexpr int kRowWords = 16;
+constexpr uint32_t kSuperRows = 8192;           // rows per group whose candidates are summed ahead of the gather
 
 // The streaming kernels are launched over at most this many rows (a little over 2 GB of g, u, v
 // traffic; the ResNet50-sized workload, 4 x 25 000 rows, is one launch): measured on MI355X,
@@ -56,9 +57,8 @@ static_assert(sizeof(Sel) == 64, "Sel is one 64-byte record");
 // live in a cache line of their own: a line that receives atomics from several XCDs must not
 // also receive plain stores in the same kernel (each XCD has its own, non-coherent L2).
 struct Ctr {
-    uint32_t ticket;      // chunk tickets of the look-back compaction over the candidates
     uint32_t barrier;     // exact path: arrivals at the node's barrier
-    uint32_t pad[30];
+    uint32_t pad[31];
 };
 static_assert(sizeof(Ctr) == 128, "Ctr is one 128-byte line");
 
@@ -79,7 +79,7 @@ struct SelArgs {
     uint32_t rank;    // rank of the sample's order statistic used as estimate
     uint32_t cap;     // capacity of the gathered candidate list, per node
     uint32_t rows;    // bitmap rows per node (stride of row_count; bitmap stride is rows * kRowWords)
-    uint32_t status_cand_stride, status_exact_stride;  // status words per node
+    uint32_t status_cand_stride, status_exact_stride;  // 64-bit words per node: chunk counts of the candidate list, look-back status
     uint32_t spin_limit;      // bound of the look-back wait
     int force;                // exact path chosen by the host (ignore fast_ok)
     Stats *stats;
@@ -90,7 +90,7 @@ struct SelArgs {
     uint32_t *fine_hist;      // [batch][kFineBins]
     uint32_t *level2_hist;    // [batch][kFineBins]
     uint32_t *radix_hist;     // [batch][3][kRadixBins]
-    unsigned long long *status_cand;   // look-back status of the output pass over the candidates
+    unsigned long long *status_cand;   // per 4096-candidate chunk of a long list: keys above T* (high half), equal to T* (low half)
     unsigned long long *status_exact;  // look-back status of the exact pass over v
     // state set of the next call, cleared by this one
     uint32_t *next_state;
@@ -98,6 +98,8 @@ struct SelArgs {
     // bulk scratch
     uint32_t *samples;        // [batch][kSample]
     uint32_t *row_count;      // [batch][rows]  candidates per row
+    uint32_t *row_super;      // [batch][supers] candidates per group of kSuperRows rows (vectors of more than one group)
+    uint32_t supers;
     unsigned long long *bitmap;  // [batch][rows][kRowWords]
     uint32_t *cand_idx;       // [batch][cap]  gathered, index-ordered
     uint32_t *cand_val;

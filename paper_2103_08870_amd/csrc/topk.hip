@@ -17,15 +17,14 @@
 //  The candidate pass writes one flag bit per element (a dense bitmap, full cache lines) and a
 //  count per row of 1024, so the streaming kernel has no communication between wavefronts at
 //  all and no scattered stores; a small gather kernel lists the flagged elements in index order.
-//  The two output compactions (over the candidates; over v in the exact path) use one look-back
-//  chain over 4096-element chunks; chunk ids are handed out by an atomic ticket, so a chunk
-//  only ever waits for chunks that already run.
+//  The output over the candidates needs no communication between blocks either: short lists are
+//  read whole by every block, long lists are counted per 4096-candidate chunk by one kernel and
+//  written by the next.  Only the exact path's compaction of v uses a look-back chain over
+//  4096-element chunks, by blocks that are all resident.
 
 #include "device_helpers.h"
 
 namespace lgc {
-
-enum { SRC_FUSED = 0, SRC_PLAIN = 1, SRC_CAND = 2 };
 
 // ------------------------------------------------------------------ plain accumulation
 
@@ -363,6 +362,25 @@ __device__ __forceinline__ uint32_t block_sum_1024(uint32_t x, uint32_t *tmp /*[
 // the work is balanced over the threads by output position (binary search of the owning row,
 // then of the bit inside the row), whatever the spread of the candidates.
 constexpr int kGatherRows = 128;
+// Long vectors: the candidates of every kSuperRows rows are summed by a kernel of their own, so
+// that a gather block adds up at most kSuperRows row counts (and a few sums) to find its place
+// instead of all the counts before it, which at 2^28 elements was most of the gather's time.
+
+__global__ __launch_bounds__(1024) void k_row_sums(SelArgs a) {
+    __shared__ uint32_t tmp[16];
+    const uint32_t nrows = (a.n + kRow - 1) / kRow;
+    const uint32_t *cnt = a.row_count + (size_t)blockIdx.y * a.rows;
+    const uint32_t lo = blockIdx.x * kSuperRows;
+    uint32_t part = 0;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {   // rows per node are a multiple of 4 in the scratch; rows past nrows are not read
+        const uint32_t i0 = lo + (r * 1024 + threadIdx.x) * 4;
+        if (i0 + 3 < nrows) { const u4 x = *(const u4 *)(cnt + i0); part += x[0] + x[1] + x[2] + x[3]; }
+        else for (uint32_t i = i0; i < nrows; ++i) part += cnt[i];
+    }
+    const uint32_t total = block_sum_1024(part, tmp);
+    if (threadIdx.x == 0) a.row_super[(size_t)blockIdx.y * a.supers + blockIdx.x] = total;
+}
 
 template <bool HIST>
 __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
@@ -389,8 +407,11 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
         bm[q] = (w2 * 2 < mine * kRowWords) ? *(const ulonglong2 *)(bitmap + (size_t)w2 * 2) : ulonglong2{0ull, 0ull};
     }
     const uint32_t t_est = HIST ? s->t_est : 0u;
-    uint32_t part = 0;
-    for (uint32_t i0 = tid * 4; i0 < first; i0 += 4096 * 4) {   // first and the row stride are multiples of 4
+    // candidates before the block: whole groups of kSuperRows rows (summed beforehand when the
+    // vector has more than one group), then the rows of the block's own group
+    const uint32_t group = first / kSuperRows;
+    uint32_t part = (uint32_t)tid < group ? a.row_super[(size_t)node * a.supers + tid] : 0u;
+    for (uint32_t i0 = group * kSuperRows + tid * 4; i0 < first; i0 += 4096 * 4) {   // first and the row stride are multiples of 4
         u4 x[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) x[r] = (i0 + r * 4096 < first) ? *(const u4 *)(cnt + i0 + r * 4096) : (u4){0u, 0u, 0u, 0u};
@@ -476,6 +497,8 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
 void launch_gather(const SelArgs &a, int batch, hipStream_t st) {
     const uint32_t nrows = (a.n + kRow - 1) / kRow;
     const dim3 grid((nrows + kGatherRows - 1) / kGatherRows, batch);
+    if (nrows > kSuperRows)
+        hipLaunchKernelGGL(k_row_sums, dim3((nrows + kSuperRows - 1) / kSuperRows, batch), dim3(1024), 0, st, a);
     // the per-layer selection has one threshold per segment, so no histogram above "the" estimate
     if (a.seg_t) hipLaunchKernelGGL(k_gather<false>, grid, dim3(1024), 0, st, a);
     else hipLaunchKernelGGL(k_gather<true>, grid, dim3(1024), 0, st, a);
@@ -727,13 +750,12 @@ __device__ __forceinline__ unsigned long long pack_status(uint32_t st, uint32_t 
 
 // The threshold T* and the tie quota are known.  The selected elements (key > T*, and the first
 // `quota` elements with key == T*) are written to the output in index order and zeroed in v
-// (and u).  SRC_CAND reads the gathered candidate list, SRC_PLAIN reads v itself (exact path).
-// Persistent blocks take 4096-element chunks by ticket; a chunk's output offset comes from a
-// look-back over the chunks before it.
-template <int SRC, bool VEC>
+// (and u), reading v itself (exact path).  Persistent blocks take the 4096-element chunks in
+// turn (block b: chunks b, b + gridDim.x, ...); a chunk's output offset comes from a look-back
+// over the chunks before it.
+template <bool VEC>
 __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, const uint32_t n_src,
                                             const uint32_t thr, const uint32_t quota) {
-    __shared__ uint32_t sh_chunk;
     __shared__ uint32_t sh_gt[kRows][kWaves], sh_eq[kRows][kWaves];
     __shared__ uint32_t sh_prefix[3];
 
@@ -743,46 +765,28 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
     const size_t off = (size_t)node * a.stride;
     float *u = a.u ? a.u + off : nullptr;
     float *v = a.v + off;
-    const uint32_t *cidx = a.cand_idx + (size_t)node * a.cap;
-    const uint32_t *cval = a.cand_val + (size_t)node * a.cap;
-    unsigned long long *st = (SRC == SRC_CAND) ? a.status_cand + (size_t)node * a.status_cand_stride
-                                               : a.status_exact + (size_t)node * a.status_exact_stride;
+    unsigned long long *st = a.status_exact + (size_t)node * a.status_exact_stride;
     uint32_t *oidx = a.out_idx + (size_t)node * a.k;
     float *oval = a.out_vals + (size_t)node * a.k;
 
     for (uint32_t it = 0;; ++it) {
         __syncthreads();
-        if (SRC == SRC_CAND) {
-            if (tid == 0) sh_chunk = atomicAdd(&a.ctr[node].ticket, 1u);
-            __syncthreads();
-        }
         // block-uniform values are made wave-uniform for the compiler, so that every branch that
         // leaves or repeats this loop (which contains barriers) is a scalar branch
-        const uint32_t chunk = __builtin_amdgcn_readfirstlane((SRC == SRC_CAND) ? sh_chunk : blockIdx.x + it * gridDim.x);
+        const uint32_t chunk = __builtin_amdgcn_readfirstlane(blockIdx.x + it * gridDim.x);
         if (chunk >= nchunks) break;
         const uint32_t base = chunk * (uint32_t)kChunk;
 
         uint32_t bits[kRows][4];   // value bits of my 16 elements
-        uint32_t pos[kRows][4];    // original index (SRC_CAND only)
         uint32_t gtm = 0, eqm = 0; // flag bit r*4+j
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
             const uint32_t e0 = base + r * kRowElems + tid * 4;
-            if (SRC == SRC_CAND) {
-                u4 ci = {0, 0, 0, 0}, cv = {0, 0, 0, 0};
-                if (e0 + 3 < n_src) { ci = *(const u4 *)(cidx + e0); cv = *(const u4 *)(cval + e0); }
-                else {
-                    for (int j = 0; j < 4; ++j) if (e0 + j < n_src) { ci[j] = cidx[e0 + j]; cv[j] = cval[e0 + j]; }
-                }
+            f4 vv = {0.f, 0.f, 0.f, 0.f};
+            if (VEC && e0 + 3 < n_src) vv = *(const f4 *)(v + e0);
+            else { for (int j = 0; j < 4; ++j) if (e0 + j < n_src) vv[j] = v[e0 + j]; }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) { pos[r][j] = ci[j]; bits[r][j] = cv[j]; }
-            } else {
-                f4 vv = {0.f, 0.f, 0.f, 0.f};
-                if (VEC && e0 + 3 < n_src) vv = *(const f4 *)(v + e0);
-                else { for (int j = 0; j < 4; ++j) if (e0 + j < n_src) vv[j] = v[e0 + j]; }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) bits[r][j] = __float_as_uint(vv[j]);
-            }
+            for (int j = 0; j < 4; ++j) bits[r][j] = __float_as_uint(vv[j]);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const bool valid = e0 + j < n_src;
@@ -866,7 +870,7 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
             if (pre_gt + blk_gt + (te < quota ? te : quota) != a.k) atomicAdd(&a.stats->errors, 1u);
         }
         // No thread-dependent `continue` here: a second back-edge taken by only some lanes makes the
-        // compiler re-enter the loop head (barriers, ticket) for those lanes alone.
+        // compiler re-enter the loop head (barrier) for those lanes alone.
         if ((gtm | eqm) != 0) {
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
@@ -878,7 +882,7 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
                 const bool fg = (gtm >> (r * 4 + j)) & 1u, fe = (eqm >> (r * 4 + j)) & 1u;
                 if (fg || (fe && ce < quota)) {
                     const uint32_t o = cg + (ce < quota ? ce : quota);
-                    const uint32_t where = (SRC == SRC_CAND) ? pos[r][j] : e0 + j;
+                    const uint32_t where = e0 + j;
                     if (o < a.k) { oidx[o] = where; oval[o] = __uint_as_float(bits[r][j]); }
                     else atomicAdd(&a.stats->errors, 1u);
                     v[where] = 0.0f;
@@ -891,27 +895,127 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
     }
 }
 
-// Long candidate lists: T* from the two histograms, then look-back compaction of the gathered list.
-__global__ __launch_bounds__(kBlock) void k_emit_candidates(SelArgs a) {
+// Long candidate lists, after k_select_level2.  Two kernels with nothing exchanged between the
+// blocks of either: k_count_chunks derives T* and the tie quota from the two histograms (every
+// block, same result in all) and counts, for each 4096-candidate chunk, the keys above T* and
+// the keys equal to it; k_emit_scanned adds up the counts of the chunks before its own, which
+// places its chunk's selected elements in the output, in index order.
+constexpr int kCountChunks = 4;   // chunks per block of k_count_chunks
+
+__global__ __launch_bounds__(1024) void k_count_chunks(SelArgs a) {
     __shared__ uint32_t hist[kFineBins];
-    __shared__ uint32_t wave_tmp[kWaves], res[2];
-    const int node = blockIdx.y;
+    __shared__ uint32_t wave_tmp[16], res[2];
+    __shared__ uint32_t sh_gt[kCountChunks][16], sh_eq[kCountChunks][16];
+    const int node = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Sel *s = a.sel + node;
     const uint32_t total = s->cand_total;
+    const uint32_t *cval = a.cand_val + (size_t)node * a.cap;
+    const uint32_t base = blockIdx.x * (uint32_t)(kCountChunks * kChunk);
+    const bool in_range = total <= a.cap;
+    // the keys first, so that the loads are under way while the threshold is worked out
+    u4 x[kCountChunks];
+#pragma unroll
+    for (int c = 0; c < kCountChunks; ++c) {
+        const uint32_t e0 = base + c * kChunk + tid * 4;   // the list's capacity is a multiple of 4
+        x[c] = (in_range && e0 < total) ? *(const u4 *)(cval + e0) : (u4){0u, 0u, 0u, 0u};
+    }
     uint32_t thr = 0, quota = 0;
-    // every block derives T* and the tie quota from the two histograms (same result in all)
     const bool ok = find_threshold<false>(a, node, total, hist, wave_tmp, res, thr, quota);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (blockIdx.x == 0 && tid == 0) {
         s->fast_ok = ok;
         if (ok) { s->thr = thr; s->quota = quota; }
         atomicAdd(ok ? &a.stats->fast : &a.stats->fallback, 1u);
     }
-    if (!ok) return;
-    emit_chunks<SRC_CAND, true>(a, node, total, thr, quota);
+    if (!ok || base >= total) return;
+#pragma unroll
+    for (int c = 0; c < kCountChunks; ++c) {
+        const uint32_t e0 = base + c * kChunk + tid * 4;
+        uint32_t gt = 0, eq = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t key = x[c][j] & 0x7fffffffu;
+            gt += e0 + j < total && key > thr;
+            eq += e0 + j < total && key == thr;
+        }
+        gt = wave_sum(gt); eq = wave_sum(eq);
+        if (lane == 0) { sh_gt[c][wave] = gt; sh_eq[c][wave] = eq; }
+    }
+    __syncthreads();
+    if (tid < kCountChunks) {
+        const uint32_t chunk = blockIdx.x * kCountChunks + tid;
+        if (chunk * (uint32_t)kChunk < total) {
+            uint32_t gt = 0, eq = 0;
+            for (int w = 0; w < 16; ++w) { gt += sh_gt[tid][w]; eq += sh_eq[tid][w]; }
+            a.status_cand[(size_t)node * a.status_cand_stride + chunk] = ((unsigned long long)gt << 32) | eq;
+        }
+    }
+}
+
+__global__ __launch_bounds__(1024) void k_emit_scanned(SelArgs a) {
+    __shared__ uint32_t sh_pg[16], sh_pe[16], sh_tg[16], sh_te[16];
+    const int node = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const Sel *s = a.sel + node;
+    const uint32_t total = s->cand_total;
+    const uint32_t chunk = blockIdx.x, base = chunk * (uint32_t)kChunk, e0 = base + tid * 4;
+    if (!s->fast_ok || base >= total) return;   // uniform; fast_ok implies k <= total <= cap
+    const uint32_t thr = s->thr, quota = s->quota;
+    const uint32_t *cidx = a.cand_idx + (size_t)node * a.cap;
+    const uint32_t *cval = a.cand_val + (size_t)node * a.cap;
+    const unsigned long long *counts = a.status_cand + (size_t)node * a.status_cand_stride;
+    u4 ci = {0, 0, 0, 0}, cv = {0u, 0u, 0u, 0u};
+    if (e0 < total) { ci = *(const u4 *)(cidx + e0); cv = *(const u4 *)(cval + e0); }
+    uint32_t pg = 0, pe = 0;
+    for (uint32_t c = tid; c < chunk; c += 1024) {
+        const unsigned long long w = counts[c];
+        pg += (uint32_t)(w >> 32); pe += (uint32_t)w;
+    }
+    pg = wave_sum(pg); pe = wave_sum(pe);
+    uint32_t lg = 0, le = 0, tg = 0, te = 0;
+    bool fg[4], fe[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t key = cv[j] & 0x7fffffffu;
+        fg[j] = e0 + j < total && key > thr;
+        fe[j] = e0 + j < total && key == thr;
+        const unsigned long long mg = __ballot(fg[j]), me = __ballot(fe[j]);
+        lg += lanes_below(mg); tg += (uint32_t)__popcll(mg);
+        le += lanes_below(me); te += (uint32_t)__popcll(me);
+    }
+    if (lane == 0) { sh_pg[wave] = pg; sh_pe[wave] = pe; sh_tg[wave] = tg; sh_te[wave] = te; }
+    __syncthreads();
+    // flagged elements before my first one: the earlier chunks, the lower wavefronts of this
+    // block, the lower lanes of this wavefront
+    uint32_t cg = lg, ce = le;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        cg += sh_pg[w]; ce += sh_pe[w];
+        if (w < wave) { cg += sh_tg[w]; ce += sh_te[w]; }
+    }
+    if (chunk == (total - 1) / (uint32_t)kChunk && tid == 1023) {
+        // the last thread of the last chunk sees everything: the selection must add up to k
+        uint32_t g_all = cg, e_all = ce;
+        for (int j = 0; j < 4; ++j) { g_all += fg[j]; e_all += fe[j]; }
+        if (g_all + (e_all < quota ? e_all : quota) != a.k) atomicAdd(&a.stats->errors, 1u);
+    }
+    float *v = a.v + (size_t)node * a.stride;
+    float *u = a.u ? a.u + (size_t)node * a.stride : nullptr;
+    uint32_t *oidx = a.out_idx + (size_t)node * a.k;
+    float *oval = a.out_vals + (size_t)node * a.k;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (fg[j] || (fe[j] && ce < quota)) {
+            const uint32_t o = cg + (ce < quota ? ce : quota);
+            if (o < a.k) { oidx[o] = ci[j]; oval[o] = __uint_as_float(cv[j]); }
+            else atomicAdd(&a.stats->errors, 1u);
+            v[ci[j]] = 0.0f;
+            if (u) u[ci[j]] = 0.0f;
+        }
+        cg += fg[j]; ce += fe[j];
+    }
 }
 
 // direct = true: short candidate lists (each block reads the whole list); false: long lists
-// (second-level histogram by many blocks, then look-back compaction).
+// (second-level histogram by many blocks, counts per chunk, output).
 void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hipStream_t st) {
     if (direct) {
         hipLaunchKernelGGL(k_output_direct, dim3((a.cap + 4095) / 4096, batch), dim3(1024), 0, st, a);
@@ -920,9 +1024,9 @@ void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hip
     uint32_t blocks = (a.cap + 16383) / 16384;
     if (blocks > 256) blocks = 256;
     hipLaunchKernelGGL(k_select_level2, dim3(blocks, batch), dim3(1024), 0, st, a);
-    blocks = (a.cap + kChunk - 1) / kChunk;
-    if (blocks > 256) blocks = 256;
-    hipLaunchKernelGGL(k_emit_candidates, dim3(blocks, batch), dim3(kBlock), 0, st, a);
+    const uint32_t chunks = (a.cap + kChunk - 1) / kChunk;
+    hipLaunchKernelGGL(k_count_chunks, dim3((chunks + kCountChunks - 1) / kCountChunks, batch), dim3(1024), 0, st, a);
+    hipLaunchKernelGGL(k_emit_scanned, dim3(chunks, batch), dim3(1024), 0, st, a);
 }
 
 // ------------------------------------------------------------------ exact path: one persistent kernel
@@ -999,7 +1103,7 @@ __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
     }
     // prefix is now the full key T*; rank the number of ties to take
     if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }
-    emit_chunks<SRC_PLAIN, VEC>(a, node, a.n, prefix, rank);
+    emit_chunks<VEC>(a, node, a.n, prefix, rank);
 }
 
 // The barriers and the static chunk order need every block of a node to be running at the same
