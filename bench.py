@@ -108,6 +108,26 @@ def ae_report(enc, dec, k, dec_batch, enc_batch, stages, which):
             "note": "fp32 in, fp32 accumulate; meaningful for --ae paper (the two-layer stacks are launch-latency bound)"}
 
 
+def plain_kernel_rates():
+    """Runs the stand-alone program built beside the library (csrc/hbm_rates.hip): the rates of a
+    plain read, a plain copy and a plain 3-reads-2-writes kernel on arrays of the ResNet50-sized
+    workload, and of the runtime's device-to-device copy.  None if it is not built or fails."""
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2103_08870_amd", "hbm_rates")
+    if not os.path.exists(exe):
+        return None
+    try:
+        r = subprocess.run([exe, "--json"], capture_output=True, text=True, timeout=120)
+        if r.returncode != 0:
+            return None
+        d = json.loads(r.stdout.strip().splitlines()[-1])
+    except Exception:
+        return None
+    d["note"] = ("one 256-thread block per 4096 elements; 3r2w reads g, u, v and writes u, v like the fused kernel, "
+                 "without any selection work; _nt = non-temporal loads and stores")
+    return d
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -239,6 +259,7 @@ def main():
         "a5_scatter": timed(lambda t: B.lgc_scatter(ctx, rec, idx, 1.0 / K, dense)),
     }
     B.lgc_stats(ctx)
+    torch.cuda.synchronize()
     roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
                 "traffic": MEASURED_TRAFFIC.get(w.cfg) if args.ratio_index in (-1, len(w.ks) - 1) and seg is None else None, "kernel": f"lgc::k_candidates<true, true, {'false' if seg is None else 'true'}> (fused accumulate + candidate bitmap, all nodes in one launch)",
                 "algorithmic_bytes_per_launch": ALGO_BYTES_PER_ELEM * K * n}
@@ -252,6 +273,11 @@ def main():
         if args.pattern == "rar":
             roofline.update(kernel="lgc::k_candidates<true, true, false> (selecting node) + lgc::k_accumulate<true> "
                                    "(other nodes): the streaming launches of one step", traffic=None)
+
+    plain = plain_kernel_rates()
+    if plain is not None:
+        # what kernels with no selection work reach on this GPU, measured now by a child process
+        roofline["plain_kernels"] = plain
 
     out = {
         "metric": "gradient elements/sec compressed (accumulate+top-k+AE encode); % of HBM peak",

@@ -1,4 +1,5 @@
-"""Builds liblgc.so (HIP, gfx950) in-tree next to this file."""
+"""Builds liblgc.so (HIP, gfx950) in-tree next to this file, and the stand-alone program hbm_rates
+(streaming rates of plain kernels, for comparison; bench.py runs it when it is there)."""
 from __future__ import annotations
 
 import os
@@ -9,6 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblgc.so")
+HBM_RATES = os.path.join(HERE, "hbm_rates")
 SOURCES = ["api.hip", "topk.hip", "segmented.hip", "autoencoder.hip", "ae_mfma.hip"]
 HEADERS = [os.path.join(CSRC, "lgc_internal.h"), os.path.join(CSRC, "device_helpers.h"),
            os.path.join(os.path.dirname(HERE), "include", "lgc.h")]
@@ -48,8 +50,18 @@ def build(force: bool = True, verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}")
         return obj
 
-    with ThreadPoolExecutor(max_workers=len(srcs)) as ex:
+    def build_probe():
+        cmd = [hipcc] + [f for f in FLAGS if f != "-fPIC"] + [os.path.join(CSRC, "hbm_rates.hip"), "-o", HBM_RATES]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if verbose or r.returncode != 0:
+            sys.stderr.write(" ".join(cmd) + "\n" + r.stdout + r.stderr)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed on hbm_rates.hip")
+
+    with ThreadPoolExecutor(max_workers=len(srcs) + 1) as ex:
+        probe = ex.submit(build_probe)
         objs = list(ex.map(compile_one, srcs))
+        probe.result()
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

@@ -296,24 +296,51 @@ void launch_scatter(const float *vals, const uint32_t *idx, uint32_t k, float sc
 
 // All nodes in one launch, same result as one k_scatter per node in node order.  Needs every
 // node's positions in ascending order.  The thread of (node b, entry j) looks its position up in
-// every other node's list (binary searches, one probe of each list in flight at a time); the
-// thread of the first node that holds the position owns it and adds the contributions of all
-// holders in node order; the other holders' threads leave it alone.  No atomics, no waiting.
+// every other node's list; the thread of the first node that holds the position owns it and adds
+// the contributions of all holders in node order; the other holders' threads leave it alone.  No
+// atomics, no waiting.  The look-up is a chain of dependent loads, so it is kept short: every
+// block first copies up to 1024 evenly spaced entries of each list into LDS (one round of loads),
+// searches those there, and is left with `stride` entries of the list itself to search.
 constexpr int kScatterNodes = 8;
+constexpr int kScatterSamples = 1024;
 
 __global__ __launch_bounds__(256) void k_scatter_nodes(const float *__restrict__ vals,
                                                        const uint32_t *__restrict__ idx, uint32_t k, int batch,
                                                        float scale, float *__restrict__ dense, uint32_t n,
-                                                       uint32_t steps, Stats *stats) {
+                                                       uint32_t stride, uint32_t steps, Stats *stats) {
+    __shared__ uint32_t smp[kScatterNodes][kScatterSamples];
     const uint32_t j = blockIdx.x * 256 + threadIdx.x;
     const int b = blockIdx.y;
-    if (j >= k) return;
-    const uint32_t i = idx[(size_t)b * k + j];
-    if (j > 0 && idx[(size_t)b * k + j - 1] >= i) atomicAdd(&stats->errors, 1u);   // not ascending
+    const uint32_t nsmp = (k + stride - 1) / stride;   // <= kScatterSamples; sample t is entry t * stride
+    const bool mine = j < k;
+    const uint32_t i = mine ? idx[(size_t)b * k + j] : 0u;
+    const uint32_t before = (mine && j > 0) ? idx[(size_t)b * k + j - 1] : 0u;
+    for (int o = 0; o < batch; ++o) {
+        if (o == b) continue;   // uniform
+        for (uint32_t t = threadIdx.x; t < nsmp; t += 256) smp[o][t] = idx[(size_t)o * k + (size_t)t * stride];
+    }
+    __syncthreads();
+    if (!mine) return;
+    if (j > 0 && before >= i) atomicAdd(&stats->errors, 1u);   // not ascending
     if (i >= n) { atomicAdd(&stats->errors, 1u); return; }
-    uint32_t lo[kScatterNodes], hi[kScatterNodes];
+    const float base = dense[i], own = vals[(size_t)b * k + j];
+    // per other node: [lo, hi) of its list still to search for the first entry >= i; hv = the entry
+    // at hi (0xffffffff when hi == k, which no valid position equals)
+    uint32_t lo[kScatterNodes], hi[kScatterNodes], hv[kScatterNodes];
 #pragma unroll
-    for (int o = 0; o < kScatterNodes; ++o) { lo[o] = 0; hi[o] = (o < batch && o != b) ? k : 0; }
+    for (int o = 0; o < kScatterNodes; ++o) {
+        lo[o] = hi[o] = 0; hv[o] = 0xffffffffu;
+        if (o < batch && o != b) {
+            uint32_t tl = 0, th = nsmp;                 // first sample >= i
+            while (tl < th) {
+                const uint32_t mid = (tl + th) >> 1;
+                if (smp[o][mid] < i) tl = mid + 1; else th = mid;
+            }
+            if (tl < nsmp) { hi[o] = tl * stride; hv[o] = smp[o][tl]; } else hi[o] = k;
+            lo[o] = tl == 0 ? 0u : (tl - 1) * stride + 1;   // sample tl - 1 is < i
+            if (lo[o] > hi[o]) lo[o] = hi[o];
+        }
+    }
     for (uint32_t s = 0; s < steps; ++s) {
         uint32_t probe[kScatterNodes];
 #pragma unroll
@@ -325,23 +352,22 @@ __global__ __launch_bounds__(256) void k_scatter_nodes(const float *__restrict__
         for (int o = 0; o < kScatterNodes; ++o) {
             const uint32_t mid = (lo[o] + hi[o]) >> 1;
             if (lo[o] < hi[o]) {
-                if (probe[o] < i) lo[o] = mid + 1; else hi[o] = mid;
+                if (probe[o] < i) lo[o] = mid + 1; else { hi[o] = mid; hv[o] = probe[o]; }
             }
         }
     }
-    // lo[o] = first entry of node o that is >= i (k if none)
+    // lo[o] == hi[o] = first entry of node o that is >= i (k if none), hv[o] its value
     bool held[kScatterNodes];
 #pragma unroll
-    for (int o = 0; o < kScatterNodes; ++o)
-        held[o] = o < batch && o != b && lo[o] < k && idx[(size_t)o * k + lo[o]] == i;
+    for (int o = 0; o < kScatterNodes; ++o) held[o] = o < batch && o != b && hv[o] == i;
     bool owner = true;
 #pragma unroll
     for (int o = 0; o < kScatterNodes; ++o) owner = owner && !(o < b && held[o]);
     if (!owner) return;
-    float acc = __fadd_rn(dense[i], __fmul_rn(scale, vals[(size_t)b * k + j]));
+    float acc = __fadd_rn(base, __fmul_rn(scale, own));
 #pragma unroll
     for (int o = 0; o < kScatterNodes; ++o)
-        if (o > b && held[o]) acc = __fadd_rn(acc, __fmul_rn(scale, vals[(size_t)o * k + lo[o]]));
+        if (o > b && held[o]) acc = __fadd_rn(acc, __fmul_rn(scale, vals[(size_t)o * k + hi[o]]));
     dense[i] = acc;
 }
 
@@ -349,10 +375,11 @@ bool launch_scatter_nodes(const float *vals, const uint32_t *idx, uint32_t k, in
                           uint32_t n, Stats *stats, hipStream_t st) {
     if (batch > kScatterNodes) return false;
     if (k == 0) return true;
+    const uint32_t stride = (k + kScatterSamples - 1) / kScatterSamples;
     uint32_t steps = 0;
-    while ((1ull << steps) <= k) ++steps;   // a binary search over k entries ends within this many halvings
+    while ((1u << steps) < stride) ++steps;   // a binary search over at most stride - 1 entries ends within this many halvings
     hipLaunchKernelGGL(k_scatter_nodes, dim3((k + 255) / 256, batch), dim3(256), 0, st, vals, idx, k, batch, scale,
-                       dense, n, steps, stats);
+                       dense, n, stride, steps, stats);
     return true;
 }
 
