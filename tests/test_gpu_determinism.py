@@ -1,0 +1,89 @@
+"""Properties of the HIP path that hold whatever the inputs: the same calls on the same inputs give
+the same bytes, run after run (no result depends on the order in which blocks or atomics happen to
+run), and the path has no state of its own beyond the caller's u and v: iterations continued from
+saved copies of u and v, in a new context, give what the uninterrupted run gives (the residuals of
+Alg. 1 / Alg. 2 are the only thing carried from one iteration to the next)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2103_08870_amd import synth
+from test_gpu_parity import B, make_ae  # noqa: F401  (B is a fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def one_run(B, w, iters, selection, ae_pack, state=None, first=0, force_exact=False):
+    """`iters` whole iterations (accumulate + top-k, encode, decode, scatter) from `state` (u, v; zeros
+    if None), starting at iteration number `first`.  Returns the final u, v and every iteration's outputs."""
+    K, n = w.nodes, w.n
+    ae, enc, dec = ae_pack
+    if selection == "layers":
+        off, ks = synth.layer_plan(w)
+        k = sum(ks)
+    else:
+        k = w.k
+    ctx = B.Context(n, k, K)
+    if force_exact:
+        B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 1)
+    seg = B.Segments(off, ks) if selection == "layers" else None
+    u = torch.zeros((K, n), device="cuda") if state is None else state[0].clone()
+    v = torch.zeros((K, n), device="cuda") if state is None else state[1].clone()
+    outs = []
+    for t in range(first, first + iters):
+        g = synth.gradients(w, t, device="cuda")
+        vals = torch.zeros((K, k), device="cuda")
+        idx = torch.zeros((K, k), device="cuda", dtype=torch.int32)
+        lat = torch.zeros((K, B.lgc_latent_len(ae, k)), device="cuda")
+        rec = torch.zeros((K, k), device="cuda")
+        dense = torch.zeros(n, device="cuda")
+        if seg is None:
+            B.lgc_accumulate_topk(ctx, g, u, v, w.momentum, k, vals, idx)
+        else:
+            B.lgc_accumulate_topk_segmented(ctx, seg, g, u, v, w.momentum, vals, idx)
+        B.lgc_encode(ctx, ae, vals, lat)
+        B.lgc_decode(ctx, ae, lat, rec)
+        B.lgc_scatter(ctx, rec, idx, 1.0 / K, dense)
+        assert B.lgc_stats(ctx)[2] == 0
+        outs.append((vals, idx, lat, rec, dense))
+    if seg is not None:
+        seg.close()
+    ctx.close()
+    return u, v, outs
+
+
+def bits_equal(a, b):
+    return a.shape == b.shape and torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+@pytest.mark.parametrize("cfg,n,selection,force_exact", [(2, 3_000_001, "flat", False), (2, 3_000_001, "layers", False),
+                                                         (5, 1 << 22, "flat", False), (2, 1_100_000, "flat", True)])
+def test_same_inputs_same_bytes(B, cfg, n, selection, force_exact):
+    w = synth.workload(cfg, n=n, nodes=min(synth.workload(cfg).nodes, 3))
+    ae, enc, dec, _ = make_ae(B, w.ae_channels)
+    ref = one_run(B, w, 3, selection, (ae, enc, dec), force_exact=force_exact)
+    for rep in range(8):
+        got = one_run(B, w, 3, selection, (ae, enc, dec), force_exact=force_exact)
+        assert bits_equal(got[0], ref[0]) and bits_equal(got[1], ref[1]), rep
+        for t, (a, b) in enumerate(zip(got[2], ref[2])):
+            for x, y in zip(a, b):
+                assert bits_equal(x, y), (rep, t)
+    ae.close()
+
+
+@pytest.mark.parametrize("selection", ["flat", "layers"])
+def test_resume_from_saved_residuals(B, selection):
+    """10 iterations in one go against 5 iterations, u and v saved to the host, a new context, 5 more."""
+    w = synth.workload(4, n=2_500_000, nodes=2)
+    ae, enc, dec, _ = make_ae(B, w.ae_channels)
+    u_all, v_all, outs_all = one_run(B, w, 10, selection, (ae, enc, dec))
+    u5, v5, outs_a = one_run(B, w, 5, selection, (ae, enc, dec))
+    saved = (u5.cpu().numpy().copy(), v5.cpu().numpy().copy())
+    del u5, v5
+    restored = tuple(torch.from_numpy(x).cuda() for x in saved)
+    u10, v10, outs_b = one_run(B, w, 5, selection, (ae, enc, dec), state=restored, first=5)
+    assert bits_equal(u10, u_all) and bits_equal(v10, v_all)
+    for t, (a, b) in enumerate(zip(outs_a + outs_b, outs_all)):
+        for x, y in zip(a, b):
+            assert bits_equal(x, y), t
+    ae.close()
