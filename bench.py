@@ -33,6 +33,8 @@ def parse():
     p.add_argument("--steps", type=int, default=50)
     p.add_argument("--warmup", type=int, default=5)
     p.add_argument("--workload", type=int, default=2, help="1..5 (default 2: ResNet50-sized)")
+    p.add_argument("--no-plain-kernels", action="store_true",
+                   help="do not run the stand-alone program that measures plain streaming kernels (use under a profiler)")
     p.add_argument("--ratio-index", type=int, default=-1, help="which of the workload's ratios")
     p.add_argument("--grad-sets", type=int, default=0, help="distinct gradient sets kept in HBM (0 = workload's)")
     p.add_argument("--pattern", choices=["ps", "rar"], default="ps",
@@ -142,6 +144,9 @@ def main():
     if not os.path.exists(B.LIB_PATH):
         from paper_2103_08870_amd import build
         build.build()
+    # what kernels with no selection work reach on this GPU: measured by a child process, which is
+    # started before this process makes its first GPU call
+    plain = None if args.no_plain_kernels else plain_kernel_rates()
     B.lib()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
@@ -274,9 +279,7 @@ def main():
             roofline.update(kernel="lgc::k_candidates<true, true, false> (selecting node) + lgc::k_accumulate<true> "
                                    "(other nodes): the streaming launches of one step", traffic=None)
 
-    plain = plain_kernel_rates()
     if plain is not None:
-        # what kernels with no selection work reach on this GPU, measured now by a child process
         roofline["plain_kernels"] = plain
 
     out = {

@@ -99,7 +99,7 @@ struct SelArgs {
     uint32_t *samples;        // [batch][kSample]
     uint32_t *row_count;      // [batch][rows]  candidates per row
     uint32_t *row_super;      // [batch][supers] candidates per group of kSuperRows rows (vectors of more than one group)
-    uint32_t supers;
+    uint32_t supers;           // groups per node in row_super; 0: the gather adds up the row counts themselves
     unsigned long long *bitmap;  // [batch][rows][kRowWords]
     uint32_t *cand_idx;       // [batch][cap]  gathered, index-ordered
     uint32_t *cand_val;

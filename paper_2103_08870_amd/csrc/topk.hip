@@ -362,7 +362,7 @@ __device__ __forceinline__ uint32_t block_sum_1024(uint32_t x, uint32_t *tmp /*[
 // the work is balanced over the threads by output position (binary search of the owning row,
 // then of the bit inside the row), whatever the spread of the candidates.
 constexpr int kGatherRows = 128;
-// Long vectors: the candidates of every kSuperRows rows are summed by a kernel of their own, so
+// Long vectors (a.supers != 0): the candidates of every kSuperRows rows are summed by a kernel of their own, so
 // that a gather block adds up at most kSuperRows row counts (and a few sums) to find its place
 // instead of all the counts before it, which at 2^28 elements was most of the gather's time.
 
@@ -409,7 +409,7 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
     const uint32_t t_est = HIST ? s->t_est : 0u;
     // candidates before the block: whole groups of kSuperRows rows (summed beforehand when the
     // vector has more than one group), then the rows of the block's own group
-    const uint32_t group = first / kSuperRows;
+    const uint32_t group = a.supers ? first / kSuperRows : 0u;
     uint32_t part = (uint32_t)tid < group ? a.row_super[(size_t)node * a.supers + tid] : 0u;
     for (uint32_t i0 = group * kSuperRows + tid * 4; i0 < first; i0 += 4096 * 4) {   // first and the row stride are multiples of 4
         u4 x[4];
@@ -497,11 +497,16 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
 void launch_gather(const SelArgs &a, int batch, hipStream_t st) {
     const uint32_t nrows = (a.n + kRow - 1) / kRow;
     const dim3 grid((nrows + kGatherRows - 1) / kGatherRows, batch);
-    if (nrows > kSuperRows)
-        hipLaunchKernelGGL(k_row_sums, dim3((nrows + kSuperRows - 1) / kSuperRows, batch), dim3(1024), 0, st, a);
+    // the sums per group pay for their launch from about 32 K rows on (measured: at 25 K rows the gather
+    // gains 0.5 us from them, at 256 K rows 17 us)
+    SelArgs g = a;
+    if (nrows > 4 * kSuperRows)
+        hipLaunchKernelGGL(k_row_sums, dim3((nrows + kSuperRows - 1) / kSuperRows, batch), dim3(1024), 0, st, g);
+    else
+        g.supers = 0;
     // the per-layer selection has one threshold per segment, so no histogram above "the" estimate
-    if (a.seg_t) hipLaunchKernelGGL(k_gather<false>, grid, dim3(1024), 0, st, a);
-    else hipLaunchKernelGGL(k_gather<true>, grid, dim3(1024), 0, st, a);
+    if (a.seg_t) hipLaunchKernelGGL(k_gather<false>, grid, dim3(1024), 0, st, g);
+    else hipLaunchKernelGGL(k_gather<true>, grid, dim3(1024), 0, st, g);
 }
 
 // Adds, for every candidate i < total that passes `member`, one count to hist[digit(d)], where
