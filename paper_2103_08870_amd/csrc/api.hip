@@ -81,6 +81,18 @@ static lgc_status fail(lgc_ctx *ctx, lgc_status s, const char *fmt, ...) {
 
 namespace {
 
+// No C++ exception leaves the library: the entry points that use containers run their bodies here.
+template <typename F>
+lgc_status no_throw(lgc_ctx *ctx, F &&body) noexcept {
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, LGC_ENOMEM, "out of host memory");
+    } catch (...) {
+        return fail(ctx, LGC_EHIP, "unexpected C++ exception");
+    }
+}
+
 struct DeviceGuard {
     int prev = -1;
     bool ok = true;
@@ -123,6 +135,12 @@ void profile_begin(lgc_ctx *c, hipStream_t st) {
         hipEvent_t a, b;
         if (hipEventCreate(&a) != hipSuccess) return;
         if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+        try {
+            c->ev.reserve(c->ev.size() + 2);
+        } catch (...) {
+            (void)hipEventDestroy(a); (void)hipEventDestroy(b);
+            return;
+        }
         c->ev.push_back(a);
         c->ev.push_back(b);
     }
@@ -428,8 +446,15 @@ extern "C" lgc_status lgc_ae_create(lgc_ae **out, int device, int n_enc, const l
     lgc_ae *ae = new (std::nothrow) lgc_ae;
     if (!ae) return fail(nullptr, LGC_ENOMEM, "out of host memory");
     ae->device = device; ae->slope = slope; ae->innovation = with_innovation;
-    ae->enc.assign(enc, enc + n_enc);
-    ae->dec.assign(dec, dec + n_dec);
+    try {
+        ae->enc.assign(enc, enc + n_enc);
+        ae->dec.assign(dec, dec + n_dec);
+        ae->enc_dev.reserve(n_enc);   // so that the push_back calls below cannot throw
+        ae->dec_dev.reserve(n_dec);
+    } catch (...) {
+        delete ae;
+        return fail(nullptr, LGC_ENOMEM, "out of host memory");
+    }
     size_t total = 0;
     auto wsize = [](const lgc_layer &l) { return align_up((size_t)l.c_in * l.c_out * l.ksize, 64); };
     auto bsize = [](const lgc_layer &l) { return align_up((size_t)l.c_out, 64); };
@@ -526,7 +551,9 @@ static std::vector<uint64_t> dec_lengths(const lgc_ae *ae, uint64_t k) {
 
 extern "C" uint64_t lgc_latent_len(const lgc_ae *ae, uint64_t k) {
     if (!ae) return 0;
-    return enc_lengths(ae, k).back() * (uint64_t)ae->enc.back().c_out;
+    uint64_t len = k;   // no container here: nothing can throw
+    for (auto &l : ae->enc) len = conv_len(len, l);
+    return len * (uint64_t)ae->enc.back().c_out;
 }
 
 static lgc_status ensure_act(lgc_ctx *ctx, size_t floats) {
@@ -550,8 +577,8 @@ static lgc_status check_ae_call(lgc_ctx *ctx, const lgc_ae *ae, const void *a, c
     return LGC_OK;
 }
 
-extern "C" lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, uint64_t k, int batch,
-                                 float *latent, void *stream) {
+static lgc_status run_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, uint64_t k, int batch,
+                             float *latent, void *stream) {
     lgc_status s = check_ae_call(ctx, ae, vals, latent, k, batch);
     if (s != LGC_OK) return s;
     if (k == 0) return LGC_OK;
@@ -593,6 +620,11 @@ extern "C" lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *va
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
     return LGC_OK;
+}
+
+extern "C" lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, uint64_t k, int batch,
+                                 float *latent, void *stream) {
+    return no_throw(ctx, [&] { return run_encode(ctx, ae, vals, k, batch, latent, stream); });
 }
 
 static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, const float *innov, uint64_t k,
@@ -653,14 +685,14 @@ static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent
 
 extern "C" lgc_status lgc_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, uint64_t k, int batch,
                                  float *rec, void *stream) {
-    return run_decode(ctx, ae, latent, nullptr, k, batch, rec, stream);
+    return no_throw(ctx, [&] { return run_decode(ctx, ae, latent, nullptr, k, batch, rec, stream); });
 }
 
 extern "C" lgc_status lgc_decode_innovation(lgc_ctx *ctx, const lgc_ae *ae, const float *latent, const float *innov,
                                             uint64_t k, int batch, float *rec, void *stream) {
     if (ctx && k > 0 && !innov) return fail(ctx, LGC_EINVAL, "innov must not be NULL");
     if (ctx && ae && k == 0 && !innov && ae->innovation) return LGC_OK;
-    return run_decode(ctx, ae, latent, innov, k, batch, rec, stream);
+    return no_throw(ctx, [&] { return run_decode(ctx, ae, latent, innov, k, batch, rec, stream); });
 }
 
 extern "C" lgc_status lgc_innovation(lgc_ctx *ctx, const lgc_segments *seg, const float *vals, int batch, float *out,
@@ -710,8 +742,8 @@ extern "C" lgc_status lgc_scatter(lgc_ctx *ctx, const float *vals, const uint32_
 constexpr uint32_t kSegSampleKeys = 16384;   // keys sampled per sampled segment (1024 threads x 16)
 constexpr uint64_t kSegMinSampled = 16384;   // smaller segments are selected from v directly
 
-extern "C" lgc_status lgc_segments_create(lgc_segments **out, int device, uint64_t n, uint64_t n_seg,
-                                          const uint64_t *offsets, const uint64_t *ks) {
+static lgc_status segments_create(lgc_segments **out, int device, uint64_t n, uint64_t n_seg,
+                                  const uint64_t *offsets, const uint64_t *ks) {
     if (!out) return fail(nullptr, LGC_EINVAL, "out is NULL");
     *out = nullptr;
     if (!offsets || !ks) return fail(nullptr, LGC_EINVAL, "offsets and ks must not be NULL");
@@ -786,6 +818,13 @@ extern "C" lgc_status lgc_segments_create(lgc_segments **out, int device, uint64
     }
     *out = sg;
     return LGC_OK;
+}
+
+extern "C" lgc_status lgc_segments_create(lgc_segments **out, int device, uint64_t n, uint64_t n_seg,
+                                          const uint64_t *offsets, const uint64_t *ks) {
+    // the host-side tables are built before anything is allocated on the device, so nothing is
+    // left behind if they cannot be
+    return no_throw(nullptr, [&] { return segments_create(out, device, n, n_seg, offsets, ks); });
 }
 
 extern "C" void lgc_segments_destroy(lgc_segments *seg) {
