@@ -493,3 +493,46 @@ def test_repeated_calls_with_short_last_chunk(B, oracle):
         assert (idx[0].cpu().numpy().astype(np.uint32) == oi).all() and same_bits(vals[0], ov)
         assert same_bits(dv[0], v) and same_bits(du[0], u)
     ctx.close()
+
+
+@pytest.mark.parametrize("n", [(1 << 30) + 4097, (1 << 31) - 4099])
+def test_vector_longer_than_4_gib(B, oracle, n):
+    """One node of 2^30 + 4097 elements, and one of nearly 2^31 (the largest the library accepts): every
+    tensor is longer than 4 GiB, so byte offsets do not fit 32 bits anywhere, and in the second case element
+    numbers use all 31 bits (the largest benchmark vector, 2^28 elements, stays far below both).  Fused
+    accumulate + top-k (accumulation against the oracle element by element, selection through the
+    properties), then the values at those positions again (lgc_gather) and their placement (lgc_scatter)."""
+    w = synth.workload(5, n=n)
+    n, k = w.n, w.n // 1000
+    ctx = B.Context(n, k, 1)
+    dg = synth.gradients(w, 0, device="cuda", k_for_ties=(k,))
+    du = torch.zeros((1, n), device="cuda")
+    dv = torch.zeros((1, n), device="cuda")
+    vals = torch.zeros((1, k), device="cuda")
+    idx = torch.zeros((1, k), device="cuda", dtype=torch.int32)
+    B.lgc_accumulate_topk(ctx, dg, du, dv, w.momentum, k, vals, idx)
+    assert B.lgc_stats(ctx) == (1, 0, 0)
+    u, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    oracle.accumulate(dg[0].cpu().numpy(), u, v, w.momentum)
+    hv, hi = vals[0].cpu().numpy(), idx[0].cpu().numpy().astype(np.uint32)
+    v_res, u_res = dv[0].cpu().numpy(), du[0].cpu().numpy()
+    check_selection_properties(v, u, v_res, u_res, hv, hi, k)
+    assert hi[-1] >= n - (1 << 24)                  # the selection reaches the end of the vector
+    del u_res, v_res
+    # second iteration on the plain path: accumulate alone, then the values at the same positions
+    B.lgc_accumulate(ctx, dg, du, dv, w.momentum)
+    v[hi] = 0.0; u[hi] = 0.0
+    oracle.accumulate(dg[0].cpu().numpy(), u, v, w.momentum)
+    again = torch.zeros((1, k), device="cuda")
+    B.lgc_gather(ctx, dv, du, idx[0], again)
+    ref = oracle.gather(v, u, hi)
+    assert same_bits(again[0], ref)
+    assert same_bits(dv[0], v) and same_bits(du[0], u)
+    del u, v
+    dense = torch.zeros(n, device="cuda")
+    B.lgc_scatter(ctx, again, idx, 0.5, dense)
+    assert B.lgc_stats(ctx)[2] == 0
+    ref_dense = np.zeros(n, np.float32)
+    oracle.scatter(ref, hi, 0.5, ref_dense)
+    assert same_bits(dense, ref_dense)
+    ctx.close()
