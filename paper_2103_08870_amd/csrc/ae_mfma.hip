@@ -58,29 +58,50 @@ constexpr int kPosTile = 64;
 constexpr int kRowPad = 136;    // per input channel: odd positions [0..64], even positions [68..131]
 constexpr int kEvenOff = 68;
 constexpr int kXPerRow = 2 * kPosTile + 1;                           // 129 inputs per channel and tile
+constexpr int kHeadMaxC = 256;                                        // most channels of a fused one-channel first layer
 constexpr int kXRegs = (kCiChunk * kXPerRow + 255) / 256;            // 9
 constexpr int kWRegs = kCiChunk * 3 * 64 / 256;                      // 12
 
 // TAIL: a following kernel-1 / stride-1 layer from these 64 channels (c_out == 64: one block holds all of
 // them for its positions) to tail_c <= 4 channels is applied to the activated tile before anything is
 // stored; `out` is then that layer's output [b][tail_c][l_out] (Table I: conv4 256->64 and conv5 64->4).
-template <bool TAIL>
+// HEAD: the layer's input is not read but made on the fly from a preceding kernel-3 / stride-2 layer with ONE
+// input channel (Table I: conv1 1->64 in front of conv2 64->128): `in` is then that layer's input
+// [b][1][l_head], head_w [c_in][1][3] and head_b [c_in] its weights, and every staged input h[ci][q] =
+// act(head_b[ci] + sum_t head_w[ci][t] x[2q - 1 + t]) comes from a 259-value stretch of x kept in LDS: no
+// intermediate tensor, no launch for the first layer, no global loads of inputs in the contraction loop.
+template <bool TAIL, bool HEAD>
 __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ in, float *__restrict__ out,
                                                       const float *__restrict__ wt, const float *__restrict__ bias,
                                                       int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
                                                       float slope, const float *__restrict__ tail_w /*[tail_c][64]*/,
-                                                      const float *__restrict__ tail_b, int tail_c, int tail_act) {
+                                                      const float *__restrict__ tail_b, int tail_c, int tail_act,
+                                                      const float *__restrict__ head_w, const float *__restrict__ head_b,
+                                                      uint32_t l_head) {
     // the last slot of the input buffer takes the stores of staging slots that hold nothing
     // (a second pair of buffers, with one barrier per chunk, was tried: it costs a resident block per
     // compute unit and gains nothing)
     __shared__ float xs[kCiChunk * kRowPad + 1];
     __shared__ float ws[kCiChunk * 3 * 64];
+    __shared__ float head_x[HEAD ? 4 * kPosTile + 4 : 1];   // x[4 p0 - 3 .. 4 p0 + 255], zeros outside [0, l_head)
+    __shared__ float head_p[HEAD ? 4 * kHeadMaxC : 1];      // per channel: the three taps, then the bias
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, half = lane >> 5, col = lane & 31;
     const uint32_t p0 = blockIdx.x * kPosTile;
     const int co0 = blockIdx.y * 64;
-    in += (size_t)blockIdx.z * c_in * l_in;
+    in += (size_t)blockIdx.z * (HEAD ? (size_t)l_head : (size_t)c_in * l_in);
     out += (size_t)blockIdx.z * (TAIL ? tail_c : c_out) * l_out;
+    if (HEAD) {
+        for (int i = tid; i < 4 * kPosTile + 3; i += 256) {
+            const long long q = 4ll * p0 - 3 + i;
+            head_x[i] = (q >= 0 && q < (long long)l_head) ? in[q] : 0.f;
+        }
+        for (int i = tid; i < c_in; i += 256) {   // c_in <= kHeadMaxC (the launcher sees to it)
+            head_p[4 * i] = head_w[3 * i]; head_p[4 * i + 1] = head_w[3 * i + 1]; head_p[4 * i + 2] = head_w[3 * i + 2];
+            head_p[4 * i + 3] = head_b[i];
+        }
+        // the first barrier of the contraction loop orders these stores before their first use in stage()
+    }
 
     // staging slots of this thread, fixed for the whole contraction: input slot e = tid + 256 i is
     // (channel e / 129, r = e % 129) with r <= 64: odd[r] = in[2 (p0 + r) - 1] and
@@ -100,23 +121,39 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
         live |= (uint32_t)ok << i;
     }
     const uint32_t gw0 = (uint32_t)((tid >> 6) * c_out + co0 + (tid & 63));   // slot e = tid + 256 i: row (tid >> 6) + 4 i
-    float xr[kXRegs], wr[kWRegs];
+    float xr[HEAD ? 1 : kXRegs], wr[kWRegs];
     auto fetch = [&](int c0) {
-        const float *xin = in + (size_t)c0 * l_in;
         const float *win = wt + (size_t)c0 * 3 * c_out + gw0;
+        if (!HEAD) {
+            const float *xin = in + (size_t)c0 * l_in;
 #pragma unroll
-        for (int i = 0; i < kXRegs; ++i) xr[i] = xin[gx[i]];
+            for (int i = 0; i < kXRegs; ++i) xr[i] = xin[gx[i]];
+        }
 #pragma unroll
         for (int i = 0; i < kWRegs; ++i) wr[i] = win[(size_t)(4 * i) * c_out];
     };
-    auto stage = [&]() {
+    auto stage = [&](int c0) {
 #pragma unroll
         for (int i = 0; i < kXRegs; ++i) {
             const int e = tid + 256 * i;
             const int ci = e / kXPerRow, r = e % kXPerRow;
             const int slot = e < kCiChunk * kXPerRow ? ci * kRowPad + (r <= kPosTile ? r : kEvenOff + (r - kPosTile - 1))
                                                      : kCiChunk * kRowPad;
-            xs[slot] = ((live >> i) & 1u) ? xr[i] : 0.f;
+            float x;
+            if (HEAD) {
+                // h[c0 + ci][q], q = 2 (p0 + r) - 1 (odd slots) or 2 (p0 + r - 65) (even slots): its window starts
+                // at x[2 q - 1] = head_x[4 r] or head_x[4 (r - 65) + 2]
+                const int x0 = r <= kPosTile ? 4 * r : 4 * (r - kPosTile - 1) + 2;
+                const float *hp = head_p + 4 * (c0 + (e < kCiChunk * kXPerRow ? ci : 0));
+                float a = hp[3];
+                a = fmaf(hp[0], head_x[x0], a);
+                a = fmaf(hp[1], head_x[x0 + 1], a);
+                a = fmaf(hp[2], head_x[x0 + 2], a);
+                x = leaky_m(a, slope);
+            } else {
+                x = xr[i];
+            }
+            xs[slot] = ((live >> i) & 1u) ? x : 0.f;
         }
 #pragma unroll
         for (int i = 0; i < kWRegs; ++i) ws[tid + 256 * i] = wr[i];
@@ -129,7 +166,7 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
     fetch(0);
     for (int c0 = 0; c0 < c_in; c0 += kCiChunk) {
         __syncthreads();   // the previous chunk's readers are done
-        stage();
+        stage(c0);
         __syncthreads();
         if (c0 + kCiChunk < c_in) fetch(c0 + kCiChunk);   // in flight during the multiplications below
         // contraction index of step s: lanes 0..31 take channel s / 3 of the chunk's first eight, lanes
@@ -197,11 +234,25 @@ bool launch_conv3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_
     if (l_out == 0) return true;
     dim3 grid((l_out + kPosTile - 1) / kPosTile, l.c_out / 64, batch);
     if (tail)
-        hipLaunchKernelGGL(k_conv3s2_mfma<true>, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
-                           (int)act, slope, tail->w, tail->b, tail->c_out, (int)tail_act);
+        hipLaunchKernelGGL((k_conv3s2_mfma<true, false>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
+                           l_out, (int)act, slope, tail->w, tail->b, tail->c_out, (int)tail_act, nullptr, nullptr, 0u);
     else
-        hipLaunchKernelGGL(k_conv3s2_mfma<false>, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
-                           (int)act, slope, nullptr, nullptr, 0, 0);
+        hipLaunchKernelGGL((k_conv3s2_mfma<false, false>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
+                           l_out, (int)act, slope, nullptr, nullptr, 0, 0, nullptr, nullptr, 0u);
+    return true;
+}
+
+// The two first layers of a stack in one launch: `head` (one input channel, kernel 3, stride 2, always
+// followed by the non-linearity) is evaluated inside the staging of `l`.  x: [batch][1][l_x]; l_in, l_out:
+// input and output length of `l` (l_in is the head's output length).
+bool launch_conv3s2_mfma_head(const float *x, float *out, const LayerDev &head, const LayerDev &l, uint32_t l_x,
+                              uint32_t l_in, uint32_t l_out, int batch, bool act, float slope, hipStream_t st) {
+    if (!conv3s2_mfma_covers(l, l_in)) return false;
+    if (!(head.c_in == 1 && head.ksize == 3 && head.stride == 2 && head.c_out == l.c_in && l.c_in <= kHeadMaxC)) return false;
+    if (l_out == 0) return true;
+    dim3 grid((l_out + kPosTile - 1) / kPosTile, l.c_out / 64, batch);
+    hipLaunchKernelGGL((k_conv3s2_mfma<false, true>), grid, dim3(256), 0, st, x, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                       (int)act, slope, nullptr, nullptr, 0, 0, head.w, head.b, l_x);
     return true;
 }
 
@@ -222,19 +273,39 @@ constexpr int kTWRegs = 3 * kCiChunk * 32 / 256;                      // 6
 // TAIL: a following kernel-1 / stride-1 layer from these 32 channels (c_out == 32) to one channel is applied
 // to the activated tiles before anything is stored; `out` is then [b][1][l_out] (Table II: deconv5 128->32
 // and the last layer 32->1).
-template <bool TAIL>
+// HEAD: the layer's input is made on the fly from the two narrow layers in front of it (Table II: deconv1
+// 4->4, kernel 3 / stride 1, and deconv2 4->32, kernel 3 / stride 2, in front of deconv3 32->64): `in` is then
+// the first of them's input z [b][hd.c0][hd.l_z].  A block first evaluates the stride-1 layer on the 65
+// positions its tile needs (into LDS), and every staged input h2[ci][m] is the stride-2 layer evaluated there:
+// even m = 2p from h1[.][p], odd m = 2p + 1 from h1[.][p] and h1[.][p + 1].  No intermediate tensors, two
+// launches fewer, no global loads of inputs in the contraction loop.
+struct ConvtHead {
+    const float *w1, *b1;   // [c0][c1][3], [c1]    kernel 3, stride 1
+    const float *w2, *b2;   // [c1][c_in][3], [c_in] kernel 3, stride 2
+    int c0, c1;             // both <= kHeadNarrow
+    uint32_t l_z;           // length of z and of the stride-1 layer's output
+};
+constexpr int kHeadNarrow = 8;
+constexpr int kHeadWide = 64;     // most channels out of the stride-2 head layer (= c_in of the deep layer)
+constexpr int kHeadPos = kTPosTile / 2 + 1;   // 65 positions of h1 per tile
+
+template <bool TAIL, bool HEAD>
 __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__ in, float *__restrict__ out,
                                                        const float *__restrict__ wt, const float *__restrict__ bias,
                                                        int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
                                                        float slope, const float *__restrict__ tail_w /*[32]*/,
-                                                       const float *__restrict__ tail_b, int tail_act) {
+                                                       const float *__restrict__ tail_b, int tail_act, ConvtHead hd) {
     __shared__ float xs[kCiChunk * kTRowPad + 1];
     __shared__ float ws[3 * kCiChunk * 32];
+    __shared__ float hz[HEAD ? kHeadNarrow * (kHeadPos + 2) : 1];        // z[c][m0/2 - 1 .. m0/2 + 65]
+    __shared__ float h1[HEAD ? kHeadNarrow * kHeadPos : 1];              // h1[c][m0/2 .. m0/2 + 64]
+    __shared__ float hw1[HEAD ? kHeadNarrow * kHeadNarrow * 3 + kHeadNarrow : 1];
+    __shared__ float hw2[HEAD ? kHeadNarrow * kHeadWide * 3 + kHeadWide : 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
     const uint32_t m0 = blockIdx.x * kTPosTile;
     const int co0 = blockIdx.y * 32;
-    in += (size_t)blockIdx.z * c_in * l_in;
+    in += (size_t)blockIdx.z * (HEAD ? (size_t)hd.c0 * hd.l_z : (size_t)c_in * l_in);
     out += (size_t)blockIdx.z * (TAIL ? 1 : c_out) * l_out;
 
     // staging slots of this thread, fixed for the whole contraction (see the convolution above)
@@ -256,18 +327,40 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
         const int t = e / (kCiChunk * 32), ci = (e / 32) % kCiChunk, co = e & 31;
         gw[i] = (uint32_t)((t * c_in + ci) * c_out + co0 + co);
     }
-    float xr[kTXRegs], wr[kTWRegs];
+    float xr[HEAD ? 1 : kTXRegs], wr[kTWRegs];
     auto fetch = [&](int c0) {
-        const float *xin = in + (size_t)c0 * l_in;
         const float *win = wt + (size_t)c0 * c_out;
+        if (!HEAD) {
+            const float *xin = in + (size_t)c0 * l_in;
 #pragma unroll
-        for (int i = 0; i < kTXRegs; ++i) xr[i] = xin[gx[i]];
+            for (int i = 0; i < kTXRegs; ++i) xr[i] = xin[gx[i]];
+        }
 #pragma unroll
         for (int i = 0; i < kTWRegs; ++i) wr[i] = win[gw[i]];
     };
-    auto stage = [&]() {
+    auto stage = [&](int c0) {
 #pragma unroll
-        for (int i = 0; i < kTXRegs; ++i) xs[lx[i]] = ((live >> i) & 1u) ? xr[i] : 0.f;
+        for (int i = 0; i < kTXRegs; ++i) {
+            float x;
+            if (HEAD) {
+                // h2[c][m0 + r] of the stride-2 head layer (m0 is even): r = 2j from h1[.][j], r = 2j + 1 from
+                // h1[.][j] (tap 2) and h1[.][j + 1] (tap 0)
+                const int e = tid + 256 * i;
+                const bool slot = e < kCiChunk * (kTPosTile + 1);
+                const int c = c0 + (slot ? e / (kTPosTile + 1) : 0), r = e % (kTPosTile + 1), j = r >> 1;
+                float a = hw2[kHeadNarrow * kHeadWide * 3 + c];
+                for (int c1 = 0; c1 < hd.c1; ++c1) {
+                    const float *w = hw2 + (c1 * c_in + c) * 3;
+                    const float *h = h1 + c1 * kHeadPos + j;
+                    if (r & 1) { a = fmaf(w[0], h[r < kTPosTile ? 1 : 0], a); a = fmaf(w[2], h[0], a); }
+                    else a = fmaf(w[1], h[0], a);
+                }
+                x = leaky_m(a, slope);
+            } else {
+                x = xr[i];
+            }
+            xs[lx[i]] = ((live >> i) & 1u) ? x : 0.f;
+        }
 #pragma unroll
         for (int i = 0; i < kTWRegs; ++i) ws[tid + 256 * i] = wr[i];
     };
@@ -277,9 +370,37 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
     for (int r = 0; r < 16; ++r) { even[r] = 0.f; odd[r] = 0.f; }
 
     fetch(0);
+    if (HEAD) {   // after the first fetch, so that the deep layer's weights are on their way meanwhile
+        const long long pz = (long long)(m0 / 2) - 1;   // first position of the z stretch
+        for (int i = tid; i < hd.c0 * (kHeadPos + 2); i += 256) {
+            const int c = i / (kHeadPos + 2), j = i % (kHeadPos + 2);
+            const long long q = pz + j;
+            hz[i] = (q >= 0 && q < (long long)hd.l_z) ? in[(size_t)c * hd.l_z + q] : 0.f;
+        }
+        for (int i = tid; i < hd.c0 * hd.c1 * 3; i += 256) hw1[i] = hd.w1[i];
+        for (int i = tid; i < hd.c1; i += 256) hw1[kHeadNarrow * kHeadNarrow * 3 + i] = hd.b1[i];
+        for (int i = tid; i < hd.c1 * c_in * 3; i += 256) hw2[i] = hd.w2[i];
+        for (int i = tid; i < c_in; i += 256) hw2[kHeadNarrow * kHeadWide * 3 + i] = hd.b2[i];
+        __syncthreads();
+        // stride-1 transposed layer: h1[c][p] = act(b1[c] + sum_cz (w1[cz][c][0] z[cz][p+1] + w1[cz][c][1] z[cz][p]
+        // + w1[cz][c][2] z[cz][p-1])); positions outside [0, l_z) hold 0
+        for (int i = tid; i < hd.c1 * kHeadPos; i += 256) {
+            const int c = i / kHeadPos, j = i % kHeadPos;   // p = m0/2 + j, z stretch index of p is j + 1
+            float a = hw1[kHeadNarrow * kHeadNarrow * 3 + c];
+            for (int cz = 0; cz < hd.c0; ++cz) {
+                const float *w = hw1 + (cz * hd.c1 + c) * 3;
+                const float *z = hz + cz * (kHeadPos + 2) + j;
+                a = fmaf(w[0], z[2], a);
+                a = fmaf(w[1], z[1], a);
+                a = fmaf(w[2], z[0], a);
+            }
+            h1[i] = (uint64_t)(m0 / 2) + j < hd.l_z ? leaky_m(a, slope) : 0.f;
+        }
+        // the first barrier of the contraction loop orders these stores before their first use in stage()
+    }
     for (int c0 = 0; c0 < c_in; c0 += kCiChunk) {
         __syncthreads();
-        stage();
+        stage(c0);
         __syncthreads();
         if (c0 + kCiChunk < c_in) fetch(c0 + kCiChunk);
         // lanes 0..31 take the chunk's first eight input channels, lanes 32..63 its last eight
@@ -345,11 +466,33 @@ bool launch_convt3s2_mfma(const float *in, float *out, const LayerDev &l, uint32
     const uint32_t m_count = (l_out + 1) / 2;
     dim3 grid((m_count + kTPosTile - 1) / kTPosTile, l.c_out / 32, batch);
     if (tail)
-        hipLaunchKernelGGL(k_convt3s2_mfma<true>, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
-                           (int)act, slope, tail->w, tail->b, (int)tail_act);
+        hipLaunchKernelGGL((k_convt3s2_mfma<true, false>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
+                           l_out, (int)act, slope, tail->w, tail->b, (int)tail_act, ConvtHead{});
     else
-        hipLaunchKernelGGL(k_convt3s2_mfma<false>, grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
-                           (int)act, slope, nullptr, nullptr, 0);
+        hipLaunchKernelGGL((k_convt3s2_mfma<false, false>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
+                           l_out, (int)act, slope, nullptr, nullptr, 0, ConvtHead{});
+    return true;
+}
+
+// The first three layers of a decoder in one launch: h1 (kernel 3, stride 1) and h2 (kernel 3, stride 2), both
+// narrow and both followed by the non-linearity, are evaluated inside the staging of the deep layer `l`.
+// z: [batch][h1.c_in][l_z]; l_in: input length of `l` (= output length of h2, 2 l_z or 2 l_z - 1); l_out: its
+// output length.
+bool launch_convt3s2_mfma_head(const float *z, float *out, const LayerDev &h1, const LayerDev &h2, const LayerDev &l,
+                               uint32_t l_z, uint32_t l_in, uint32_t l_out, int batch, bool act, float slope,
+                               hipStream_t st) {
+    if (!l.wt || l.ksize != 3 || l.stride != 2 || l.c_in % kCiChunk != 0 || l.c_out % 32 != 0) return false;
+    if ((uint64_t)l_in * kCiChunk >= (1ull << 32) || (uint64_t)l.c_in * 3 * l.c_out >= (1ull << 32)) return false;
+    if (!(h1.ksize == 3 && h1.stride == 1 && h2.ksize == 3 && h2.stride == 2 && h1.c_out == h2.c_in && h2.c_out == l.c_in &&
+          h1.c_in <= kHeadNarrow && h1.c_out <= kHeadNarrow && l.c_in <= kHeadWide))
+        return false;
+    if (!(l_in == 2 * l_z || l_in + 1 == 2 * l_z)) return false;
+    if (l_out == 0) return true;
+    const uint32_t m_count = (l_out + 1) / 2;
+    dim3 grid((m_count + kTPosTile - 1) / kTPosTile, l.c_out / 32, batch);
+    const ConvtHead hd{h1.w, h1.b, h2.w, h2.b, h1.c_in, h1.c_out, l_z};
+    hipLaunchKernelGGL((k_convt3s2_mfma<false, true>), grid, dim3(256), 0, st, z, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                       (int)act, slope, nullptr, nullptr, 0, hd);
     return true;
 }
 

@@ -602,6 +602,14 @@ static lgc_status run_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, 
     const float *cur = vals;
     for (size_t l = 0; l < nl; ++l) {
         const bool last = l + 1 == nl;
+        if (l == 0 && nl > 2) {   // the one-channel first layer inside the staging of the deep layer after it
+            if (launch_conv3s2_mfma_head(vals, ctx->act[1], ae->enc_dev[0], ae->enc_dev[1], (uint32_t)len[0], (uint32_t)len[1],
+                                         (uint32_t)len[2], batch, true, ae->slope, st)) {
+                cur = ctx->act[1];
+                ++l;
+                continue;
+            }
+        }
         if (l + 1 < nl) {   // a deep layer and the kernel-1 layer after it in one launch, where the shapes allow
             const bool next_last = l + 2 == nl;
             float *dst2 = next_last ? latent : ctx->act[(l + 1) & 1];
@@ -658,6 +666,15 @@ static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent
     const float *cur = latent;
     for (size_t l = 0; l < nl; ++l) {
         const bool last = l + 1 == nl;
+        if (l == 0 && nl > 3) {   // the two narrow first layers inside the staging of the deep layer after them
+            if (launch_convt3s2_mfma_head(latent, ctx->act[0], ae->dec_dev[0], ae->dec_dev[1], ae->dec_dev[2], (uint32_t)in_len,
+                                          (uint32_t)out_len[1], (uint32_t)out_len[2], batch, true, ae->slope, st)) {
+                cur = ctx->act[0];
+                in_len = out_len[2];
+                l = 2;
+                continue;
+            }
+        }
         if (l + 1 < nl && !innov) {   // a deep layer and the kernel-1 layer after it in one launch, where the shapes allow
             const bool next_last = l + 2 == nl;
             float *dst2 = next_last ? rec : ctx->act[(l + 1) & 1];

@@ -162,8 +162,13 @@ void launch_weights_contraction_major(const float *w, float *wt, int c_in, int c
 // (64 -> at most 4 channels after a convolution, 32 -> 1 after a transposed one); `out` is then the tail's output
 bool launch_conv3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
                          bool act, float slope, hipStream_t st, const LayerDev *tail = nullptr, bool tail_act = false);
+bool launch_conv3s2_mfma_head(const float *x, float *out, const LayerDev &head, const LayerDev &l, uint32_t l_x,
+                              uint32_t l_in, uint32_t l_out, int batch, bool act, float slope, hipStream_t st);
 bool launch_convt3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
                           bool act, float slope, hipStream_t st, const LayerDev *tail = nullptr, bool tail_act = false);
+bool launch_convt3s2_mfma_head(const float *z, float *out, const LayerDev &h1, const LayerDev &h2, const LayerDev &l,
+                               uint32_t l_z, uint32_t l_in, uint32_t l_out, int batch, bool act, float slope,
+                               hipStream_t st);
 void launch_gather_at(float *v, float *u, uint64_t stride, uint32_t n, int batch, const uint32_t *idx, uint32_t k,
                       float *out, Stats *stats, hipStream_t st);
 void launch_average(const float *x, uint32_t len, int batch, float scale, float *out, hipStream_t st);
