@@ -6,8 +6,10 @@
 // 3 c_in inputs under the window (contraction depth 192 .. 768), and a kernel-3 / stride-2
 // transposed convolution is two such products (even and odd output positions, depth c_in and
 // 2 c_in).  These run here as implicit GEMMs in fp32 on the MFMA units (fp32 in, fp32 accumulate:
-// the 1e-4 parity bar against the fp64 oracle rules out bf16 / fp16 inputs).  The first and last
-// layers of each stack (1 or 4 channels on one side) stay on the per-layer vector kernels.
+// the 1e-4 parity bar against the fp64 oracle rules out bf16 / fp16 inputs).  The narrow first
+// layers of each stack (1 or 4 channels on one side) are evaluated inside the input staging of the
+// deep layer after them, the kernel-1 layers that end the stacks in the epilogue of the deep layer
+// before them.
 //
 // Operand layout of v_mfma_f32_32x32x2_f32 (checked on the device): lane l supplies
 // A[i = l % 32][k = l / 32] and B[k = l / 32][j = l % 32]; of the 16 results of lane l, number r
