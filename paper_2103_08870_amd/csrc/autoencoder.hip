@@ -298,68 +298,90 @@ void launch_scatter(const float *vals, const uint32_t *idx, uint32_t k, float sc
 // node's positions in ascending order.  The thread of (node b, entry j) looks its position up in
 // every other node's list; the thread of the first node that holds the position owns it and adds
 // the contributions of all holders in node order; the other holders' threads leave it alone.  No
-// atomics, no waiting.  The look-up is a chain of dependent loads, so it is kept short: every
-// block first copies up to 1024 evenly spaced entries of each list into LDS (one round of loads),
-// searches those there, and is left with `stride` entries of the list itself to search.
+// atomics, no waiting.  A look-up is a chain of dependent loads, so a block does it once for all
+// of its 256 entries: 16 lanes per other list and bound find, by 16-way search (log16 k rounds of
+// loads), the stretch of that list between the block's first and last position; the stretches are
+// copied to LDS (they hold about as many entries as the block's own, the nodes' selections being
+// alike) and every thread searches them there.  A stretch too long for LDS is searched in place.
 constexpr int kScatterNodes = 8;
-constexpr int kScatterSamples = 1024;
+constexpr int kScatterWin = 1024;
 
 __global__ __launch_bounds__(256) void k_scatter_nodes(const float *__restrict__ vals,
                                                        const uint32_t *__restrict__ idx, uint32_t k, int batch,
                                                        float scale, float *__restrict__ dense, uint32_t n,
-                                                       uint32_t stride, uint32_t steps, Stats *stats) {
-    __shared__ uint32_t smp[kScatterNodes][kScatterSamples];
-    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
-    const int b = blockIdx.y;
-    const uint32_t nsmp = (k + stride - 1) / stride;   // <= kScatterSamples; sample t is entry t * stride
+                                                       Stats *stats) {
+    __shared__ uint32_t win[kScatterNodes][kScatterWin];
+    __shared__ uint32_t w_lo[kScatterNodes], w_hi[kScatterNodes];
+    const int tid = threadIdx.x, b = blockIdx.y;
+    const uint32_t j0 = blockIdx.x * 256, j = j0 + tid;   // j0 < k: the grid has ceil(k / 256) blocks
+    const uint32_t *own_list = idx + (size_t)b * k;
     const bool mine = j < k;
-    const uint32_t i = mine ? idx[(size_t)b * k + j] : 0u;
-    const uint32_t before = (mine && j > 0) ? idx[(size_t)b * k + j - 1] : 0u;
+    const uint32_t i = mine ? own_list[j] : 0u;
+    const uint32_t before = (mine && j > 0) ? own_list[j - 1] : 0u;
+    const uint32_t first = own_list[j0], last = own_list[k - j0 > 256 ? j0 + 255 : k - 1];
+    // loaded now, used at the end: only the owner of a position ever writes it, and it reads first
+    const float base = (mine && i < n) ? dense[i] : 0.f, own = mine ? vals[(size_t)b * k + j] : 0.f;
+    {
+        // search g = tid / 16: list g / 2, its first entry >= first (even g) or > last (odd g)
+        const int g = tid >> 4, t = tid & 15, o = g >> 1;
+        const bool active = o < batch && o != b;
+        const uint32_t target = (g & 1) ? last + 1 : first;
+        const uint32_t *list = idx + (size_t)(active ? o : b) * k;
+        // everything below lo is < target, everything from hi on is >= target
+        uint32_t lo = 0, hi = active ? k : 0u;
+        while (__any(lo < hi)) {   // all lanes of the wavefront take part in the ballot
+            const uint32_t len = hi - lo, step = (len + 15) / 16;
+            const uint32_t p = lo + (uint32_t)t * step;
+            const bool probe = lo < hi && p < hi;
+            const uint32_t x = probe ? list[p] : 0xffffffffu;
+            const unsigned long long m = __ballot(probe && x < target);
+            const uint32_t c = (uint32_t)__popc((uint32_t)(m >> (tid & 48)) & 0xffffu);   // probes of this search below the target
+            if (lo < hi) {
+                const uint32_t probes = (len + step - 1) / step;
+                const uint32_t nlo = c ? lo + (c - 1) * step + 1 : lo;
+                hi = c < probes ? lo + c * step : hi;
+                lo = nlo;
+            }
+        }
+        if (t == 0 && active) { if (g & 1) w_hi[o] = lo; else w_lo[o] = lo; }
+    }
+    __syncthreads();
     for (int o = 0; o < batch; ++o) {
         if (o == b) continue;   // uniform
-        for (uint32_t t = threadIdx.x; t < nsmp; t += 256) smp[o][t] = idx[(size_t)o * k + (size_t)t * stride];
+        const uint32_t lo = w_lo[o], hi = w_hi[o], len = hi > lo ? hi - lo : 0u;
+        if (len <= (uint32_t)kScatterWin)
+            for (uint32_t t = tid; t < len; t += 256) win[o][t] = idx[(size_t)o * k + lo + t];
     }
     __syncthreads();
     if (!mine) return;
     if (j > 0 && before >= i) atomicAdd(&stats->errors, 1u);   // not ascending
     if (i >= n) { atomicAdd(&stats->errors, 1u); return; }
-    const float base = dense[i], own = vals[(size_t)b * k + j];
-    // per other node: [lo, hi) of its list still to search for the first entry >= i; hv = the entry
-    // at hi (0xffffffff when hi == k, which no valid position equals)
-    uint32_t lo[kScatterNodes], hi[kScatterNodes], hv[kScatterNodes];
+    // per other node: is i in its list, and where
+    bool held[kScatterNodes];
+    uint32_t at[kScatterNodes];
 #pragma unroll
     for (int o = 0; o < kScatterNodes; ++o) {
-        lo[o] = hi[o] = 0; hv[o] = 0xffffffffu;
+        held[o] = false; at[o] = 0;
         if (o < batch && o != b) {
-            uint32_t tl = 0, th = nsmp;                 // first sample >= i
-            while (tl < th) {
-                const uint32_t mid = (tl + th) >> 1;
-                if (smp[o][mid] < i) tl = mid + 1; else th = mid;
+            const uint32_t wl = w_lo[o], wh = w_hi[o], len = wh > wl ? wh - wl : 0u;
+            uint32_t lo = 0, hi = len;   // first entry of the stretch that is >= i
+            if (len <= (uint32_t)kScatterWin) {
+                while (lo < hi) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (win[o][mid] < i) lo = mid + 1; else hi = mid;
+                }
+                held[o] = lo < len && win[o][lo] == i;
+            } else {
+                const uint32_t *list = idx + (size_t)o * k + wl;
+                while (lo < hi) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (list[mid] < i) lo = mid + 1; else hi = mid;
+                }
+                held[o] = lo < len && list[lo] == i;
             }
-            if (tl < nsmp) { hi[o] = tl * stride; hv[o] = smp[o][tl]; } else hi[o] = k;
-            lo[o] = tl == 0 ? 0u : (tl - 1) * stride + 1;   // sample tl - 1 is < i
-            if (lo[o] > hi[o]) lo[o] = hi[o];
+            at[o] = wl + lo;
         }
     }
-    for (uint32_t s = 0; s < steps; ++s) {
-        uint32_t probe[kScatterNodes];
-#pragma unroll
-        for (int o = 0; o < kScatterNodes; ++o) {
-            const uint32_t mid = (lo[o] + hi[o]) >> 1;
-            probe[o] = lo[o] < hi[o] ? idx[(size_t)o * k + mid] : 0u;
-        }
-#pragma unroll
-        for (int o = 0; o < kScatterNodes; ++o) {
-            const uint32_t mid = (lo[o] + hi[o]) >> 1;
-            if (lo[o] < hi[o]) {
-                if (probe[o] < i) lo[o] = mid + 1; else { hi[o] = mid; hv[o] = probe[o]; }
-            }
-        }
-    }
-    // lo[o] == hi[o] = first entry of node o that is >= i (k if none), hv[o] its value
-    bool held[kScatterNodes];
-#pragma unroll
-    for (int o = 0; o < kScatterNodes; ++o) held[o] = o < batch && o != b && hv[o] == i;
     bool owner = true;
 #pragma unroll
     for (int o = 0; o < kScatterNodes; ++o) owner = owner && !(o < b && held[o]);
@@ -367,7 +389,7 @@ __global__ __launch_bounds__(256) void k_scatter_nodes(const float *__restrict__
     float acc = __fadd_rn(base, __fmul_rn(scale, own));
 #pragma unroll
     for (int o = 0; o < kScatterNodes; ++o)
-        if (o > b && held[o]) acc = __fadd_rn(acc, __fmul_rn(scale, vals[(size_t)o * k + hi[o]]));
+        if (o > b && held[o]) acc = __fadd_rn(acc, __fmul_rn(scale, vals[(size_t)o * k + at[o]]));
     dense[i] = acc;
 }
 
@@ -375,11 +397,8 @@ bool launch_scatter_nodes(const float *vals, const uint32_t *idx, uint32_t k, in
                           uint32_t n, Stats *stats, hipStream_t st) {
     if (batch > kScatterNodes) return false;
     if (k == 0) return true;
-    const uint32_t stride = (k + kScatterSamples - 1) / kScatterSamples;
-    uint32_t steps = 0;
-    while ((1u << steps) < stride) ++steps;   // a binary search over at most stride - 1 entries ends within this many halvings
     hipLaunchKernelGGL(k_scatter_nodes, dim3((k + 255) / 256, batch), dim3(256), 0, st, vals, idx, k, batch, scale,
-                       dense, n, stride, steps, stats);
+                       dense, n, stats);
     return true;
 }
 

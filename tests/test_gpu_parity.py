@@ -323,6 +323,29 @@ def test_scatter_nodes_in_order(B, oracle, K, k):
     ctx.close()
 
 
+def test_scatter_nodes_with_unlike_densities(B, oracle):
+    """Node lists of very different local density: where one node's positions are spread out and another's are
+    packed, the stretch of the packed list that faces one block of the sparse one is longer than the block's
+    on-chip window (1024 entries) and is searched in place; the packed node's blocks face empty stretches."""
+    n, k, K = 2_000_000, 20_000, 3
+    rng = np.random.default_rng(11)
+    spread = np.sort(rng.choice(n, k, replace=False))
+    packed = np.arange(700_000, 700_000 + 2 * k, 2)                      # every other position of a short range
+    mixed = np.sort(np.concatenate([spread[: k // 2], np.setdiff1d(packed, spread[: k // 2])[: k - k // 2]]))
+    idx = np.stack([spread, packed, np.sort(mixed)]).astype(np.uint32)
+    assert all((np.diff(idx[b].astype(np.int64)) > 0).all() for b in range(K))
+    vals = rng.standard_normal((K, k)).astype(np.float32)
+    ctx = B.Context(n, k, K)
+    dense = torch.zeros(n, device="cuda")
+    B.lgc_scatter(ctx, dev(vals), dev(idx.astype(np.int32)), 0.5, dense)
+    ref = np.zeros(n, np.float32)
+    for b in range(K):
+        oracle.scatter(vals[b], idx[b], 0.5, ref)
+    assert B.lgc_stats(ctx)[2] == 0
+    assert same_bits(dense, ref)
+    ctx.close()
+
+
 def test_scatter_bad_positions_are_counted(B, oracle):
     n, k = 100_000, 3000
     rng = np.random.default_rng(5)
