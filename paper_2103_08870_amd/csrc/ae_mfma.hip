@@ -22,6 +22,7 @@
 namespace lgc {
 
 typedef float acc16 __attribute__((ext_vector_type(16)));
+typedef float f4v __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float leaky_m(float x, float slope) { return x > 0.f ? x : slope * x; }
 
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
     // (a second pair of buffers, with one barrier per chunk, was tried: it costs a resident block per
     // compute unit and gains nothing)
     __shared__ float xs[kCiChunk * kRowPad + 1];
-    __shared__ float ws[kCiChunk * 3 * 64];
+    __shared__ __align__(16) float ws[kCiChunk * 3 * 64];
     __shared__ float head_x[HEAD ? 4 * kPosTile + 4 : 1];   // x[4 p0 - 3 .. 4 p0 + 255], zeros outside [0, l_head)
     __shared__ float head_p[HEAD ? 4 * kHeadMaxC : 1];      // per channel: the three taps, then the bias
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -122,8 +123,11 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
         gx[i] = ok ? (uint32_t)(ci * (size_t)l_in + q) : 0u;
         live |= (uint32_t)ok << i;
     }
-    const uint32_t gw0 = (uint32_t)((tid >> 6) * c_out + co0 + (tid & 63));   // slot e = tid + 256 i: row (tid >> 6) + 4 i
-    float xr[HEAD ? 1 : kXRegs], wr[kWRegs];
+    // weights: 16-byte loads (the load instructions' issue rate, not their bytes, is what the staging costs);
+    // group f = tid + 256 i of four channels: row f / 16 = (tid >> 4) + 16 i of the chunk's 48, channels 4 (f % 16) ..
+    const uint32_t gw0 = (uint32_t)((tid >> 4) * c_out + co0 + (tid & 15) * 4);
+    float xr[HEAD ? 1 : kXRegs];
+    f4v wr[kWRegs / 4];
     auto fetch = [&](int c0) {
         const float *win = wt + (size_t)c0 * 3 * c_out + gw0;
         if (!HEAD) {
@@ -132,7 +136,7 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
             for (int i = 0; i < kXRegs; ++i) xr[i] = xin[gx[i]];
         }
 #pragma unroll
-        for (int i = 0; i < kWRegs; ++i) wr[i] = win[(size_t)(4 * i) * c_out];
+        for (int i = 0; i < kWRegs / 4; ++i) wr[i] = *(const f4v *)(win + (size_t)(16 * i) * c_out);
     };
     auto stage = [&](int c0) {
 #pragma unroll
@@ -158,7 +162,7 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
             xs[slot] = ((live >> i) & 1u) ? x : 0.f;
         }
 #pragma unroll
-        for (int i = 0; i < kWRegs; ++i) ws[tid + 256 * i] = wr[i];
+        for (int i = 0; i < kWRegs / 4; ++i) *(f4v *)(ws + (tid + 256 * i) * 4) = wr[i];
     };
 
     acc16 acc;
