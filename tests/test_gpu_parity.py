@@ -300,6 +300,39 @@ def test_paper_size_autoencoder(B, oracle, k):
     ctx.close(); ae.close()
 
 
+STACKS = [
+    # narrow first layers at the fused kernels' limits (16 channels into the first deep layer; 3 -> 8 -> 32 in
+    # front of the deep decoder layer), kernel-1 layers at both ends
+    ([(1, 16, 3, 2), (16, 64, 3, 2), (64, 3, 1, 1)], [(3, 8, 3, 1), (8, 32, 3, 2), (32, 32, 3, 2), (32, 1, 1, 1)]),
+    # a deep stack whose shapes fit none of the fused forms: every layer on its own
+    ([(1, 24, 3, 2), (24, 40, 3, 2), (40, 5, 3, 1)], [(5, 40, 3, 1), (40, 24, 3, 2), (24, 1, 3, 2)]),
+    # deep layers without narrow neighbours to fuse: 1 -> 32 (kernel 1) -> 64 -> 128 and back
+    ([(1, 32, 1, 1), (32, 64, 3, 2), (64, 128, 3, 2)], [(128, 64, 3, 2), (64, 32, 3, 2), (32, 1, 3, 1)]),
+]
+
+
+@pytest.mark.parametrize("stack", range(len(STACKS)))
+@pytest.mark.parametrize("k", [3, 50, 1000, 4099])
+def test_autoencoder_of_other_shapes(B, oracle, stack, k):
+    """Layer lists other than the benchmark's and the paper's: whichever kernels the library picks for them
+    (fused narrow layers, matrix cores, per-layer vector kernels), the result is the oracle's."""
+    enc, dec = STACKS[stack]
+    ew, eb, dw, db = synth.ae_weights(enc, dec, device="cuda")
+    ae = B.Autoencoder(enc, dec, ew, eb, dw, db, slope=0.05)
+    hw = [[t.cpu().numpy() for t in xs] for xs in (ew, eb, dw, db)]
+    ctx = B.Context(1 << 16, 1 << 16, 3)
+    x = np.random.default_rng(k).laplace(0, 1e-2, (3, k)).astype(np.float32)
+    lat = torch.zeros((3, B.lgc_latent_len(ae, k)), device="cuda")
+    rec = torch.zeros((3, k), device="cuda")
+    B.lgc_encode(ctx, ae, dev(x), lat)
+    B.lgc_decode(ctx, ae, lat, rec)
+    for b in range(3):
+        ol = oracle.encode(x[b], enc, hw[0], hw[1], slope=0.05)
+        assert rel_l2(lat[b], ol) <= REL_L2_TOL
+        assert rel_l2(rec[b], oracle.decode(ol, k, enc, dec, hw[2], hw[3], slope=0.05)) <= 2 * REL_L2_TOL
+    ctx.close(); ae.close()
+
+
 # ------------------------------------------------------------------------------ a5
 
 @pytest.mark.parametrize("K,k", [(1, 3000), (2, 1), (3, 257), (4, 3001), (8, 25_600), (9, 700)])
