@@ -178,6 +178,42 @@ def test_topk_heavy_tail_beyond_histogram_range(B, oracle):
     ctx.close()
 
 
+def adversarial_inputs(n, k, rng):
+    """Magnitude layouts that stress the sampled estimate, the tie rule and the order of the output, at sizes
+    that take the fast path first (whichever path ends up serving them, the result must be the oracle's)."""
+    ramp = np.arange(1, n + 1, dtype=np.float32) * np.float32(2.0 ** -24)
+    sign = np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+    yield "ascending magnitudes", ramp * sign
+    yield "descending magnitudes", ramp[::-1] * sign
+    two = np.full(n, 1e-4, np.float32)
+    two[rng.choice(n, 3 * k, replace=False)] = 1.0              # 3k equal large values: the cut is inside them
+    yield "cut inside a large tie group", two * sign
+    sparse = np.zeros(n, np.float32)
+    sparse[rng.choice(n, k // 2, replace=False)] = rng.standard_normal(k // 2).astype(np.float32)
+    sparse[rng.choice(n, 100, replace=False)] *= -0.0           # some negative zeros among the ties
+    yield "fewer non-zeros than k", sparse
+    blocks = rng.standard_normal(n).astype(np.float32) * 1e-3
+    blocks[n // 2: n // 2 + 2 * k] *= 1e3                        # everything selected sits in one short stretch
+    yield "selection clustered in one stretch", blocks
+    wild = rng.standard_normal(n).astype(np.float32)
+    wild[rng.choice(n, 50, replace=False)] = np.inf
+    wild[rng.choice(n, 50, replace=False)] = -np.inf
+    wild[rng.choice(n, 20, replace=False)] = np.nan
+    yield "infinities and NaNs", wild
+    steps = (np.floor(rng.random(n) * 16) * 0.25 + 0.25).astype(np.float32)   # 16 distinct magnitudes
+    yield "sixteen distinct magnitudes", steps * sign
+
+
+@pytest.mark.parametrize("n,k", [((1 << 20) + 77, 1500), (2_500_000, 40_000)])
+def test_topk_adversarial_layouts(B, oracle, n, k):
+    rng = np.random.default_rng(n)
+    ctx = B.Context(n, k, 1)
+    u0 = rng.standard_normal((1, n)).astype(np.float32)
+    for name, v in adversarial_inputs(n, k, rng):
+        run_topk(B, oracle, ctx, v[None, :].copy(), u0, k)
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------ a1+a2 fused
 
 def run_iterations(B, oracle, w, ks, iters, force_exact=False, check_every=1):

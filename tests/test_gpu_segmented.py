@@ -219,3 +219,21 @@ def test_argument_errors(B):
     with pytest.raises(B.LgcError):
         B.lgc_topk_segmented(ctx, seg, v, None, torch.zeros(6, device="cuda"), torch.zeros(6, device="cuda", dtype=torch.int32))
     seg.close(); ctx.close()
+
+
+def test_adversarial_layouts_per_layer(B, oracle):
+    """The magnitude layouts of test_topk_adversarial_layouts under a per-layer plan of large (sampled) and
+    small layers: ramps, a cut inside a tie group, mostly zeros, one hot stretch, infinities and NaNs."""
+    from test_gpu_parity import adversarial_inputs
+    n = 2_300_000
+    rng = np.random.default_rng(9)
+    off = np.unique(np.concatenate([[0, n], rng.choice(np.arange(1, n), 11, replace=False),
+                                    900_000 + np.arange(1, 30) * 500]))      # 12 large layers, 29 of 500 elements
+    lens = np.diff(off)
+    ks = np.maximum(1, lens // 60)
+    ctx = B.Context(n, int(ks.sum()), 1)
+    seg = B.Segments(off.tolist(), ks.tolist())
+    u0 = rng.standard_normal((1, n)).astype(np.float32)
+    for name, v in adversarial_inputs(n, int(ks.sum()), rng):
+        run_segmented(B, oracle, ctx, seg, off, ks, v[None, :].copy(), u0)
+    seg.close(); ctx.close()
