@@ -87,3 +87,49 @@ def test_resume_from_saved_residuals(B, selection):
         for x, y in zip(a, b):
             assert bits_equal(x, y), t
     ae.close()
+
+
+@pytest.mark.parametrize("force_exact", [False, True])
+def test_two_contexts_on_two_streams(B, force_exact):
+    """Two contexts, each on a stream of its own, run their iterations at the same time on the one GPU (the
+    exact path's persistent kernels of both share the compute units): each gives what it gives alone."""
+    w = synth.workload(2, n=1_500_000, nodes=2)
+    K, n, k = w.nodes, w.n, w.k
+    gs = [synth.gradients(w, t, device="cuda") for t in range(3)]
+
+    def state():
+        return dict(u=torch.zeros((K, n), device="cuda"), v=torch.zeros((K, n), device="cuda"),
+                    vals=torch.zeros((K, k), device="cuda"), idx=torch.zeros((K, k), device="cuda", dtype=torch.int32))
+
+    def make_ctx():
+        ctx = B.Context(n, k, K)
+        if force_exact:
+            B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 1)
+        return ctx
+
+    def run(ctx, s, order):
+        for t in order:
+            B.lgc_accumulate_topk(ctx, gs[t], s["u"], s["v"], w.momentum, k, s["vals"], s["idx"])
+
+    orders = ([0, 1, 2, 0], [2, 1, 0, 1])
+    alone = []
+    for order in orders:                       # each on its own, default stream
+        ctx, s = make_ctx(), state()
+        run(ctx, s, order)
+        torch.cuda.synchronize()
+        assert B.lgc_stats(ctx)[2] == 0
+        ctx.close()
+        alone.append(s)
+    ctxs, together = [make_ctx(), make_ctx()], [state(), state()]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for t in range(4):                         # interleaved submission, one call per stream at a time
+        for c in range(2):
+            with torch.cuda.stream(streams[c]):
+                run(ctxs[c], together[c], orders[c][t:t + 1])
+    torch.cuda.synchronize()
+    for c in range(2):
+        assert B.lgc_stats(ctxs[c])[2] == 0
+        for key in alone[c]:
+            assert bits_equal(together[c][key], alone[c][key]), (c, key)
+        ctxs[c].close()
