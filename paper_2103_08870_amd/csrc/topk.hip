@@ -124,11 +124,16 @@ __global__ __launch_bounds__(1024) void k_sample(SelArgs a) {
     }
     const size_t off = (size_t)node * a.stride;
     // four neighbouring threads read one 64-byte cluster of 16 elements; the clusters sit at
-    // jittered positions, one in each of kSampleGroups/4 equal strata of the vector
+    // jittered positions, one in each of kSampleGroups/4 strata of the vector
     const uint32_t j = blockIdx.x * 1024u + tid;  // < kSampleGroups
     const uint32_t cl = j >> 2;
-    const uint32_t stratum = (a.n >> 4) / (kSampleGroups / 4);
-    const uint32_t e = ((cl * stratum + mix32(cl + 0x5bd1e995u * (uint32_t)node) % stratum) << 4) + ((j & 3u) << 2);
+    // stratum cl = clusters [cl * C / 4096, (cl + 1) * C / 4096) of the vector's C = n / 16 whole clusters: the
+    // strata cover the vector evenly whatever n is (n >= kMinFastN makes none of them empty)
+    static_assert(kSampleGroups / 4 == 4096 && kMinFastN >= 16 * 4096, "4096 strata of at least one cluster");
+    const uint32_t clusters = a.n >> 4;
+    const uint32_t s_lo = (uint32_t)(((unsigned long long)cl * clusters) >> 12);
+    const uint32_t s_hi = (uint32_t)(((unsigned long long)(cl + 1) * clusters) >> 12);
+    const uint32_t e = ((s_lo + mix32(cl + 0x5bd1e995u * (uint32_t)node) % (s_hi - s_lo)) << 4) + ((j & 3u) << 2);
     uint32_t *smp = a.samples + (size_t)node * kSample;
     uint32_t *sh = a.sample_hist + node * kSampleBins;
     for (int i = tid; i < kSampleBins; i += 1024) hist[i] = 0;

@@ -99,7 +99,7 @@ def run_topk(B, oracle, ctx, v0, u0, k, expect_path=None):
             assert same_bits(du[b], u1)
 
 
-@pytest.mark.parametrize("n", [1, 2, 63, 64, 1000, 4096, 4097, 50_000, 300_001])
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 1000, 4096, 4097, 50_000, 130_001])
 def test_topk_exact_path_small(B, oracle, n):
     rng = np.random.default_rng(n)
     ctx = B.Context(n, n, 2)
@@ -129,7 +129,9 @@ def test_topk_special_values(B, oracle):
 
 
 # the last two cases have long candidate lists (second-level histogram by many blocks, look-back output)
-@pytest.mark.parametrize("n,k", [(1 << 20, 1024), (1_300_007, 1300), (3_000_001, 300), (2_000_000, 60_000),
+# the first three are just above the smallest vector that takes the fast path (2^17 elements)
+@pytest.mark.parametrize("n,k", [(1 << 17, 131), (150_001, 150), (600_001, 6000),
+                                 (1 << 20, 1024), (1_300_007, 1300), (3_000_001, 300), (2_000_000, 60_000),
                                  (3_000_000, 150_000), (5_000_001, 400_000)])
 def test_topk_fast_path_and_forced_exact(B, oracle, n, k):
     rng = np.random.default_rng(k)
@@ -255,7 +257,7 @@ def test_fused_iterations_match_oracle(B, oracle, cfg, n):
 def test_fused_exact_path_iterations(B, oracle):
     w = synth.workload(2, n=1_200_000, nodes=2)
     run_iterations(B, oracle, w, w.ks, iters=3, force_exact=True)
-    w = synth.workload(5, n=300_000, nodes=1)          # below the fast path's minimum size
+    w = synth.workload(5, n=120_000, nodes=1)          # below the fast path's minimum size
     run_iterations(B, oracle, w, w.ks, iters=3)
 
 
