@@ -41,7 +41,7 @@ constexpr uint32_t kSuperRows = 8192;           // rows per group whose candidat
 constexpr uint32_t kRowsPerLaunch = 104 * 1024;
 
 // Per-node selection state, device memory.  It lives in a "state set" together with the
-// histograms and look-back status words; there are two sets, used by alternate calls, and each
+// histograms and chunk / block counts; there are two sets, used by alternate calls, and each
 // call clears the set of the next one.
 struct Sel {
     uint32_t t_est;       // fast path: candidates are the elements with key >= t_est
@@ -79,8 +79,8 @@ struct SelArgs {
     uint32_t rank;    // rank of the sample's order statistic used as estimate
     uint32_t cap;     // capacity of the gathered candidate list, per node
     uint32_t rows;    // bitmap rows per node (stride of row_count; bitmap stride is rows * kRowWords)
-    uint32_t status_cand_stride, status_exact_stride;  // 64-bit words per node: chunk counts of the candidate list, look-back status
-    uint32_t spin_limit;      // bound of the look-back wait
+    uint32_t status_cand_stride, status_exact_stride;  // 64-bit words per node: chunk counts of the candidate list, block counts of the exact path
+    uint32_t spin_limit;      // bound of the wait at a node barrier
     int force;                // exact path chosen by the host (ignore fast_ok)
     Stats *stats;
     // current state set
@@ -91,7 +91,7 @@ struct SelArgs {
     uint32_t *level2_hist;    // [batch][kFineBins]
     uint32_t *radix_hist;     // [batch][3][kRadixBins]
     unsigned long long *status_cand;   // per 4096-candidate chunk of a long list: keys above T* (high half), equal to T* (low half)
-    unsigned long long *status_exact;  // look-back status of the exact pass over v
+    unsigned long long *status_exact;  // exact path: per block, keys above T* (high half) and equal to it (low half) in its run of v
     // state set of the next call, cleared by this one
     uint32_t *next_state;
     uint32_t next_words;
@@ -125,7 +125,8 @@ void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_
 void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
 void launch_gather(const SelArgs &a, int batch, hipStream_t st);
 void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hipStream_t st);
-void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st);
+int exact_blocks_per_cu();   // how many blocks of the exact-path kernel one compute unit holds (at most 4)
+void launch_exact(const SelArgs &a, int batch, bool vec, int cus, int resident, hipStream_t st);
 // per-layer selection (segmented.hip)
 void launch_seg_estimate(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
 void launch_seg_select(const SelArgs &a, int batch, bool vec, hipStream_t st);

@@ -19,8 +19,8 @@
 //  all and no scattered stores; a small gather kernel lists the flagged elements in index order.
 //  The output over the candidates needs no communication between blocks either: short lists are
 //  read whole by every block, long lists are counted per 4096-candidate chunk by one kernel and
-//  written by the next.  Only the exact path's compaction of v uses a look-back chain over
-//  4096-element chunks, by blocks that are all resident.
+//  written by the next.  The exact path is one persistent kernel whose blocks meet at barriers:
+//  three radix passes, a count of every block's run of v, and the ordered output of the runs.
 
 #include "device_helpers.h"
 
@@ -750,64 +750,92 @@ __global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
     }
 }
 
-// ------------------------------------------------------------------ ordered output compaction
-
-// status word of a chunk: [63:62] 0 = nothing yet, 1 = this chunk's own counts, 2 = counts of all
-// chunks up to and including this one; [61:31] count of "greater", [30:0] count of "equal".
-__device__ __forceinline__ unsigned long long pack_status(uint32_t st, uint32_t gt, uint32_t eq) {
-    return ((unsigned long long)st << 62) | ((unsigned long long)gt << 31) | (unsigned long long)eq;
-}
+// ------------------------------------------------------------------ ordered output of the exact path
 
 // The threshold T* and the tie quota are known.  The selected elements (key > T*, and the first
 // `quota` elements with key == T*) are written to the output in index order and zeroed in v
-// (and u), reading v itself (exact path).  Persistent blocks take the 4096-element chunks in
-// turn (block b: chunks b, b + gridDim.x, ...); a chunk's output offset comes from a look-back
-// over the chunks before it.
+// (and u), reading v itself.  Every block of the node owns a run of consecutive 4096-element chunks.
+// load_chunk: the value bits of this thread's 16 elements of a chunk and their flags (bit r*4+j).
 template <bool VEC>
-__device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, const uint32_t n_src,
-                                            const uint32_t thr, const uint32_t quota) {
-    __shared__ uint32_t sh_gt[kRows][kWaves], sh_eq[kRows][kWaves];
-    __shared__ uint32_t sh_prefix[3];
+__device__ __forceinline__ void load_chunk(const float *__restrict__ v, const uint32_t base, const uint32_t n,
+                                           const uint32_t thr, uint32_t (&bits)[kRows][4], uint32_t &gtm, uint32_t &eqm) {
+    const int tid = threadIdx.x;
+    gtm = 0; eqm = 0;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const uint32_t e0 = base + r * kRowElems + tid * 4;
+        f4 vv = {0.f, 0.f, 0.f, 0.f};
+        if (VEC && e0 + 3 < n) vv = *(const f4 *)(v + e0);
+        else { for (int j = 0; j < 4; ++j) if (e0 + j < n) vv[j] = v[e0 + j]; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bits[r][j] = __float_as_uint(vv[j]);
+            const bool valid = e0 + j < n;
+            const uint32_t key = bits[r][j] & 0x7fffffffu;
+            gtm |= (uint32_t)(valid && key > thr) << (r * 4 + j);
+            eqm |= (uint32_t)(valid && key == thr) << (r * 4 + j);
+        }
+    }
+}
 
+// Phase 1 (before the node's barrier): the block's counts of "greater" and "equal" over its run, stored as
+// totals[blockIdx.x] = greater << 32 | equal.  Phase 2 (after it): the counts of the blocks before this one
+// place the run in the output; the run is then written chunk by chunk with a running offset.  Nothing
+// waits for anything: the barrier between the phases is the only exchange.
+template <bool VEC>
+__device__ __forceinline__ void count_run(const SelArgs &a, const int node, const uint32_t thr,
+                                          const uint32_t c_lo, const uint32_t c_hi) {
+    __shared__ uint32_t sh_cnt[2][kWaves];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    Sel *s = a.sel + node;
-    const uint32_t nchunks = (n_src + kChunk - 1) / kChunk;
+    const float *v = a.v + (size_t)node * a.stride;
+    uint32_t g = 0, e = 0;
+    for (uint32_t chunk = c_lo; chunk < c_hi; ++chunk) {
+        uint32_t bits[kRows][4], gtm, eqm;
+        load_chunk<VEC>(v, chunk * (uint32_t)kChunk, a.n, thr, bits, gtm, eqm);
+        g += (uint32_t)__popc(gtm); e += (uint32_t)__popc(eqm);
+    }
+    g = wave_sum(g); e = wave_sum(e);
+    if (lane == 0) { sh_cnt[0][wave] = g; sh_cnt[1][wave] = e; }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t bg = 0, be = 0;
+        for (int w = 0; w < kWaves; ++w) { bg += sh_cnt[0][w]; be += sh_cnt[1][w]; }
+        st_agent(&a.status_exact[(size_t)node * a.status_exact_stride + blockIdx.x], ((unsigned long long)bg << 32) | be);
+    }
+}
+
+template <bool VEC>
+__device__ __forceinline__ void emit_run(const SelArgs &a, const int node, const uint32_t thr, const uint32_t quota,
+                                         const uint32_t c_lo, const uint32_t c_hi, const uint32_t nchunks) {
+    __shared__ uint32_t sh_gt[kRows][kWaves], sh_eq[kRows][kWaves];
+    __shared__ uint32_t sh_pre[2][kWaves];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t off = (size_t)node * a.stride;
     float *u = a.u ? a.u + off : nullptr;
     float *v = a.v + off;
-    unsigned long long *st = a.status_exact + (size_t)node * a.status_exact_stride;
     uint32_t *oidx = a.out_idx + (size_t)node * a.k;
     float *oval = a.out_vals + (size_t)node * a.k;
+    // selected-or-tied elements of the blocks before this one (their totals were stored before the barrier)
+    const unsigned long long *totals = a.status_exact + (size_t)node * a.status_exact_stride;
+    uint32_t pg = 0, pe = 0;
+    for (uint32_t b = tid; b < blockIdx.x; b += kBlock) {
+        const unsigned long long t = ld_agent(&totals[b]);
+        pg += (uint32_t)(t >> 32); pe += (uint32_t)t;
+    }
+    pg = wave_sum(pg); pe = wave_sum(pe);
+    if (lane == 0) { sh_pre[0][wave] = pg; sh_pre[1][wave] = pe; }
+    __syncthreads();
+    uint32_t pre_gt = 0, pre_eq = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) { pre_gt += sh_pre[0][w]; pre_eq += sh_pre[1][w]; }
 
-    for (uint32_t it = 0;; ++it) {
-        __syncthreads();
-        // block-uniform values are made wave-uniform for the compiler, so that every branch that
-        // leaves or repeats this loop (which contains barriers) is a scalar branch
-        const uint32_t chunk = __builtin_amdgcn_readfirstlane(blockIdx.x + it * gridDim.x);
-        if (chunk >= nchunks) break;
+    for (uint32_t chunk = c_lo; chunk < c_hi; ++chunk) {   // c_lo, c_hi: the same for the whole block
         const uint32_t base = chunk * (uint32_t)kChunk;
-
-        uint32_t bits[kRows][4];   // value bits of my 16 elements
-        uint32_t gtm = 0, eqm = 0; // flag bit r*4+j
-#pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-            const uint32_t e0 = base + r * kRowElems + tid * 4;
-            f4 vv = {0.f, 0.f, 0.f, 0.f};
-            if (VEC && e0 + 3 < n_src) vv = *(const f4 *)(v + e0);
-            else { for (int j = 0; j < 4; ++j) if (e0 + j < n_src) vv[j] = v[e0 + j]; }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bits[r][j] = __float_as_uint(vv[j]);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bool valid = e0 + j < n_src;
-                const uint32_t key = bits[r][j] & 0x7fffffffu;
-                gtm |= (uint32_t)(valid && key > thr) << (r * 4 + j);
-                eqm |= (uint32_t)(valid && key == thr) << (r * 4 + j);
-            }
-        }
-
+        uint32_t bits[kRows][4], gtm, eqm;
+        load_chunk<VEC>(v, base, a.n, thr, bits, gtm, eqm);
         // position of my flagged elements inside the chunk, in index order (row, wave, lane, j)
         uint32_t lane_gt[kRows], lane_eq[kRows];
+        __syncthreads();   // the previous chunk's readers of sh_gt / sh_eq are done
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
             uint32_t lg = 0, le = 0, tg = 0, te = 0;
@@ -831,77 +859,31 @@ __device__ __forceinline__ void emit_chunks(const SelArgs &a, const int node, co
                 blk_gt += sh_gt[r][w]; blk_eq += sh_eq[r][w];
             }
         }
-
-        // look-back over the preceding chunks (first wavefront only)
-        if (wave == 0) {
-            uint32_t pg = 0, pe = 0;
-            bool failed = false;
-            if (chunk == 0) {
-                if (lane == 0) st_agent(&st[0], pack_status(2, blk_gt, blk_eq));
-            } else {
-                if (lane == 0) st_agent(&st[chunk], pack_status(1, blk_gt, blk_eq));
-                int first = (int)chunk - 1;
-                uint32_t spins = 0;
-                while (first >= 0) {
-                    const int jn = first - lane;
-                    const bool valid = jn >= 0;
-                    unsigned long long w = 0;
-                    while (true) {
-                        if (valid) w = ld_agent(&st[jn]);
-                        const bool ready = !valid || (w >> 62) != 0;
-                        if (__all(ready)) break;
-                        // bounded wait; a failure anywhere (counted in stats) ends all waits at once
-                        if (++spins > a.spin_limit || ((spins & 255u) == 0 && ld_agent32(&a.stats->errors) != 0)) {
-                            failed = true;
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(2);
-                    }
-                    if (failed) break;
-                    const unsigned long long incl = __ballot(valid && (w >> 62) == 2);
-                    const int nearest = incl ? (__ffsll((long long)incl) - 1) : 64;
-                    const bool take = valid && lane <= nearest;
-                    pg += wave_sum(take ? (uint32_t)((w >> 31) & 0x7fffffffu) : 0u);
-                    pe += wave_sum(take ? (uint32_t)(w & 0x7fffffffu) : 0u);
-                    if (incl) break;
-                    first -= 64;
-                }
-                if (failed && lane == 0) atomicAdd(&a.stats->errors, 1u);
-                if (lane == 0) st_agent(&st[chunk], pack_status(2, pg + blk_gt, pe + blk_eq));
-            }
-            if (lane == 0) { sh_prefix[0] = pg; sh_prefix[1] = pe; sh_prefix[2] = failed; }
-        }
-        __syncthreads();
-        if (__builtin_amdgcn_readfirstlane(sh_prefix[2])) break;   // output invalid anyway; lgc_stats reports the error
-        const uint32_t pre_gt = sh_prefix[0], pre_eq = sh_prefix[1];
-
-        if (tid == 0 && chunk == nchunks - 1) {
+        if (tid == 0 && chunk == nchunks - 1) {   // the last chunk of the node sees everything: the selection must add up to k
             const uint32_t te = pre_eq + blk_eq;
             if (pre_gt + blk_gt + (te < quota ? te : quota) != a.k) atomicAdd(&a.stats->errors, 1u);
         }
-        // No thread-dependent `continue` here: a second back-edge taken by only some lanes makes the
-        // compiler re-enter the loop head (barrier) for those lanes alone.
         if ((gtm | eqm) != 0) {
 #pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-            uint32_t cg = pre_gt + off_gt[r] + lane_gt[r];
-            uint32_t ce = pre_eq + off_eq[r] + lane_eq[r];
-            const uint32_t e0 = base + r * kRowElems + tid * 4;
+            for (int r = 0; r < kRows; ++r) {
+                uint32_t cg = pre_gt + off_gt[r] + lane_gt[r];
+                uint32_t ce = pre_eq + off_eq[r] + lane_eq[r];
+                const uint32_t e0 = base + r * kRowElems + tid * 4;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bool fg = (gtm >> (r * 4 + j)) & 1u, fe = (eqm >> (r * 4 + j)) & 1u;
-                if (fg || (fe && ce < quota)) {
-                    const uint32_t o = cg + (ce < quota ? ce : quota);
-                    const uint32_t where = e0 + j;
-                    if (o < a.k) { oidx[o] = where; oval[o] = __uint_as_float(bits[r][j]); }
-                    else atomicAdd(&a.stats->errors, 1u);
-                    v[where] = 0.0f;
-                    if (u) u[where] = 0.0f;
+                for (int j = 0; j < 4; ++j) {
+                    const bool fg = (gtm >> (r * 4 + j)) & 1u, fe = (eqm >> (r * 4 + j)) & 1u;
+                    if (fg || (fe && ce < quota)) {
+                        const uint32_t o = cg + (ce < quota ? ce : quota);
+                        if (o < a.k) { oidx[o] = e0 + j; oval[o] = __uint_as_float(bits[r][j]); }
+                        else atomicAdd(&a.stats->errors, 1u);
+                        v[e0 + j] = 0.0f;
+                        if (u) u[e0 + j] = 0.0f;
+                    }
+                    cg += fg; ce += fe;
                 }
-                cg += fg; ce += fe;
             }
         }
-        }
+        pre_gt += blk_gt; pre_eq += blk_eq;   // block-uniform
     }
 }
 
@@ -1046,9 +1028,17 @@ void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hip
 // wait in the library ends every other wait within a few polls.
 __device__ __forceinline__ bool node_barrier(const SelArgs &a, Ctr *s, uint32_t &epoch) {
     __shared__ uint32_t sh_ok;
-    __threadfence();
+    // Release: every wavefront waits until its own stores and atomics have been acknowledged (a wait, no
+    // cache operation), the block barrier collects them, and ONE thread then issues the device-scope fence
+    // (the write-back of this XCD's L2) before it arrives.  A fence by every thread is the same guarantee at
+    // an L2 write-back request per wavefront: about 20 us per barrier with 256 blocks of 4 wavefronts.
+    // Acquire: none.  Everything that crosses blocks after a barrier (the summed histograms, the blocks'
+    // counts) is read with device-scope atomic loads, which do not go through the non-coherent caches, and
+    // an invalidation of the L2 would only make the next pass over v miss it.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): all of this wavefront's loads, stores and atomics are done
     __syncthreads();
     if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         epoch += gridDim.x;
         atomicAdd(&s->barrier, 1u);
         uint32_t spins = 0, ok = 1;
@@ -1057,7 +1047,6 @@ __device__ __forceinline__ bool node_barrier(const SelArgs &a, Ctr *s, uint32_t 
             if ((spins & 255u) == 0 && ld_agent32(&a.stats->errors) != 0) { ok = 0; break; }
             __builtin_amdgcn_s_sleep(8);
         }
-        __threadfence();
         sh_ok = ok;
     }
     __syncthreads();
@@ -1113,14 +1102,36 @@ __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
     }
     // prefix is now the full key T*; rank the number of ties to take
     if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }
-    emit_chunks<VEC>(a, node, a.n, prefix, rank);
+    // ordered output: block b owns the chunks [b * per, (b + 1) * per) of the node
+    const uint32_t nchunks = (a.n + kChunk - 1) / kChunk, per = (nchunks + gridDim.x - 1) / gridDim.x;
+    const uint32_t c_lo = blockIdx.x * per < nchunks ? blockIdx.x * per : nchunks;
+    const uint32_t c_hi = c_lo + per < nchunks ? c_lo + per : nchunks;
+    count_run<VEC>(a, node, prefix, c_lo, c_hi);
+    if (!node_barrier(a, a.ctr + node, epoch)) return;
+    emit_run<VEC>(a, node, prefix, rank, c_lo, c_hi, nchunks);
 }
 
-// The barriers and the static chunk order need every block of a node to be running at the same
-// time.  The grid is therefore at most one block per compute unit, shared evenly by the nodes:
-// that many blocks are resident whatever the kernel's register use.
-void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st) {
+// The barriers need every block of every node to be running at the same time.  `resident` is how many
+// blocks of this kernel the device holds at once (lgc_create asks the runtime for the kernel's occupancy);
+// they are shared evenly by the nodes.  Several blocks per compute unit matter for the passes over v: with
+// one block of four wavefronts per unit they ran at 1.4 TB/s.
+int exact_blocks_per_cu() {
+    int a = 0, b = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&a, k_exact<true>, kBlock, 0) != hipSuccess) a = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, k_exact<false>, kBlock, 0) != hipSuccess) b = 1;
+    const int m = a < b ? a : b;
+    return m < 1 ? 1 : (m > 4 ? 4 : m);   // four blocks of 256 threads per unit are enough to keep the loads coming
+}
+
+void launch_exact(const SelArgs &a, int batch, bool vec, int cus, int resident, hipStream_t st) {
+    // One block per compute unit (shared by the nodes) up to 64 K elements per block, more blocks beyond
+    // that, as far as the device holds them: every block more makes the four barriers dearer (an L2
+    // write-back per block and barrier), every block less the five passes over v slower.  Measured at
+    // 2^20 .. 2^24 elements per node, 1 and 4 nodes.
     uint32_t per_node = (uint32_t)(cus / batch);
+    const uint32_t by_size = a.n / 65536;
+    if (per_node < by_size) per_node = by_size;
+    if (per_node > (uint32_t)(resident / batch)) per_node = (uint32_t)(resident / batch);
     const uint32_t chunks = (a.n + kChunk - 1) / kChunk;
     if (per_node > chunks) per_node = chunks;
     if (per_node < 1) per_node = 1;
