@@ -1080,9 +1080,19 @@ __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
         };
         if (VEC) {
             const uint32_t n4 = a.n >> 2;
-            for (uint32_t i = gtid; i < n4; i += nthreads) {
-                const f4 vv = ((const f4 *)v)[i];
-                count(key_of(vv.x)); count(key_of(vv.y)); count(key_of(vv.z)); count(key_of(vv.w));
+            for (uint32_t i = gtid; i < n4; i += 4 * nthreads) {   // four 16-byte loads in flight per thread
+                f4 vv[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t ii = i + r * nthreads;   // < 2^29 + 2^20: no wrap
+                    vv[r] = ii < n4 ? ((const f4 *)v)[ii] : (f4){0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (i + r * nthreads < n4) {
+                        count(key_of(vv[r].x)); count(key_of(vv[r].y)); count(key_of(vv[r].z)); count(key_of(vv[r].w));
+                    }
+                }
             }
             for (uint32_t i = (n4 << 2) + gtid; i < a.n; i += nthreads) count(key_of(v[i]));
         } else {
