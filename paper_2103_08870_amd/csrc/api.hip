@@ -242,13 +242,12 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
         launch_output_from_candidates(a, batch, expected_candidates((double)n, (double)k) <= 131072.0, st);
         a.force = 0;
     } else {
-        launch_clear(a.next_state, a.next_words, st);
         if (fused) {
             profile_begin(ctx, st);
             launch_accumulate(g, u, v, (uint32_t)n, batch, stride, m, vec, st);
             profile_end(ctx, st);
         }
-        a.force = 1;
+        a.force = 1;   // the exact kernel then also clears the next call's state set
     }
     // exact path: runs when forced, otherwise only for nodes the fast path handed back
     // forced: all the blocks the device holds; as the fast path's fall-back, which nearly always has nothing

@@ -18,7 +18,7 @@ constexpr int kWaves = kBlock / 64;
 constexpr uint32_t kSample = 65536;             // sampled keys per node
 constexpr uint32_t kSampleGroups = kSample / 4; // sampled in groups of 4 neighbours
 constexpr int kSampleBins = 2048;               // first level: key >> 20
-constexpr uint32_t kMinFastN = 1u << 17;        // below this the exact path is used directly
+constexpr uint32_t kMinFastN = 1u << 18;        // below this the exact path is used directly (and is as fast)
 
 // ---- histogram of the candidates above the estimate -------------------------
 constexpr int kFineBins = 4096;

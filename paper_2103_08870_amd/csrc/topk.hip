@@ -1067,6 +1067,10 @@ __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
     const float *v = a.v + (size_t)node * a.stride;
     const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock;
     uint32_t epoch = 0, prefix = 0, rank = a.k;
+    if (a.force) {   // no sampling kernel ran in this call: the next call's state set is cleared here
+        const uint32_t all = gridDim.y * nthreads;
+        for (uint32_t i = blockIdx.y * nthreads + gtid; i < a.next_words; i += all) a.next_state[i] = 0;
+    }
 
     for (int pass = 0; pass < 3; ++pass) {
         const int nb = pass == 0 ? kRadixBins : 1024;

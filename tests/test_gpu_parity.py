@@ -129,8 +129,8 @@ def test_topk_special_values(B, oracle):
 
 
 # the last two cases have long candidate lists (second-level histogram by many blocks, look-back output)
-# the first three are just above the smallest vector that takes the fast path (2^17 elements)
-@pytest.mark.parametrize("n,k", [(1 << 17, 131), (150_001, 150), (600_001, 6000),
+# the first three are just above the smallest vector that takes the fast path (2^18 elements)
+@pytest.mark.parametrize("n,k", [(1 << 18, 262), (300_001, 300), (600_001, 6000),
                                  (1 << 20, 1024), (1_300_007, 1300), (3_000_001, 300), (2_000_000, 60_000),
                                  (3_000_000, 150_000), (5_000_001, 400_000)])
 def test_topk_fast_path_and_forced_exact(B, oracle, n, k):
