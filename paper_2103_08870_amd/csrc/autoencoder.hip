@@ -213,7 +213,9 @@ __global__ __launch_bounds__(256) void k_decoder2(const float *__restrict__ z, f
     const bool h0 = s0 < l1, h1 = s0 + 1 < l1, h2 = s0 + 2 < l1;
     const float bias = b4[0];
     float y0 = bias, y1 = bias, y2 = bias, y3 = bias;
-#pragma unroll
+    // two hidden channels per round: unrolled over all of them, the weights (wave-uniform, in scalar
+    // registers) do not fit and spill into vector lanes, several reads of a lane for every multiply-add
+#pragma unroll 2
     for (int c = 0; c < CH; ++c) {
         // hidden position 2r (even): tap 1 from z[r]; 2r+1 (odd): tap 0 from z[r+1], tap 2 from z[r];
         // 2r+2 (even): tap 1 from z[r+1].  Taps that do not reach a position add nothing.
