@@ -295,7 +295,7 @@ constexpr int kHeadNarrow = 8;
 constexpr int kHeadWide = 64;     // most channels out of the stride-2 head layer (= c_in of the deep layer)
 constexpr int kHeadPos = kTPosTile / 2 + 1;   // 65 positions of h1 per tile
 
-template <bool TAIL, bool HEAD>
+template <bool TAIL, int HC1>   // HC1: 0 = no head, else the channels between the two head layers (hd.c1)
 __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__ in, float *__restrict__ out,
                                                        const float *__restrict__ wt, const float *__restrict__ bias,
                                                        int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
@@ -303,6 +303,7 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
                                                        const float *__restrict__ tail_b, int tail_act, ConvtHead hd) {
     __shared__ float xs[kCiChunk * kTRowPad + 1];
     __shared__ float ws[3 * kCiChunk * 32];
+    constexpr bool HEAD = HC1 > 0;
     __shared__ float hz[HEAD ? kHeadNarrow * (kHeadPos + 2) : 1];        // z[c][m0/2 - 1 .. m0/2 + 65]
     __shared__ float h1[HEAD ? kHeadNarrow * kHeadPos : 1];              // h1[c][m0/2 .. m0/2 + 64]
     __shared__ float hw1[HEAD ? kHeadNarrow * kHeadNarrow * 3 + kHeadNarrow : 1];
@@ -355,11 +356,15 @@ __global__ __launch_bounds__(256) void k_convt3s2_mfma(const float *__restrict__
                 const bool slot = e < kCiChunk * (kTPosTile + 1);
                 const int c = c0 + (slot ? e / (kTPosTile + 1) : 0), r = e % (kTPosTile + 1), j = r >> 1;
                 float a = hw2[kHeadNarrow * kHeadWide * 3 + c];
-                for (int c1 = 0; c1 < hd.c1; ++c1) {
+                const bool odd = r & 1;   // no branch: both forms are evaluated and one is kept
+#pragma unroll
+                for (int c1 = 0; c1 < HC1; ++c1) {
                     const float *w = hw2 + (c1 * c_in + c) * 3;
                     const float *h = h1 + c1 * kHeadPos + j;
-                    if (r & 1) { a = fmaf(w[0], h[r < kTPosTile ? 1 : 0], a); a = fmaf(w[2], h[0], a); }
-                    else a = fmaf(w[1], h[0], a);
+                    const float h0 = h[0], hn = h[odd ? 1 : 0];
+                    const float even_a = fmaf(w[1], h0, a);
+                    const float odd_a = fmaf(w[2], h0, fmaf(w[0], hn, a));
+                    a = odd ? odd_a : even_a;
                 }
                 x = leaky_m(a, slope);
             } else {
@@ -472,10 +477,10 @@ bool launch_convt3s2_mfma(const float *in, float *out, const LayerDev &l, uint32
     const uint32_t m_count = (l_out + 1) / 2;
     dim3 grid((m_count + kTPosTile - 1) / kTPosTile, l.c_out / 32, batch);
     if (tail)
-        hipLaunchKernelGGL((k_convt3s2_mfma<true, false>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
+        hipLaunchKernelGGL((k_convt3s2_mfma<true, 0>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
                            l_out, (int)act, slope, tail->w, tail->b, (int)tail_act, ConvtHead{});
     else
-        hipLaunchKernelGGL((k_convt3s2_mfma<false, false>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
+        hipLaunchKernelGGL((k_convt3s2_mfma<false, 0>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
                            l_out, (int)act, slope, nullptr, nullptr, 0, ConvtHead{});
     return true;
 }
@@ -490,15 +495,19 @@ bool launch_convt3s2_mfma_head(const float *z, float *out, const LayerDev &h1, c
     if (!l.wt || l.ksize != 3 || l.stride != 2 || l.c_in % kCiChunk != 0 || l.c_out % 32 != 0) return false;
     if ((uint64_t)l_in * kCiChunk >= (1ull << 32) || (uint64_t)l.c_in * 3 * l.c_out >= (1ull << 32)) return false;
     if (!(h1.ksize == 3 && h1.stride == 1 && h2.ksize == 3 && h2.stride == 2 && h1.c_out == h2.c_in && h2.c_out == l.c_in &&
-          h1.c_in <= kHeadNarrow && h1.c_out <= kHeadNarrow && l.c_in <= kHeadWide))
+          h1.c_in <= kHeadNarrow && (h1.c_out == 4 || h1.c_out == 8) && l.c_in <= kHeadWide))
         return false;
     if (!(l_in == 2 * l_z || l_in + 1 == 2 * l_z)) return false;
     if (l_out == 0) return true;
     const uint32_t m_count = (l_out + 1) / 2;
     dim3 grid((m_count + kTPosTile - 1) / kTPosTile, l.c_out / 32, batch);
     const ConvtHead hd{h1.w, h1.b, h2.w, h2.b, h1.c_in, h1.c_out, l_z};
-    hipLaunchKernelGGL((k_convt3s2_mfma<false, true>), grid, dim3(256), 0, st, z, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
-                       (int)act, slope, nullptr, nullptr, 0, hd);
+    if (h1.c_out == 4)
+        hipLaunchKernelGGL((k_convt3s2_mfma<false, 4>), grid, dim3(256), 0, st, z, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                           (int)act, slope, nullptr, nullptr, 0, hd);
+    else
+        hipLaunchKernelGGL((k_convt3s2_mfma<false, 8>), grid, dim3(256), 0, st, z, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
+                           (int)act, slope, nullptr, nullptr, 0, hd);
     return true;
 }
 
