@@ -270,6 +270,56 @@ def case_innovation(B, O, rng, desc):
         assert bits(out[b], O.innovation(vals[b], off, ks)), b
     seg.close(); ctx.close()
 
+def case_reuse(B, O, rng, desc):
+    """One context, many calls of different n, k, batch, path and entry point."""
+    max_n = int(rng.choice([300_000, 1_200_000, 3_000_000])); max_k = max_n // int(rng.choice([3, 10, 100])); max_b = int(rng.integers(1, 5))
+    calls = int(rng.integers(4, 12))
+    desc.append(f"reuse max_n={max_n} max_k={max_k} max_b={max_b} calls={calls}")
+    ctx = B.Context(max_n, max_k, max_b)
+    for c in range(calls):
+        n = int(rng.integers(1, max_n + 1)) if rng.random() < 0.7 else max_n
+        k = min(n, max_k, rand_k(rng, n)); batch = int(rng.integers(1, max_b + 1)); kind = int(rng.integers(0, 6))
+        mode = int(rng.integers(0, 4)); force = int(rng.random() < 0.25)
+        desc.append(f"  call {c}: n={n} k={k} batch={batch} kind={kind} mode={mode} force={force}")
+        B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, force)
+        u = values(rng, (batch, n), 1); v = values(rng, (batch, n), kind); g = values(rng, (batch, n), 1)
+        du, dv, dg = (torch.from_numpy(a.copy()).cuda() for a in (u, v, g))
+        if mode == 3:   # per-layer plan over the same vector
+            n_seg = int(rng.integers(1, min(100, n) + 1))
+            cuts = np.sort(rng.choice(np.arange(1, n), size=n_seg - 1, replace=False)) if n_seg > 1 else np.array([], np.int64)
+            off = [0] + [int(x) for x in cuts] + [n]
+            ks = [min(off[i + 1] - off[i], max(1, int((k / n) * (off[i + 1] - off[i])))) for i in range(n_seg)]
+            while sum(ks) > max_k:
+                ks[int(np.argmax(ks))] //= 2
+            total = sum(ks)
+            seg = B.Segments(off, ks)
+            ovals = torch.full((batch, total), 7.0, device="cuda"); oidx = torch.full((batch, total), -1, device="cuda", dtype=torch.int32)
+            B.lgc_accumulate_topk_segmented(ctx, seg, dg, du, dv, 0.9, ovals, oidx)
+            seg.close()
+        else:
+            ovals = torch.full((batch, k), 7.0, device="cuda"); oidx = torch.full((batch, k), -1, device="cuda", dtype=torch.int32)
+            if mode == 0:
+                B.lgc_accumulate_topk(ctx, dg, du, dv, 0.9, k, ovals, oidx)
+            elif mode == 1:
+                B.lgc_topk(ctx, dv, du, k, ovals, oidx)
+            else:
+                B.lgc_accumulate(ctx, dg, du, dv, 0.9)
+                B.lgc_topk(ctx, dv, None, k, ovals, oidx)
+        assert B.lgc_stats(ctx)[2] == 0
+        for b in range(batch):
+            ub, vb = u[b].copy(), v[b].copy()
+            if mode != 1:
+                O.accumulate(g[b].copy(), ub, vb, 0.9)
+            if mode == 3:
+                vals, idx = O.topk_segmented(vb, ub, off, ks)
+            else:
+                vals, idx = O.topk(vb, ub if mode != 2 else None, k)
+            u[b], v[b] = ub, vb
+            assert (oidx[b].cpu().numpy().astype(np.uint32) == idx).all(), ("idx", c, b)
+            assert bits(ovals[b], vals), ("vals", c, b)
+        assert bits(dv, v) and bits(du, u), ("uv", c)
+    ctx.close()
+
 
 def run_cases(B, oracle, fn, family, block, count):
     for i in range(count):
@@ -309,3 +359,8 @@ def test_random_gather_and_average(B, oracle, block):
 @pytest.mark.parametrize("block", range(2))
 def test_random_innovation(B, oracle, block):
     run_cases(B, oracle, case_innovation, 5, block, 20)
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_calls_on_one_context(B, oracle, block):
+    run_cases(B, oracle, case_reuse, 6, block, 6)
