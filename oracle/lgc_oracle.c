@@ -32,8 +32,8 @@ static uint32_t mag_key(float x) { return f32_bits(x) & 0x7FFFFFFFu; }
  * Local accumulation with momentum correction.
  *
  * Alg. 1 / Alg. 2, first line of the layer loop: the fresh gradient is added
- * to the carried residual, g_l = grad + g_acc.  Sec. V-A (last paragraph) says
- * the unsent part is accumulated "with a momentum correction similar to DGC"
+ * to the carried residual, g_l = grad + g_acc.  Sec. V-A (last paragraph) has
+ * the unsent part accumulated with a momentum correction in the manner of DGC
  * and gives no formula; the reading taken is DGC's published rule
  *     u <- m*u + g        (momentum buffer)
  *     v <- v + u          (accumulated gradient, the paper's g_acc / g_l)
