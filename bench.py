@@ -37,9 +37,11 @@ def parse():
                    help="do not run the stand-alone program that measures plain streaming kernels (use under a profiler)")
     p.add_argument("--ratio-index", type=int, default=-1, help="which of the workload's ratios")
     p.add_argument("--grad-sets", type=int, default=0, help="distinct gradient sets kept in HBM (0 = workload's)")
-    p.add_argument("--pattern", choices=["ps", "rar"], default="ps",
+    p.add_argument("--pattern", choices=["ps", "rar", "ps-innovation"], default="ps",
                    help="ps: every node selects (default, the headline); rar: ring-allreduce pattern, one "
-                        "rotating node selects and the others take the values at its positions (Alg. 2)")
+                        "rotating node selects and the others take the values at its positions (Alg. 2); "
+                        "ps-innovation: Alg. 1 in full, every node also forms its innovation component (top 10 %% "
+                        "of each layer's selected values) and the decoder takes it as one more channel")
     p.add_argument("--selection", choices=["flat", "layers"], default="flat",
                    help="flat: one top-k over the whole vector (default, the headline); layers: per-layer "
                         "top-k over the workload's layers, mu_l = max(1, floor(ratio n_l)) (Sec. V-A)")
@@ -54,7 +56,7 @@ def parse():
     return p.parse_args()
 
 
-def cpu_baseline(w, k, enc, dec, host_w, g_host, momentum, plan=None):
+def cpu_baseline(w, k, enc, dec, host_w, g_host, momentum, plan=None, inv_plan=None):
     """The oracle, as it stands, on one iteration of the same workload: accumulate + top-k +
     encode + decode + scatter for every node, nodes on separate threads (the only parallelism
     that cannot change its results)."""
@@ -70,7 +72,10 @@ def cpu_baseline(w, k, enc, dec, host_w, g_host, momentum, plan=None):
         oracle.accumulate(g_host[b], u, v, momentum)
         vals, idx = oracle.topk(v, u, k) if plan is None else oracle.topk_segmented(v, u, plan[0], plan[1])
         lat = oracle.encode(vals, enc, ew, eb)
-        rec = oracle.decode(lat, k, enc, dec, dw, db)
+        if inv_plan is None:
+            rec = oracle.decode(lat, k, enc, dec, dw, db)
+        else:
+            rec = oracle.decode_with_innovation(lat, oracle.innovation(vals, inv_plan[0], inv_plan[1]), k, enc, dec, dw, db)
         return rec, idx
 
     t0 = time.perf_counter()
@@ -156,12 +161,26 @@ def main():
     k = w.ks[args.ratio_index]
     seg = None
     if args.selection == "layers":
-        assert w.kind == "laplace_segments" and args.pattern == "ps", "--selection layers: workloads 2-4, pattern ps"
+        assert w.kind == "laplace_segments" and args.pattern != "rar", "--selection layers: workloads 2-4, not with rar"
         seg_off, seg_ks = synth.layer_plan(w, w.ratios[args.ratio_index])
         seg = B.Segments(seg_off, seg_ks)
         k = seg.total_k
     sets = args.grad_sets or w.iters
-    enc, dec = synth.mirrored_ae(w.ae_channels) if args.ae == "config" else synth.paper_ae()
+    inv_seg = inv_plan = None
+    if args.pattern == "ps-innovation":
+        # Alg. 1: per layer of the selected values (one layer when the selection is flat) the top 10 % are
+        # the innovation component
+        assert args.ae == "config", "ps-innovation: the workload's autoencoder with the innovation channel"
+        ks_out = seg_ks if seg is not None else [k]
+        out_off = [0]
+        for k_l in ks_out:
+            out_off.append(out_off[-1] + k_l)
+        inv_plan = (out_off, [max(1, k_l // 10) for k_l in ks_out])
+        inv_seg = B.Segments(*inv_plan)
+    if args.pattern == "ps-innovation":
+        enc, dec = synth.innovation_ae(w.ae_channels)
+    else:
+        enc, dec = synth.mirrored_ae(w.ae_channels) if args.ae == "config" else synth.paper_ae()
     slope = 0.0 if args.ae == "config" else 0.01
     ew, eb, dw, db = synth.ae_weights(enc, dec, device="cuda")
     ae = B.Autoencoder(enc, dec, ew, eb, dw, db, slope=slope)
@@ -188,6 +207,15 @@ def main():
         B.lgc_decode(ctx, ae, lat, rec)
         B.lgc_scatter(ctx, rec, idx, 1.0 / K, dense)
 
+    innov = torch.zeros((K, k), device="cuda") if inv_seg is not None else None
+
+    def step_ps_innovation(t):
+        select(t)
+        B.lgc_innovation(ctx, inv_seg, vals, innov)
+        B.lgc_encode(ctx, ae, vals, lat)
+        B.lgc_decode_innovation(ctx, ae, lat, innov, rec)
+        B.lgc_scatter(ctx, rec, idx, 1.0 / K, dense)
+
     lat_avg = torch.zeros((1, lat.shape[1]), device="cuda")
 
     def step_rar(t):
@@ -201,7 +229,7 @@ def main():
         B.lgc_decode(ctx, ae, lat_avg, rec[:1])
         B.lgc_scatter(ctx, rec[:1], idx[:1], 1.0, dense)
 
-    step = step_ps if args.pattern == "ps" else step_rar
+    step = {"ps": step_ps, "rar": step_rar, "ps-innovation": step_ps_innovation}[args.pattern]
 
     for t in range(args.warmup):
         step(t)
@@ -260,9 +288,12 @@ def main():
                          (lambda t: B.lgc_topk_segmented(ctx, seg, v, u, vals, idx))),
         "a1a2_fused": fused_ms,
         "a3_encode": timed(lambda t: B.lgc_encode(ctx, ae, vals, lat)),
-        "a4_decode": timed(lambda t: B.lgc_decode(ctx, ae, lat, rec)),
+        "a4_decode": timed((lambda t: B.lgc_decode(ctx, ae, lat, rec)) if inv_seg is None else
+                           (lambda t: B.lgc_decode_innovation(ctx, ae, lat, innov, rec))),
         "a5_scatter": timed(lambda t: B.lgc_scatter(ctx, rec, idx, 1.0 / K, dense)),
     }
+    if inv_seg is not None:
+        stages["innovation"] = timed(lambda t: B.lgc_innovation(ctx, inv_seg, vals, innov))
     B.lgc_stats(ctx)
     torch.cuda.synchronize()
     roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
@@ -296,6 +327,10 @@ def main():
                             f"accumulate + per-layer top-k over {len(seg_ks)} layers (fused, all nodes in one call) "
                             "+ encode + decode + scatter")
                            if args.pattern == "ps" else
+                           (f"Alg. 1 in full: accumulate + {'per-layer ' if seg is not None else ''}top-k (fused, all nodes "
+                            f"in one call) + innovation component ({sum(inv_plan[1])} of {k} values per node, top 10 % per "
+                            "layer) + encode + decode with the innovation channel + scatter")
+                           if args.pattern == "ps-innovation" else
                            "ring-allreduce pattern: accumulate+top-k on the selecting node, accumulate+gather at "
                            "its positions on the others, encode (all), average, decode (once), scatter (once)"},
         "whole_step_hbm_frac": ALGO_BYTES_PER_ELEM * value / (HBM_PEAK_GBS * 1e9),
@@ -307,14 +342,14 @@ def main():
                                  "ms_median_of_5": reps[2], "ms_min_of_5": reps[0],
                                  "note": "same buffers, measured after the timed region"},
         "stages_ms": {name: round(ms, 5) for name, ms in stages.items()},
-        "autoencoder": ae_report(enc, dec, k, K if args.pattern == "ps" else 1, K, stages, args.ae),
+        "autoencoder": ae_report(enc, dec, k, 1 if args.pattern == "rar" else K, K, stages, args.ae),
         "roofline": roofline,
     }
 
     if not args.no_cpu_baseline:
         host_w = [[t.cpu().numpy() for t in xs] for xs in (ew, eb, dw, db)]
         out["cpu_baseline"] = cpu_baseline(w, k, enc, dec, host_w, grads[0].cpu().numpy(), w.momentum,
-                                           None if seg is None else (seg_off, seg_ks))
+                                           None if seg is None else (seg_off, seg_ks), inv_plan)
     print(json.dumps(out))
 
 

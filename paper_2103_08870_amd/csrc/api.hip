@@ -660,6 +660,13 @@ static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent
         if (e2 != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e2));
         return LGC_OK;
     }
+    if (innov && nl == 3 &&
+        launch_decoder3i(latent, innov, rec, ae->dec_dev[0], ae->dec_dev[1], ae->dec_dev[2], (uint32_t)in_len,
+                         (uint32_t)out_len[0], (uint32_t)out_len[1], batch, ae->slope, st)) {
+        hipError_t e3 = hipGetLastError();
+        if (e3 != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e3));
+        return LGC_OK;
+    }
     size_t need = 0;
     for (size_t l = 0; l + 1 < nl; ++l) {
         size_t f = (size_t)batch * ae->dec[l].c_out * out_len[l];

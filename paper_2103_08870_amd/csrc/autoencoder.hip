@@ -246,6 +246,80 @@ __global__ __launch_bounds__(256) void k_decoder2(const float *__restrict__ z, f
     if (q + 3 < l0) y[q + 3] = y3;
 }
 
+// The parameter-server decoder at the benchmark's shape in one launch (Sec. IV-C, Sec. V-B): two kernel-3 /
+// stride-2 transposed layers CZ -> CH -> CM channels as in k_decoder2, then the kernel-1 layer that takes the CM
+// channels and the innovation component as one more channel:
+//   y[b][q] = b5 + sum_cm w5[cm] * act(m[cm][q]) + w5[CM] * innov[b][q],
+//   m[cm][q] = b4[cm] + sum_c sum_{(s,t): 2s-1+t = q} w4[c][cm][t] * h[c][s],   h as in k_decoder2.
+// Thread r4 writes y[4 r4 .. 4 r4 + 3].
+template <int CZ, int CH, int CM>
+__global__ __launch_bounds__(256) void k_decoder3i(const float *__restrict__ z, const float *__restrict__ innov,
+                                                   float *__restrict__ y, const float *__restrict__ w3,
+                                                   const float *__restrict__ b3, const float *__restrict__ w4,
+                                                   const float *__restrict__ b4, const float *__restrict__ w5,
+                                                   const float *__restrict__ b5, uint32_t l2, uint32_t l1, uint32_t l0,
+                                                   float slope) {
+    const uint32_t r = blockIdx.x * 256 + threadIdx.x;
+    if (4ull * r >= l0) return;
+    z += (size_t)blockIdx.y * CZ * l2;
+    y += (size_t)blockIdx.y * l0;
+    innov += (size_t)blockIdx.y * l0;
+    const uint64_t q = 4ull * r;
+    float in[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) in[j] = q + j < l0 ? innov[q + j] : 0.f;
+    const bool z0 = r < l2, z1 = r + 1 < l2;
+    float za[CZ], zb[CZ];
+#pragma unroll
+    for (int cz = 0; cz < CZ; ++cz) {
+        za[cz] = z0 ? z[(size_t)cz * l2 + r] : 0.f;
+        zb[cz] = z1 ? z[(size_t)cz * l2 + r + 1] : 0.f;
+    }
+    const uint32_t s0 = 2 * r;
+    const bool h0 = s0 < l1, h1 = s0 + 1 < l1, h2 = s0 + 2 < l1;
+    float m[CM][4];
+#pragma unroll
+    for (int cm = 0; cm < CM; ++cm) m[cm][0] = m[cm][1] = m[cm][2] = m[cm][3] = b4[cm];
+    // one hidden channel per round: the round's 3 CZ + 3 CM wave-uniform weights fit the scalar registers
+#pragma unroll 1
+    for (int c = 0; c < CH; ++c) {
+        float a0 = b3[c], a1 = b3[c], a2 = b3[c];
+#pragma unroll
+        for (int cz = 0; cz < CZ; ++cz) {
+            const float t0 = w3[(cz * CH + c) * 3 + 0], t1 = w3[(cz * CH + c) * 3 + 1], t2 = w3[(cz * CH + c) * 3 + 2];
+            a0 = fmaf(t1, za[cz], a0);
+            a1 = fmaf(t0, zb[cz], a1);
+            a1 = fmaf(t2, za[cz], a1);
+            a2 = fmaf(t1, zb[cz], a2);
+        }
+        const float g0 = h0 ? leaky(a0, slope) : 0.f;
+        const float g1 = h1 ? leaky(a1, slope) : 0.f;
+        const float g2 = h2 ? leaky(a2, slope) : 0.f;
+#pragma unroll
+        for (int cm = 0; cm < CM; ++cm) {
+            const float u0 = w4[(c * CM + cm) * 3 + 0], u1 = w4[(c * CM + cm) * 3 + 1], u2 = w4[(c * CM + cm) * 3 + 2];
+            m[cm][0] = fmaf(u1, g0, m[cm][0]);
+            m[cm][1] = fmaf(u0, g1, m[cm][1]);
+            m[cm][1] = fmaf(u2, g0, m[cm][1]);
+            m[cm][2] = fmaf(u1, g1, m[cm][2]);
+            m[cm][3] = fmaf(u0, g2, m[cm][3]);
+            m[cm][3] = fmaf(u2, g1, m[cm][3]);
+        }
+    }
+    float out[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float a = b5[0];
+#pragma unroll
+        for (int cm = 0; cm < CM; ++cm) a = fmaf(w5[cm], leaky(m[cm][j], slope), a);
+        out[j] = fmaf(w5[CM], in[j], a);
+    }
+    y[q] = out[0];
+    if (q + 1 < l0) y[q + 1] = out[1];
+    if (q + 2 < l0) y[q + 2] = out[2];
+    if (q + 3 < l0) y[q + 3] = out[3];
+}
+
 static bool two_layer_shape(const LayerDev &a, const LayerDev &b) {
     return a.ksize == 3 && a.stride == 2 && b.ksize == 3 && b.stride == 2;
 }
@@ -273,6 +347,25 @@ bool launch_decoder2(const float *z, float *y, const LayerDev &a, const LayerDev
         hipLaunchKernelGGL((k_decoder2<4, 8>), grid, dim3(256), 0, st, z, y, a.w, a.b, b.w, b.b, l2, l1, l0, slope);
     else if (a.c_in == 8 && a.c_out == 16)
         hipLaunchKernelGGL((k_decoder2<8, 16>), grid, dim3(256), 0, st, z, y, a.w, a.b, b.w, b.b, l2, l1, l0, slope);
+    else
+        return false;
+    return true;
+}
+
+// a, b: the two transposed layers; c: the kernel-1 layer over b's channels and the innovation component
+bool launch_decoder3i(const float *z, const float *innov, float *y, const LayerDev &a, const LayerDev &b,
+                      const LayerDev &c, uint32_t l2, uint32_t l1, uint32_t l0, int batch, float slope, hipStream_t st) {
+    if (!two_layer_shape(a, b) || a.c_out != b.c_in || c.ksize != 1 || c.stride != 1 || c.c_out != 1 ||
+        c.c_in != b.c_out + 1)
+        return false;
+    if (l0 == 0) return true;
+    dim3 grid(((l0 + 3) / 4 + 255) / 256, batch);
+    if (a.c_in == 4 && a.c_out == 8 && b.c_out == 4)
+        hipLaunchKernelGGL((k_decoder3i<4, 8, 4>), grid, dim3(256), 0, st, z, innov, y, a.w, a.b, b.w, b.b, c.w, c.b, l2, l1,
+                           l0, slope);
+    else if (a.c_in == 8 && a.c_out == 16 && b.c_out == 8)
+        hipLaunchKernelGGL((k_decoder3i<8, 16, 8>), grid, dim3(256), 0, st, z, innov, y, a.w, a.b, b.w, b.b, c.w, c.b, l2,
+                           l1, l0, slope);
     else
         return false;
     return true;

@@ -150,6 +150,8 @@ bool launch_encoder2(const float *x, float *z, const LayerDev &a, const LayerDev
                      uint32_t l2, int batch, float slope, hipStream_t st);
 bool launch_decoder2(const float *z, float *y, const LayerDev &a, const LayerDev &b, uint32_t l2, uint32_t l1,
                      uint32_t l0, int batch, float slope, hipStream_t st);
+bool launch_decoder3i(const float *z, const float *innov, float *y, const LayerDev &a, const LayerDev &b,
+                      const LayerDev &c, uint32_t l2, uint32_t l1, uint32_t l0, int batch, float slope, hipStream_t st);
 void launch_scatter(const float *vals, const uint32_t *idx, uint32_t k, float scale, float *dense,
                     uint32_t n, Stats *stats, hipStream_t st);
 

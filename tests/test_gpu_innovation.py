@@ -51,7 +51,9 @@ def make_innovation_ae(B, channels, slope=0.0):
 
 
 @pytest.mark.parametrize("channels,k,batch,slope", [((1, 8, 4), 1024, 1, 0.0), ((1, 8, 4), 25_532, 4, 0.0),
-                                                    ((1, 16, 8), 44_501, 2, 0.01), ((1, 16, 8), 5, 2, 0.0)])
+                                                    ((1, 16, 8), 44_501, 2, 0.01), ((1, 16, 8), 5, 2, 0.0),
+                                                    # not one of the shapes with a kernel of their own: layer by layer
+                                                    ((1, 6, 3), 777, 2, 0.01), ((1, 16, 8), 4099, 3, 0.2)])
 def test_decode_with_innovation(B, oracle, channels, k, batch, slope):
     ae, enc, dec, (ew, eb, dw, db) = make_innovation_ae(B, channels, slope)
     ctx = B.Context(1 << 20, 1 << 20, 4)
