@@ -16,6 +16,9 @@
  *  - Every data pointer is a DEVICE pointer owned by the caller, fp32 or uint32,
  *    contiguous.  The library keeps no pointer after a call returns (the
  *    autoencoder handle copies its weights when it is created).
+ *    The arrays of one call must not overlap each other (nor the nodes' rows
+ *    of one array: stride >= n); what an entry point reads and what it
+ *    writes is stated with it.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work: they never synchronise the stream and never read
  *    results back to the host.  Outputs are valid once the stream has drained.
