@@ -27,19 +27,13 @@
  *    stride >= n).  batch = 1 is the single-node form.
  *  - A context owns only scratch memory.  One context serves one stream at a
  *    time and is not thread-safe; calls on one context that overlap race.
- *    Different contexts may work on different streams at the same time, with
- *    one limit.  The exact selection path (taken for vectors below 2^18
- *    elements, for k above about a quarter of n, with LGC_OPT_SELECT_PATH = 1,
- *    and as the fall-back of a node whose sampled threshold failed) is one
- *    kernel whose blocks wait for each other, so all of them must be on the
- *    device together.  As a fall-back it has one block per compute unit and
- *    several such kernels fit side by side.  Taken outright for more than about
- *    25 M elements per call (all nodes together) it fills more than half of
- *    the device, and two such calls started at the same moment on two streams
- *    could each hold places the other's blocks wait for.  The waits are
- *    bounded: such a call ends with invalid outputs, a non-zero error count in
- *    lgc_stats and LGC_EDEVICE, never in a hang.  Keep at most one call of that
- *    kind in flight per device.
+ *    Different contexts may work on different streams at the same time.  The
+ *    one kernel of the library whose blocks wait for each other (the exact
+ *    selection of short inputs, and the fall-back of a node whose sampled
+ *    threshold failed) never has more than one block per compute unit, a third
+ *    of what the device holds, so several of them fit side by side; its waits
+ *    are bounded all the same (an expired wait gives invalid outputs, a
+ *    non-zero error count in lgc_stats and LGC_EDEVICE, never a hang).
  *  - The calls can be recorded into a HIP graph (stream capture) once the
  *    context's scratch has grown to its size (one warm-up call of each kind):
  *    they allocate nothing then, never synchronise and use no memset.  The

@@ -1057,6 +1057,74 @@ __device__ __forceinline__ bool node_barrier(const SelArgs &a, Ctr *s, uint32_t 
 // pass histograms one digit of the keys that match the digits fixed so far, all blocks then
 // fix the next digit from the summed histogram), followed by the ordered output compaction
 // of v with that key.  Runs for the nodes the fast path handed back, or for all when forced.
+
+// One pass over v of this block's share: the histogram of digit `pass` among the keys whose higher digits
+// equal `prefix`, counted in LDS and added to the node's histogram of that pass.
+template <bool VEC>
+__device__ __forceinline__ void radix_count(const SelArgs &a, const int node, const int pass, const uint32_t prefix,
+                                            uint32_t *hist /*[kRadixBins]*/) {
+    const int tid = threadIdx.x;
+    const float *v = a.v + (size_t)node * a.stride;
+    const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock;
+    const int nb = pass == 0 ? kRadixBins : 1024;
+    uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
+    for (int i = tid; i < nb; i += kBlock) hist[i] = 0;
+    __syncthreads();
+    auto count = [&](uint32_t key) {
+        if (pass == 0) atomicAdd(&hist[key >> 20], 1u);
+        else if (pass == 1) { if ((key >> 20) == prefix) atomicAdd(&hist[(key >> 10) & 1023u], 1u); }
+        else { if ((key >> 10) == prefix) atomicAdd(&hist[key & 1023u], 1u); }
+    };
+    if (VEC) {
+        const uint32_t n4 = a.n >> 2;
+        for (uint32_t i = gtid; i < n4; i += 4 * nthreads) {   // four 16-byte loads in flight per thread
+            f4 vv[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t ii = i + r * nthreads;   // < 2^29 + 2^22: no wrap
+                vv[r] = ii < n4 ? ((const f4 *)v)[ii] : (f4){0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (i + r * nthreads < n4) {
+                    count(key_of(vv[r].x)); count(key_of(vv[r].y)); count(key_of(vv[r].z)); count(key_of(vv[r].w));
+                }
+            }
+        }
+        for (uint32_t i = (n4 << 2) + gtid; i < a.n; i += nthreads) count(key_of(v[i]));
+    } else {
+        for (uint32_t i = gtid; i < a.n; i += nthreads) count(key_of(v[i]));
+    }
+    __syncthreads();
+    for (int i = tid; i < nb; i += kBlock) { const uint32_t h = hist[i]; if (h) atomicAdd(&gh[i], h); }
+}
+
+// Once every block's counts of `pass` are in the node's histogram: the digit that holds the rank-th largest
+// key, appended to prefix; rank becomes the rank inside that digit's keys.  Block-wide, the same in all blocks.
+__device__ __forceinline__ void radix_fix(const SelArgs &a, const int node, const int pass, uint32_t *hist,
+                                          uint32_t *wave_tmp, uint32_t *res, uint32_t &prefix, uint32_t &rank) {
+    const int tid = threadIdx.x;
+    const int nb = pass == 0 ? kRadixBins : 1024;
+    const uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
+    for (int i = tid; i < kRadixBins; i += kBlock) hist[i] = i < nb ? ld_agent32(&gh[i]) : 0u;
+    __syncthreads();
+    if (pass == 0) find_rank_bin<kRadixBins>(hist, rank, wave_tmp, res);
+    else find_rank_bin<1024>(hist, rank, wave_tmp, res);
+    const uint32_t digit = res[0] == 0xffffffffu ? 0u : res[0];
+    rank -= res[1];
+    prefix = pass == 0 ? digit : ((prefix << 10) | digit);
+    __syncthreads();
+}
+
+// this block's run of chunks in the ordered output: block b owns the chunks [b * per, (b + 1) * per) of the node
+__device__ __forceinline__ void block_run(const SelArgs &a, uint32_t &c_lo, uint32_t &c_hi, uint32_t &nchunks) {
+    nchunks = (a.n + kChunk - 1) / kChunk;
+    const uint32_t per = (nchunks + gridDim.x - 1) / gridDim.x;
+    c_lo = blockIdx.x * per < nchunks ? blockIdx.x * per : nchunks;
+    c_hi = c_lo + per < nchunks ? c_lo + per : nchunks;
+}
+
+// The whole path in one kernel whose blocks meet at node-wide barriers: all of them must be resident.
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
     __shared__ uint32_t hist[kRadixBins];
@@ -1064,65 +1132,57 @@ __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
     const int node = blockIdx.y, tid = threadIdx.x;
     Sel *s = a.sel + node;
     if (!a.force && s->fast_ok) return;
-    const float *v = a.v + (size_t)node * a.stride;
     const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock;
     uint32_t epoch = 0, prefix = 0, rank = a.k;
     if (a.force) {   // no sampling kernel ran in this call: the next call's state set is cleared here
         const uint32_t all = gridDim.y * nthreads;
         for (uint32_t i = blockIdx.y * nthreads + gtid; i < a.next_words; i += all) a.next_state[i] = 0;
     }
-
     for (int pass = 0; pass < 3; ++pass) {
-        const int nb = pass == 0 ? kRadixBins : 1024;
-        uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
-        for (int i = tid; i < nb; i += kBlock) hist[i] = 0;
-        __syncthreads();
-        auto count = [&](uint32_t key) {
-            if (pass == 0) atomicAdd(&hist[key >> 20], 1u);
-            else if (pass == 1) { if ((key >> 20) == prefix) atomicAdd(&hist[(key >> 10) & 1023u], 1u); }
-            else { if ((key >> 10) == prefix) atomicAdd(&hist[key & 1023u], 1u); }
-        };
-        if (VEC) {
-            const uint32_t n4 = a.n >> 2;
-            for (uint32_t i = gtid; i < n4; i += 4 * nthreads) {   // four 16-byte loads in flight per thread
-                f4 vv[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const uint32_t ii = i + r * nthreads;   // < 2^29 + 2^20: no wrap
-                    vv[r] = ii < n4 ? ((const f4 *)v)[ii] : (f4){0.f, 0.f, 0.f, 0.f};
-                }
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (i + r * nthreads < n4) {
-                        count(key_of(vv[r].x)); count(key_of(vv[r].y)); count(key_of(vv[r].z)); count(key_of(vv[r].w));
-                    }
-                }
-            }
-            for (uint32_t i = (n4 << 2) + gtid; i < a.n; i += nthreads) count(key_of(v[i]));
-        } else {
-            for (uint32_t i = gtid; i < a.n; i += nthreads) count(key_of(v[i]));
-        }
-        __syncthreads();
-        for (int i = tid; i < nb; i += kBlock) { const uint32_t h = hist[i]; if (h) atomicAdd(&gh[i], h); }
+        radix_count<VEC>(a, node, pass, prefix, hist);
         if (!node_barrier(a, a.ctr + node, epoch)) return;   // a wait expired somewhere: give up, lgc_stats reports it
-        for (int i = tid; i < kRadixBins; i += kBlock) hist[i] = i < nb ? ld_agent32(&gh[i]) : 0u;
-        __syncthreads();
-        if (pass == 0) find_rank_bin<kRadixBins>(hist, rank, wave_tmp, res);
-        else find_rank_bin<1024>(hist, rank, wave_tmp, res);
-        const uint32_t digit = res[0] == 0xffffffffu ? 0u : res[0];
-        rank -= res[1];
-        prefix = pass == 0 ? digit : ((prefix << 10) | digit);
-        __syncthreads();
+        radix_fix(a, node, pass, hist, wave_tmp, res, prefix, rank);
     }
     // prefix is now the full key T*; rank the number of ties to take
     if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }
-    // ordered output: block b owns the chunks [b * per, (b + 1) * per) of the node
-    const uint32_t nchunks = (a.n + kChunk - 1) / kChunk, per = (nchunks + gridDim.x - 1) / gridDim.x;
-    const uint32_t c_lo = blockIdx.x * per < nchunks ? blockIdx.x * per : nchunks;
-    const uint32_t c_hi = c_lo + per < nchunks ? c_lo + per : nchunks;
+    uint32_t c_lo, c_hi, nchunks;
+    block_run(a, c_lo, c_hi, nchunks);
     count_run<VEC>(a, node, prefix, c_lo, c_hi);
     if (!node_barrier(a, a.ctr + node, epoch)) return;
     emit_run<VEC>(a, node, prefix, rank, c_lo, c_hi, nchunks);
+}
+
+// The same path as five launches, for forced exact selection of long vectors: the kernel boundaries take the
+// place of the barriers, so the blocks need not be resident together (several contexts may run it at the same
+// time, whatever else the device is doing) and their number is chosen for the passes over v alone.  From 2^20
+// elements per call on this form is also the faster one (selection alone, one kernel with barriers against
+// five launches: 2^19 34 / 36 us, 2^20 51 / 39 us, 2^24 181 / 109 us, 4 x 2^24 374 / 256 us, 4 x 2^26 1225 / 987 us).  step 0..2: the radix pass of that digit (the digits before it are
+// fixed again from their finished histograms: a few microseconds, no exchange); step 3: T*, the tie quota and
+// the counts of every block's run; step 4: the ordered output.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_exact_step(SelArgs a, int step) {
+    __shared__ uint32_t hist[kRadixBins];
+    __shared__ uint32_t wave_tmp[kWaves], res[2];
+    const int node = blockIdx.y, tid = threadIdx.x;
+    Sel *s = a.sel + node;
+    if (step == 0) {   // forced path only: the next call's state set is cleared here
+        const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock, all = gridDim.y * nthreads;
+        for (uint32_t i = blockIdx.y * nthreads + gtid; i < a.next_words; i += all) a.next_state[i] = 0;
+    }
+    uint32_t c_lo, c_hi, nchunks;
+    block_run(a, c_lo, c_hi, nchunks);
+    if (step == 4) {
+        emit_run<VEC>(a, node, s->thr, s->quota, c_lo, c_hi, nchunks);
+        return;
+    }
+    uint32_t prefix = 0, rank = a.k;
+    for (int pass = 0; pass < (step < 3 ? step : 3); ++pass) radix_fix(a, node, pass, hist, wave_tmp, res, prefix, rank);
+    if (step < 3) {
+        radix_count<VEC>(a, node, step, prefix, hist);
+        return;
+    }
+    if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }
+    count_run<VEC>(a, node, prefix, c_lo, c_hi);
 }
 
 // The barriers need every block of every node to be running at the same time.  `resident` is how many
@@ -1137,11 +1197,13 @@ int exact_blocks_per_cu() {
     return m < 1 ? 1 : (m > 4 ? 4 : m);   // four blocks of 256 threads per unit are enough to keep the loads coming
 }
 
+constexpr uint64_t kStepMinElems = 1ull << 20;   // forced exact selection of this many elements (all nodes) and more: five launches
+
 void launch_exact(const SelArgs &a, int batch, bool vec, int cus, int resident, hipStream_t st) {
-    // One block per compute unit (shared by the nodes) up to 64 K elements per block, more blocks beyond
-    // that, as far as the device holds them: every block more makes the four barriers dearer (an L2
-    // write-back per block and barrier), every block less the five passes over v slower.  Measured at
-    // 2^20 .. 2^24 elements per node, 1 and 4 nodes.
+    // The kernel with barriers: one block per compute unit (shared by the nodes) up to 64 K elements per block,
+    // more blocks beyond that, as far as the device holds them: every block more makes the four barriers dearer
+    // (an L2 write-back per block and barrier), every block less the five passes over v slower.  It serves
+    // the fast path's fall-back (one launch that nearly always has nothing to do) and short forced calls.
     uint32_t per_node = (uint32_t)(cus / batch);
     const uint32_t by_size = a.n / 65536;
     if (per_node < by_size) per_node = by_size;
@@ -1149,6 +1211,19 @@ void launch_exact(const SelArgs &a, int batch, bool vec, int cus, int resident, 
     const uint32_t chunks = (a.n + kChunk - 1) / kChunk;
     if (per_node > chunks) per_node = chunks;
     if (per_node < 1) per_node = 1;
+    if (a.force && (uint64_t)a.n * batch >= kStepMinElems) {
+        // five launches, no barriers, no need to be resident together: about four blocks per compute unit in
+        // all (fewer make a block's share of a pass long, more make the histogram flushes dear)
+        per_node = (uint32_t)(4 * cus / batch);
+        if (per_node > chunks) per_node = chunks;
+        if (per_node < 1) per_node = 1;
+        dim3 grid2(per_node, batch);
+        for (int step = 0; step < 5; ++step) {
+            if (vec) hipLaunchKernelGGL(k_exact_step<true>, grid2, dim3(kBlock), 0, st, a, step);
+            else hipLaunchKernelGGL(k_exact_step<false>, grid2, dim3(kBlock), 0, st, a, step);
+        }
+        return;
+    }
     dim3 grid(per_node, batch);
     if (vec) hipLaunchKernelGGL(k_exact<true>, grid, dim3(kBlock), 0, st, a);
     else hipLaunchKernelGGL(k_exact<false>, grid, dim3(kBlock), 0, st, a);

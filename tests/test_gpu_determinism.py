@@ -89,11 +89,12 @@ def test_resume_from_saved_residuals(B, selection):
     ae.close()
 
 
-@pytest.mark.parametrize("force_exact", [False, True])
-def test_two_contexts_on_two_streams(B, force_exact):
+@pytest.mark.parametrize("force_exact,n", [(False, 1_500_000), (True, 1_500_000), (True, 6_000_000)])
+def test_two_contexts_on_two_streams(B, force_exact, n):
     """Two contexts, each on a stream of its own, run their iterations at the same time on the one GPU (the
-    exact path's persistent kernels of both share the compute units): each gives what it gives alone."""
-    w = synth.workload(2, n=1_500_000, nodes=2)
+    exact path's kernels of both share the compute units: one kernel with barriers each at the shorter
+    length, five launches each at the longer): each gives what it gives alone."""
+    w = synth.workload(2, n=n, nodes=2)
     K, n, k = w.nodes, w.n, w.k
     gs = [synth.gradients(w, t, device="cuda") for t in range(3)]
 

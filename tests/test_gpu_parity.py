@@ -144,6 +144,36 @@ def test_topk_fast_path_and_forced_exact(B, oracle, n, k):
     ctx.close()
 
 
+@pytest.mark.parametrize("n,batch,shift", [(1 << 23, 1, 0), (9_000_000, 1, 0), (2_200_001, 4, 0), (4_500_000, 2, 1),
+                                           (30_000_000, 1, 0)])
+def test_forced_exact_of_long_vectors(B, oracle, n, batch, shift):
+    """From 2^23 elements per call the forced exact path is five launches instead of one kernel with barriers
+    (the shorter cases of the other tests take that one): k from 1 to n / 3, few distinct magnitudes so that
+    the cut falls inside a tie group, rows and base pointers on and off the 16-byte grid."""
+    rng = np.random.default_rng(n + batch)
+    ctx = B.Context(n, n // 3, batch)
+    B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 1)
+    for trial, k in enumerate((1, n // 1000, n // 3)):
+        if trial == 1:
+            v0 = (rng.integers(-40, 41, (batch, n)) * 0.03125).astype(np.float32)
+        else:
+            v0 = rng.laplace(0, 1e-3, (batch, n)).astype(np.float32)
+        u0 = rng.standard_normal((batch, n)).astype(np.float32)
+        flat_v = torch.from_numpy(np.concatenate([np.zeros(shift, np.float32), v0.ravel()])).cuda()
+        flat_u = torch.from_numpy(np.concatenate([np.zeros(shift, np.float32), u0.ravel()])).cuda()
+        dv, du = flat_v[shift:].view(batch, n), flat_u[shift:].view(batch, n)
+        ovals = torch.full((batch, k), 7.0, device="cuda")
+        oidx = torch.full((batch, k), -1, device="cuda", dtype=torch.int32)
+        B.lgc_topk(ctx, dv, du, k, ovals, oidx)
+        assert B.lgc_stats(ctx) == (0, 0, 0)
+        for b in range(batch):
+            v1, u1 = v0[b].copy(), u0[b].copy()
+            vals, idx = oracle.topk(v1, u1, k)
+            assert (oidx[b].cpu().numpy().astype(np.uint32) == idx).all(), (trial, b)
+            assert same_bits(ovals[b], vals) and same_bits(dv[b], v1) and same_bits(du[b], u1), (trial, b)
+    ctx.close()
+
+
 def test_topk_falls_back_on_device(B, oracle):
     # all magnitudes equal: every element is a candidate, the list overflows, the device
     # switches to the exact path by itself; node 1 is ordinary and stays on the fast path
