@@ -399,7 +399,7 @@ void launch_scatter(const float *vals, const uint32_t *idx, uint32_t k, float sc
 // copied to LDS (they hold about as many entries as the block's own, the nodes' selections being
 // alike) and every thread searches them there.  A stretch too long for LDS is searched in place.
 constexpr int kScatterNodes = 8;
-constexpr int kScatterWin = 1024;
+constexpr int kScatterWin = 512;
 
 __global__ __launch_bounds__(256) void k_scatter_nodes(const float *__restrict__ vals,
                                                        const uint32_t *__restrict__ idx, uint32_t k, int batch,
