@@ -19,8 +19,9 @@
 //  all and no scattered stores; a small gather kernel lists the flagged elements in index order.
 //  The output over the candidates needs no communication between blocks either: short lists are
 //  read whole by every block, long lists are counted per 4096-candidate chunk by one kernel and
-//  written by the next.  The exact path is one persistent kernel whose blocks meet at barriers:
-//  three radix passes, a count of every block's run of v, and the ordered output of the runs.
+//  written by the next.  The exact path is three radix passes, a count of every block's run of v, and the
+//  ordered output of the runs: one persistent kernel whose blocks meet at barriers when it is the fast path's
+//  fall-back or the input is short, five launches when it is chosen outright for a long input.
 
 #include "device_helpers.h"
 
