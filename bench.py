@@ -42,9 +42,10 @@ def parse():
                         "rotating node selects and the others take the values at its positions (Alg. 2); "
                         "ps-innovation: Alg. 1 in full, every node also forms its innovation component (top 10 %% "
                         "of each layer's selected values) and the decoder takes it as one more channel")
-    p.add_argument("--selection", choices=["flat", "layers"], default="flat",
+    p.add_argument("--selection", choices=["flat", "layers"], default=None,
                    help="flat: one top-k over the whole vector (default, the headline); layers: per-layer "
-                        "top-k over the workload's layers, mu_l = max(1, floor(ratio n_l)) (Sec. V-A)")
+                        "top-k over the workload's layers, mu_l = max(1, floor(ratio n_l)) (Sec. V-A; the default "
+                        "of --pattern ps-innovation on workloads 2-4, Alg. 1 being written per layer)")
     p.add_argument("--ae", choices=["config", "paper"], default="config",
                    help="config: the workload's two-layer autoencoder (default); paper: Table I / Table II layer "
                         "shapes (1-64-128-256-64-4 / 4-4-32-64-128-32-1, leaky slope 0.01), deep layers on the matrix cores")
@@ -157,6 +158,8 @@ def main():
     torch.cuda.set_device(0)
 
     w = synth.workload(args.workload)
+    if args.selection is None:
+        args.selection = "layers" if args.pattern == "ps-innovation" and w.kind == "laplace_segments" else "flat"
     K, n = w.nodes, w.n
     k = w.ks[args.ratio_index]
     seg = None
