@@ -26,7 +26,6 @@ struct lgc_ctx {
     uint32_t state_words = 0;
     int cur = 0;                      // set the next call will use (it is clean)
     int cus = 1;                      // compute units of the device
-    int exact_resident = 1;           // blocks of the exact-path kernel that the device holds at once
     uint32_t rows = 0, status_cand_stride = 0, status_exact_stride = 0;
     uint32_t *samples = nullptr, *row_count = nullptr, *row_super = nullptr;
     uint32_t supers = 0;
@@ -249,10 +248,9 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
         }
         a.force = 1;   // the exact kernel then also clears the next call's state set
     }
-    // exact path: runs when forced, otherwise only for nodes the fast path handed back
-    // forced: all the blocks the device holds; as the fast path's fall-back, which nearly always has nothing
-    // to do, one block per compute unit (the launch of an idle grid four times larger costs more)
-    launch_exact(a, batch, vec, ctx->cus, a.force ? ctx->exact_resident : ctx->cus, st);
+    // exact path: runs when forced (as five launches when the input is long), otherwise only for nodes the fast
+    // path handed back: one launch of one block per compute unit, which nearly always has nothing to do
+    launch_exact(a, batch, vec, ctx->cus, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
     return LGC_OK;
@@ -283,7 +281,6 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
         hipError_t pe = hipGetDeviceProperties(&prop, device);
         if (pe != hipSuccess) { delete c; return fail(nullptr, LGC_EHIP, "hipGetDeviceProperties: %s", hipGetErrorString(pe)); }
         c->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
-        c->exact_resident = c->cus * exact_blocks_per_cu();
     }
     c->rows = (uint32_t)align_up((max_n + kRow - 1) / kRow, 4);
     c->status_exact_stride = (uint32_t)((max_n + kChunk - 1) / kChunk);

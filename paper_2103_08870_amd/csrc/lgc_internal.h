@@ -125,8 +125,7 @@ void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_
 void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
 void launch_gather(const SelArgs &a, int batch, hipStream_t st);
 void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hipStream_t st);
-int exact_blocks_per_cu();   // how many blocks of the exact-path kernel one compute unit holds (at most 4)
-void launch_exact(const SelArgs &a, int batch, bool vec, int cus, int resident, hipStream_t st);
+void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st);
 // per-layer selection (segmented.hip)
 void launch_seg_estimate(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
 void launch_seg_select(const SelArgs &a, int batch, bool vec, hipStream_t st);

@@ -1186,29 +1186,15 @@ __global__ __launch_bounds__(kBlock) void k_exact_step(SelArgs a, int step) {
     count_run<VEC>(a, node, prefix, c_lo, c_hi);
 }
 
-// The barriers need every block of every node to be running at the same time.  `resident` is how many
-// blocks of this kernel the device holds at once (lgc_create asks the runtime for the kernel's occupancy);
-// they are shared evenly by the nodes.  Several blocks per compute unit matter for the passes over v: with
-// one block of four wavefronts per unit they ran at 1.4 TB/s.
-int exact_blocks_per_cu() {
-    int a = 0, b = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&a, k_exact<true>, kBlock, 0) != hipSuccess) a = 1;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, k_exact<false>, kBlock, 0) != hipSuccess) b = 1;
-    const int m = a < b ? a : b;
-    return m < 1 ? 1 : (m > 4 ? 4 : m);   // four blocks of 256 threads per unit are enough to keep the loads coming
-}
-
 constexpr uint64_t kStepMinElems = 1ull << 20;   // forced exact selection of this many elements (all nodes) and more: five launches
 
-void launch_exact(const SelArgs &a, int batch, bool vec, int cus, int resident, hipStream_t st) {
-    // The kernel with barriers: one block per compute unit (shared by the nodes) up to 64 K elements per block,
-    // more blocks beyond that, as far as the device holds them: every block more makes the four barriers dearer
-    // (an L2 write-back per block and barrier), every block less the five passes over v slower.  It serves
-    // the fast path's fall-back (one launch that nearly always has nothing to do) and short forced calls.
+void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st) {
+    // The kernel with barriers needs all its blocks on the device at the same time: at most one block per
+    // compute unit, shared by the nodes (the device holds three of this kernel per unit, so several such
+    // kernels fit side by side).  Every block more makes the four barriers dearer (an L2 write-back per block
+    // and barrier), every block less the five passes over v slower.  It serves the fast path's fall-back (one
+    // launch that nearly always has nothing to do) and short forced calls.
     uint32_t per_node = (uint32_t)(cus / batch);
-    const uint32_t by_size = a.n / 65536;
-    if (per_node < by_size) per_node = by_size;
-    if (per_node > (uint32_t)(resident / batch)) per_node = (uint32_t)(resident / batch);
     const uint32_t chunks = (a.n + kChunk - 1) / kChunk;
     if (per_node > chunks) per_node = chunks;
     if (per_node < 1) per_node = 1;
