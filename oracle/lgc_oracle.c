@@ -155,14 +155,16 @@ void oracle_conv1d(const float *in, int c_in, size_t l_in,
  * dropped.  l_out is given by the caller (the length the mirrored encoder
  * layer consumed), which fixes the otherwise ambiguous output length.
  * Weight layout W[c_in][c_out][ksize].
+ * Returns 0, or -1 if the row of fp64 accumulators cannot be allocated.
  */
-void oracle_conv_transpose1d(const float *in, int c_in, size_t l_in,
+int oracle_conv_transpose1d(const float *in, int c_in, size_t l_in,
                              const float *w, const float *b, int c_out,
                              int ksize, int stride, size_t l_out,
                              int apply_act, float slope, float *out)
 {
     int pad = (ksize - 1) / 2;
     double *acc = (double *)malloc((l_out ? l_out : 1) * sizeof(double));
+    if (!acc) return -1;
     for (int co = 0; co < c_out; ++co) {
         for (size_t q = 0; q < l_out; ++q) acc[q] = (double)b[co];
         for (int ci = 0; ci < c_in; ++ci)
@@ -180,6 +182,7 @@ void oracle_conv_transpose1d(const float *in, int c_in, size_t l_in,
         }
     }
     free(acc);
+    return 0;
 }
 
 /*
@@ -234,8 +237,9 @@ int oracle_decode(const float *latent, size_t l_latent, int n_layers, const int 
         float *dst = last ? rec
                           : (float *)malloc(((size_t)chan[l + 1] * out_len[l] + 1) * sizeof(float));
         if (!dst) { free(owned); return -1; }
-        oracle_conv_transpose1d(cur, chan[l], len, w[l], b[l], chan[l + 1], ksize[l], stride[l],
-                                out_len[l], !last, slope, dst);
+        int rc = oracle_conv_transpose1d(cur, chan[l], len, w[l], b[l], chan[l + 1], ksize[l], stride[l],
+                                         out_len[l], !last, slope, dst);
+        if (rc != 0) { if (!last) free(dst); free(owned); return -1; }
         free(owned);
         owned = last ? NULL : dst;
         cur = dst;

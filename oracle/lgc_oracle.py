@@ -57,7 +57,7 @@ def _load():
         lib.oracle_conv1d.restype = None
         lib.oracle_conv_transpose1d.argtypes = [fp, C.c_int, C.c_size_t, fp, fp, C.c_int, C.c_int,
                                                 C.c_int, C.c_size_t, C.c_int, C.c_float, fp]
-        lib.oracle_conv_transpose1d.restype = None
+        lib.oracle_conv_transpose1d.restype = C.c_int
         lib.oracle_encode.argtypes = [fp, C.c_size_t, C.c_int, ip, ip, ip, C.POINTER(fp),
                                       C.POINTER(fp), C.c_float, fp]
         lib.oracle_encode.restype = C.c_size_t
@@ -136,8 +136,10 @@ def conv_transpose1d(x: np.ndarray, w: np.ndarray, b: np.ndarray, ksize: int, st
     c_out = w.shape[1]
     assert w.shape == (c_in, c_out, ksize) and b.shape == (c_out,)
     out = np.zeros((c_out, l_out), dtype=np.float32)
-    _load().oracle_conv_transpose1d(_f(x), c_in, l_in, _f(w), _f(b), c_out, ksize, stride,
-                                    l_out, int(apply_act), np.float32(slope), _f(out))
+    rc = _load().oracle_conv_transpose1d(_f(x), c_in, l_in, _f(w), _f(b), c_out, ksize, stride,
+                                         l_out, int(apply_act), np.float32(slope), _f(out))
+    if rc != 0:
+        raise MemoryError("oracle_conv_transpose1d: out of memory")
     return out
 
 

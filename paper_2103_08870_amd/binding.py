@@ -131,12 +131,19 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
+def _require(cond: bool, what: str) -> None:
+    """Shape / layout precondition of a call: the C ABI sees raw pointers only, so a tensor that
+    does not have the extent the call will touch must never reach it (also under ``python -O``)."""
+    if not cond:
+        raise ValueError(f"liblgc binding: {what}")
+
+
 def _layout(t: torch.Tensor) -> Tuple[int, int, int]:
     """(n, batch, stride) of a [n] or [batch][n] tensor whose rows are contiguous."""
     if t.dim() == 1:
-        assert t.stride(0) == 1
+        _require(t.stride(0) == 1 or t.shape[0] <= 1, "1-D tensor must be contiguous")
         return t.shape[0], 1, t.shape[0]
-    assert t.dim() == 2 and t.stride(1) == 1
+    _require(t.dim() == 2 and (t.stride(1) == 1 or t.shape[1] <= 1), "expected [batch][n] with contiguous rows")
     return t.shape[1], t.shape[0], (t.stride(0) if t.shape[0] > 1 else t.shape[1])
 
 
@@ -196,7 +203,7 @@ class Segments:
 
     def __init__(self, offsets: Sequence[int], ks: Sequence[int], device: int = 0):
         n_seg = len(ks)
-        assert len(offsets) == n_seg + 1
+        _require(len(offsets) == n_seg + 1, "len(offsets) == n_seg + 1")
         off = (C.c_uint64 * (n_seg + 1))(*[int(x) for x in offsets])
         kk = (C.c_uint64 * n_seg)(*[int(x) for x in ks])
         self.h = C.c_void_p()
@@ -220,7 +227,7 @@ class Segments:
 
 def lgc_accumulate(ctx: Context, g: torch.Tensor, u: torch.Tensor, v: torch.Tensor, momentum: float) -> None:
     n, batch, stride = _layout(v)
-    assert _layout(g) == _layout(u) == (n, batch, stride)
+    _require(_layout(g) == _layout(u) == (n, batch, stride), "_layout(g) == _layout(u) == (n, batch, stride)")
     _check(lib().lgc_accumulate(ctx.h, _ptr(g, torch.float32), _ptr(u, torch.float32), _ptr(v, torch.float32),
                                 n, batch, stride, momentum, _stream()), ctx.h)
 
@@ -228,8 +235,8 @@ def lgc_accumulate(ctx: Context, g: torch.Tensor, u: torch.Tensor, v: torch.Tens
 def lgc_topk(ctx: Context, v: torch.Tensor, u: Optional[torch.Tensor], k: int,
              out_vals: torch.Tensor, out_idx: torch.Tensor) -> None:
     n, batch, stride = _layout(v)
-    assert u is None or _layout(u) == (n, batch, stride)
-    assert out_vals.is_contiguous() and out_idx.is_contiguous() and out_vals.numel() == out_idx.numel() == batch * k
+    _require(u is None or _layout(u) == (n, batch, stride), "u is None or _layout(u) == (n, batch, stride)")
+    _require(out_vals.is_contiguous() and out_idx.is_contiguous() and out_vals.numel() == out_idx.numel() == batch * k, "out_vals.is_contiguous() and out_idx.is_contiguous() and out_vals.numel() == out_idx.numel() == batch * k")
     _check(lib().lgc_topk(ctx.h, _ptr(v, torch.float32), _ptr(u, torch.float32), n, batch, stride, k,
                           _ptr(out_vals, torch.float32), _ptr(out_idx, torch.int32), _stream()), ctx.h)
 
@@ -237,8 +244,8 @@ def lgc_topk(ctx: Context, v: torch.Tensor, u: Optional[torch.Tensor], k: int,
 def lgc_accumulate_topk(ctx: Context, g: torch.Tensor, u: torch.Tensor, v: torch.Tensor, momentum: float, k: int,
                         out_vals: torch.Tensor, out_idx: torch.Tensor) -> None:
     n, batch, stride = _layout(v)
-    assert _layout(g) == _layout(u) == (n, batch, stride)
-    assert out_vals.is_contiguous() and out_idx.is_contiguous() and out_vals.numel() == out_idx.numel() == batch * k
+    _require(_layout(g) == _layout(u) == (n, batch, stride), "_layout(g) == _layout(u) == (n, batch, stride)")
+    _require(out_vals.is_contiguous() and out_idx.is_contiguous() and out_vals.numel() == out_idx.numel() == batch * k, "out_vals.is_contiguous() and out_idx.is_contiguous() and out_vals.numel() == out_idx.numel() == batch * k")
     _check(lib().lgc_accumulate_topk(ctx.h, _ptr(g, torch.float32), _ptr(u, torch.float32), _ptr(v, torch.float32),
                                      n, batch, stride, momentum, k, _ptr(out_vals, torch.float32),
                                      _ptr(out_idx, torch.int32), _stream()), ctx.h)
@@ -250,26 +257,26 @@ def lgc_latent_len(ae: Autoencoder, k: int) -> int:
 
 def lgc_encode(ctx: Context, ae: Autoencoder, vals: torch.Tensor, latent: torch.Tensor) -> None:
     """vals [batch][k] -> latent [batch][lgc_latent_len(ae, k)]."""
-    assert vals.dim() == 2 and vals.is_contiguous() and latent.is_contiguous()
+    _require(vals.dim() == 2 and vals.is_contiguous() and latent.is_contiguous(), "vals.dim() == 2 and vals.is_contiguous() and latent.is_contiguous()")
     batch, k = vals.shape
-    assert latent.numel() == batch * lgc_latent_len(ae, k)
+    _require(latent.numel() == batch * lgc_latent_len(ae, k), "latent.numel() == batch * lgc_latent_len(ae, k)")
     _check(lib().lgc_encode(ctx.h, ae.h, _ptr(vals, torch.float32), k, batch, _ptr(latent, torch.float32),
                             _stream()), ctx.h)
 
 
 def lgc_decode(ctx: Context, ae: Autoencoder, latent: torch.Tensor, rec: torch.Tensor) -> None:
     """latent [batch][...] -> rec [batch][k]."""
-    assert rec.dim() == 2 and rec.is_contiguous() and latent.is_contiguous()
+    _require(rec.dim() == 2 and rec.is_contiguous() and latent.is_contiguous(), "rec.dim() == 2 and rec.is_contiguous() and latent.is_contiguous()")
     batch, k = rec.shape
-    assert latent.numel() == batch * lgc_latent_len(ae, k)
+    _require(latent.numel() == batch * lgc_latent_len(ae, k), "latent.numel() == batch * lgc_latent_len(ae, k)")
     _check(lib().lgc_decode(ctx.h, ae.h, _ptr(latent, torch.float32), k, batch, _ptr(rec, torch.float32),
                             _stream()), ctx.h)
 
 
 def lgc_scatter(ctx: Context, vals: torch.Tensor, idx: torch.Tensor, scale: float, dense: torch.Tensor) -> None:
     """vals, idx [batch][k] (or [k]); dense [n], updated in place, nodes in order."""
-    assert vals.is_contiguous() and idx.is_contiguous() and dense.is_contiguous() and dense.dim() == 1
-    assert vals.shape == idx.shape
+    _require(vals.is_contiguous() and idx.is_contiguous() and dense.is_contiguous() and dense.dim() == 1, "vals.is_contiguous() and idx.is_contiguous() and dense.is_contiguous() and dense.dim() == 1")
+    _require(vals.shape == idx.shape, "vals.shape == idx.shape")
     batch, k = (1, vals.shape[0]) if vals.dim() == 1 else vals.shape
     _check(lib().lgc_scatter(ctx.h, _ptr(vals, torch.float32), _ptr(idx, torch.int32), k, batch, scale,
                              _ptr(dense, torch.float32), dense.numel(), _stream()), ctx.h)
@@ -278,9 +285,9 @@ def lgc_scatter(ctx: Context, vals: torch.Tensor, idx: torch.Tensor, scale: floa
 def lgc_topk_segmented(ctx: Context, seg: Segments, v: torch.Tensor, u: Optional[torch.Tensor],
                        out_vals: torch.Tensor, out_idx: torch.Tensor) -> None:
     n, batch, stride = _layout(v)
-    assert n == seg.n and (u is None or _layout(u) == (n, batch, stride))
-    assert out_vals.is_contiguous() and out_idx.is_contiguous()
-    assert out_vals.numel() == out_idx.numel() == batch * seg.total_k
+    _require(n == seg.n and (u is None or _layout(u) == (n, batch, stride)), "n == seg.n and (u is None or _layout(u) == (n, batch, stride))")
+    _require(out_vals.is_contiguous() and out_idx.is_contiguous(), "out_vals.is_contiguous() and out_idx.is_contiguous()")
+    _require(out_vals.numel() == out_idx.numel() == batch * seg.total_k, "out_vals.numel() == out_idx.numel() == batch * seg.total_k")
     _check(lib().lgc_topk_segmented(ctx.h, seg.h, _ptr(v, torch.float32), _ptr(u, torch.float32), batch, stride,
                                     _ptr(out_vals, torch.float32), _ptr(out_idx, torch.int32), _stream()), ctx.h)
 
@@ -288,9 +295,9 @@ def lgc_topk_segmented(ctx: Context, seg: Segments, v: torch.Tensor, u: Optional
 def lgc_accumulate_topk_segmented(ctx: Context, seg: Segments, g: torch.Tensor, u: torch.Tensor, v: torch.Tensor,
                                   momentum: float, out_vals: torch.Tensor, out_idx: torch.Tensor) -> None:
     n, batch, stride = _layout(v)
-    assert n == seg.n and _layout(g) == _layout(u) == (n, batch, stride)
-    assert out_vals.is_contiguous() and out_idx.is_contiguous()
-    assert out_vals.numel() == out_idx.numel() == batch * seg.total_k
+    _require(n == seg.n and _layout(g) == _layout(u) == (n, batch, stride), "n == seg.n and _layout(g) == _layout(u) == (n, batch, stride)")
+    _require(out_vals.is_contiguous() and out_idx.is_contiguous(), "out_vals.is_contiguous() and out_idx.is_contiguous()")
+    _require(out_vals.numel() == out_idx.numel() == batch * seg.total_k, "out_vals.numel() == out_idx.numel() == batch * seg.total_k")
     _check(lib().lgc_accumulate_topk_segmented(ctx.h, seg.h, _ptr(g, torch.float32), _ptr(u, torch.float32),
                                                _ptr(v, torch.float32), batch, stride, momentum,
                                                _ptr(out_vals, torch.float32), _ptr(out_idx, torch.int32),
@@ -299,8 +306,8 @@ def lgc_accumulate_topk_segmented(ctx: Context, seg: Segments, g: torch.Tensor, 
 
 def lgc_innovation(ctx: Context, seg: Segments, vals: torch.Tensor, out: torch.Tensor) -> None:
     """vals [batch][k] -> out [batch][k]: per segment of the plan the top-magnitude values, +0 elsewhere."""
-    assert vals.dim() == 2 and vals.is_contiguous() and out.is_contiguous() and out.shape == vals.shape
-    assert vals.shape[1] == seg.n
+    _require(vals.dim() == 2 and vals.is_contiguous() and out.is_contiguous() and out.shape == vals.shape, "vals.dim() == 2 and vals.is_contiguous() and out.is_contiguous() and out.shape == vals.shape")
+    _require(vals.shape[1] == seg.n, "vals.shape[1] == seg.n")
     _check(lib().lgc_innovation(ctx.h, seg.h, _ptr(vals, torch.float32), vals.shape[0], _ptr(out, torch.float32),
                                 _stream()), ctx.h)
 
@@ -308,9 +315,9 @@ def lgc_innovation(ctx: Context, seg: Segments, vals: torch.Tensor, out: torch.T
 def lgc_decode_innovation(ctx: Context, ae: Autoencoder, latent: torch.Tensor, innov: torch.Tensor,
                           rec: torch.Tensor) -> None:
     """latent [batch][...] and innovation component [batch][k] -> rec [batch][k]."""
-    assert rec.dim() == 2 and rec.is_contiguous() and latent.is_contiguous() and innov.is_contiguous()
+    _require(rec.dim() == 2 and rec.is_contiguous() and latent.is_contiguous() and innov.is_contiguous(), "rec.dim() == 2 and rec.is_contiguous() and latent.is_contiguous() and innov.is_contiguous()")
     batch, k = rec.shape
-    assert innov.shape == rec.shape and latent.numel() == batch * lgc_latent_len(ae, k)
+    _require(innov.shape == rec.shape and latent.numel() == batch * lgc_latent_len(ae, k), "innov.shape == rec.shape and latent.numel() == batch * lgc_latent_len(ae, k)")
     _check(lib().lgc_decode_innovation(ctx.h, ae.h, _ptr(latent, torch.float32), _ptr(innov, torch.float32), k, batch,
                                        _ptr(rec, torch.float32), _stream()), ctx.h)
 
@@ -319,9 +326,9 @@ def lgc_gather(ctx: Context, v: torch.Tensor, u: Optional[torch.Tensor], idx: to
                out_vals: torch.Tensor) -> None:
     """Values of every node at the shared positions idx [k]; v, u zeroed there.  out_vals [batch][k]."""
     n, batch, stride = _layout(v)
-    assert u is None or _layout(u) == (n, batch, stride)
+    _require(u is None or _layout(u) == (n, batch, stride), "u is None or _layout(u) == (n, batch, stride)")
     k = idx.numel()
-    assert idx.is_contiguous() and out_vals.is_contiguous() and out_vals.numel() == batch * k
+    _require(idx.is_contiguous() and out_vals.is_contiguous() and out_vals.numel() == batch * k, "idx.is_contiguous() and out_vals.is_contiguous() and out_vals.numel() == batch * k")
     _check(lib().lgc_gather(ctx.h, _ptr(v, torch.float32), _ptr(u, torch.float32), n, batch, stride,
                             _ptr(idx, torch.int32), k, _ptr(out_vals, torch.float32), _stream()), ctx.h)
 
@@ -329,9 +336,9 @@ def lgc_gather(ctx: Context, v: torch.Tensor, u: Optional[torch.Tensor], idx: to
 def lgc_accumulate_gather(ctx: Context, g: torch.Tensor, u: torch.Tensor, v: torch.Tensor, momentum: float,
                           idx: torch.Tensor, out_vals: torch.Tensor) -> None:
     n, batch, stride = _layout(v)
-    assert _layout(g) == _layout(u) == (n, batch, stride)
+    _require(_layout(g) == _layout(u) == (n, batch, stride), "_layout(g) == _layout(u) == (n, batch, stride)")
     k = idx.numel()
-    assert idx.is_contiguous() and out_vals.is_contiguous() and out_vals.numel() == batch * k
+    _require(idx.is_contiguous() and out_vals.is_contiguous() and out_vals.numel() == batch * k, "idx.is_contiguous() and out_vals.is_contiguous() and out_vals.numel() == batch * k")
     _check(lib().lgc_accumulate_gather(ctx.h, _ptr(g, torch.float32), _ptr(u, torch.float32), _ptr(v, torch.float32),
                                        n, batch, stride, momentum, _ptr(idx, torch.int32), k,
                                        _ptr(out_vals, torch.float32), _stream()), ctx.h)
@@ -339,7 +346,7 @@ def lgc_accumulate_gather(ctx: Context, g: torch.Tensor, u: torch.Tensor, v: tor
 
 def lgc_average(ctx: Context, x: torch.Tensor, scale: float, out: torch.Tensor) -> None:
     """x [batch][len] -> out [len]: sum over nodes, in order, of scale*x."""
-    assert x.dim() == 2 and x.is_contiguous() and out.is_contiguous() and out.numel() == x.shape[1]
+    _require(x.dim() == 2 and x.is_contiguous() and out.is_contiguous() and out.numel() == x.shape[1], "x.dim() == 2 and x.is_contiguous() and out.is_contiguous() and out.numel() == x.shape[1]")
     _check(lib().lgc_average(ctx.h, _ptr(x, torch.float32), x.shape[1], x.shape[0], scale,
                              _ptr(out, torch.float32), _stream()), ctx.h)
 

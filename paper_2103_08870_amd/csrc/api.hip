@@ -600,6 +600,8 @@ static lgc_status run_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, 
     }
     if ((s = ensure_act(ctx, need)) != LGC_OK) return s;
     const float *cur = vals;
+    // a layer never writes the buffer it reads: the activation buffer that is not `cur`
+    auto other = [&](const float *c) { return c == ctx->act[0] ? ctx->act[1] : ctx->act[0]; };
     for (size_t l = 0; l < nl; ++l) {
         const bool last = l + 1 == nl;
         if (l == 0 && nl > 2) {   // the one-channel first layer inside the staging of the deep layer after it
@@ -612,7 +614,7 @@ static lgc_status run_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, 
         }
         if (l + 1 < nl) {   // a deep layer and the kernel-1 layer after it in one launch, where the shapes allow
             const bool next_last = l + 2 == nl;
-            float *dst2 = next_last ? latent : ctx->act[(l + 1) & 1];
+            float *dst2 = next_last ? latent : other(cur);
             if (launch_conv3s2_mfma(cur, dst2, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, true, ae->slope,
                                     st, &ae->enc_dev[l + 1], !next_last)) {
                 cur = dst2;
@@ -620,7 +622,7 @@ static lgc_status run_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, 
                 continue;
             }
         }
-        float *dst = last ? latent : ctx->act[l & 1];
+        float *dst = last ? latent : other(cur);
         if (!launch_conv3s2_mfma(cur, dst, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, !last, ae->slope, st))
             launch_conv1d(cur, dst, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, !last, ae->slope, st);
         cur = dst;
@@ -671,6 +673,8 @@ static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent
     }
     if ((s = ensure_act(ctx, need)) != LGC_OK) return s;
     const float *cur = latent;
+    // a layer never writes the buffer it reads: the activation buffer that is not `cur`
+    auto other = [&](const float *c) { return c == ctx->act[0] ? ctx->act[1] : ctx->act[0]; };
     for (size_t l = 0; l < nl; ++l) {
         const bool last = l + 1 == nl;
         if (l == 0 && nl > 3) {   // the two narrow first layers inside the staging of the deep layer after them
@@ -684,7 +688,7 @@ static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent
         }
         if (l + 1 < nl && !innov) {   // a deep layer and the kernel-1 layer after it in one launch, where the shapes allow
             const bool next_last = l + 2 == nl;
-            float *dst2 = next_last ? rec : ctx->act[(l + 1) & 1];
+            float *dst2 = next_last ? rec : other(cur);
             if (launch_convt3s2_mfma(cur, dst2, ae->dec_dev[l], (uint32_t)in_len, (uint32_t)out_len[l], batch, true, ae->slope,
                                      st, &ae->dec_dev[l + 1], !next_last)) {
                 cur = dst2;
@@ -693,7 +697,7 @@ static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent
                 continue;
             }
         }
-        float *dst = last ? rec : ctx->act[l & 1];
+        float *dst = last ? rec : other(cur);
         const float *extra = last ? innov : nullptr;
         if (extra || !launch_convt3s2_mfma(cur, dst, ae->dec_dev[l], (uint32_t)in_len, (uint32_t)out_len[l], batch, !last,
                                            ae->slope, st))

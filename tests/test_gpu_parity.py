@@ -376,6 +376,9 @@ STACKS = [
     ([(1, 24, 3, 2), (24, 40, 3, 2), (40, 5, 3, 1)], [(5, 40, 3, 1), (40, 24, 3, 2), (24, 1, 3, 2)]),
     # deep layers without narrow neighbours to fuse: 1 -> 32 (kernel 1) -> 64 -> 128 and back
     ([(1, 32, 1, 1), (32, 64, 3, 2), (64, 128, 3, 2)], [(128, 64, 3, 2), (64, 32, 3, 2), (32, 1, 3, 1)]),
+    # kernel-1 bottlenecks in the MIDDLE of both stacks: the deep layer and the kernel-1 layer after it run as one
+    # launch whose output is an intermediate tensor, not the stack's result
+    ([(1, 32, 1, 1), (32, 64, 3, 2), (64, 4, 1, 1), (4, 16, 3, 2)], [(16, 32, 3, 2), (32, 1, 1, 1), (1, 8, 3, 2), (8, 1, 3, 1)]),
 ]
 
 
