@@ -84,6 +84,9 @@ const char *lgc_status_string(lgc_status s);
  *        u <- momentum*u + g ;  v <- v + u        (in place, elementwise)
  * Three separate fp32 roundings per element, never a fused multiply-add;
  * denormals are kept.  momentum = 0 gives the paper's line exactly.
+ * A NaN operand, or Inf - Inf, gives a NaN; the sign and the payload of that
+ * NaN are not specified (processors differ in which operand's they pass on and
+ * in the NaN they generate).  Every result that is not a NaN is bit-exact.
  * g, u, v: [batch][stride] device fp32, n valid elements per node.
  */
 lgc_status lgc_accumulate(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n, int batch,
@@ -94,7 +97,8 @@ lgc_status lgc_accumulate(lgc_ctx *ctx, const float *g, float *u, float *v, uint
  * threshold, mask, g~ = mask.*g_l, g_acc keeps the rest.  Exactly k positions
  * per node are selected (Sec. V-A fixes the size of g~): order positions by
  * (|v| descending, index ascending) on the key bits(v) & 0x7fffffff and take
- * the first k.  Outputs per node b:
+ * the first k.  The key orders every fp32 value: -0 equals +0, NaNs lie above
+ * Inf and order among themselves by their payload bits.  Outputs per node b:
  *   out_idx [b*k .. b*k+k)  the selected positions, ascending
  *   out_vals[b*k .. b*k+k)  v at those positions (bit-exact, sign kept)
  * then v <- +0 at the selected positions, and u <- +0 there too (momentum

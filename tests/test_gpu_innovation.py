@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2103_08870_amd import synth
-from test_gpu_parity import B, REL_L2_TOL, dev, rel_l2, same_bits  # noqa: F401  (B is a fixture)
+from test_gpu_parity import B, REL_L2_TOL, assert_close, dev, rel_l2, same_bits  # noqa: F401  (B is a fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -65,7 +65,7 @@ def test_decode_with_innovation(B, oracle, channels, k, batch, slope):
     B.lgc_decode_innovation(ctx, ae, dev(latent), dev(innov), rec)
     for b in range(batch):
         ref = oracle.decode_with_innovation(latent[b].reshape(channels[-1], -1), innov[b], k, enc, dec, dw, db, slope)
-        assert rel_l2(rec[b], ref) <= REL_L2_TOL
+        assert_close(rec[b], ref, what=("reconstruction", b))
     # the two decoders do not take each other's autoencoders
     with pytest.raises(B.LgcError):
         B.lgc_decode(ctx, ae, dev(latent), rec)
@@ -115,9 +115,9 @@ def test_parameter_server_iteration_per_layer(B, oracle):
             assert same_bits(innov[b], oinv)
             assert np.count_nonzero(oinv) <= sum(inv_ks)
             olat = oracle.encode(ovals, enc, ew, eb)
-            assert rel_l2(lat[b], olat) <= REL_L2_TOL
+            assert_close(lat[b], olat, what=("latent", b))
             orec = oracle.decode_with_innovation(olat, oinv, mu, enc, dec, dw, db)
-            assert rel_l2(rec[b], orec) <= 2 * REL_L2_TOL
+            assert_close(rec[b], orec, factor=2.0, what=("reconstruction", b))
             oracle.scatter(rec_h[b], oidx, 1.0 / K, ref_dense)      # exact on the library's own reconstruction
         assert same_bits(dv, v) and same_bits(du, u)
         assert same_bits(dense, ref_dense)

@@ -7,14 +7,19 @@ import pytest
 import torch
 
 from paper_2103_08870_amd import synth
-from test_gpu_parity import B  # noqa: F401  (fixture)
+from test_gpu_parity import B, ELEM_TOL_DEEP, assert_close  # noqa: F401  (B is a fixture)
 
 pytestmark = pytest.mark.gpu
 
 
 def bits(t, a):
+    """Bit for bit, except that where the oracle holds a NaN any NaN will do: a NaN that went through the
+    accumulation keeps its NaN-ness, but its sign and payload follow the processor's propagation rule."""
     h = t.detach().cpu().numpy()
-    return h.shape == a.shape and bool((h.view(np.uint32) == a.view(np.uint32)).all())
+    if h.shape != a.shape:
+        return False
+    same = h.view(np.uint32) == a.view(np.uint32)
+    return bool((same | (np.isnan(h) & np.isnan(a))).all())
 
 
 def values(rng, shape, kind):
@@ -70,8 +75,6 @@ def case_flat(B, O, rng, desc):
     n = rand_n(rng); k = rand_k(rng, n); batch = int(rng.integers(1, 5))
     pad = int(rng.choice([0, 0, 1, 3, 4, 64])); shift = int(rng.choice([0, 0, 0, 1, 2, 4]))
     kind = int(rng.integers(0, 7)); fused = bool(rng.random() < 0.6); with_u = fused or bool(rng.random() < 0.6)
-    if fused and kind == 6:
-        kind = 4   # NaN payloads through an addition differ between the CPU and the GPU
     force = bool(rng.random() < 0.2); iters = int(rng.integers(1, 4)); m = float(rng.choice([0.0, 0.5, 0.9]))
     desc.append(f"flat n={n} k={k} batch={batch} pad={pad} shift={shift} kind={kind} fused={fused} u={with_u} force={force} iters={iters} m={m}")
     stride = n + pad
@@ -116,8 +119,6 @@ def case_seg(B, O, rng, desc):
         for i in rng.integers(0, n_seg, 3):
             ks[i] = int(rng.integers(0, off[i + 1] - off[i] + 1))
     fused = bool(rng.random() < 0.6); iters = int(rng.integers(1, 3))
-    if fused and kind == 6:
-        kind = 4
     desc.append(f"seg n={n} n_seg={n_seg} total_k={sum(ks)} batch={batch} kind={kind} fused={fused} iters={iters}")
     total = sum(ks)
     ctx = B.Context(n, max(total, 1), batch)
@@ -168,11 +169,6 @@ def case_scatter(B, O, rng, desc):
     ctx.close()
 
 
-def rel_l2(t, a):
-    h = t.detach().cpu().numpy().astype(np.float64).ravel(); a = a.astype(np.float64).ravel()
-    return float(np.linalg.norm(h - a) / max(np.linalg.norm(a), 1e-300))
-
-
 CH = [1, 2, 3, 4, 5, 8, 12, 16, 24, 32, 48, 64, 128]
 
 
@@ -217,9 +213,9 @@ def case_ae(B, O, rng, desc):
     rec = torch.zeros((batch, k), device="cuda")
     B.lgc_decode(ctx, ae, torch.from_numpy(np.stack([o.ravel() for o in ols])).cuda(), rec)
     for b in range(batch):
-        e1 = rel_l2(lat[b], ols[b])
-        e2 = rel_l2(rec[b], O.decode(ols[b], k, enc, dec, hw[2], hw[3], slope=slope))
-        assert e1 <= 1e-4 and e2 <= 1e-4, (b, e1, e2)
+        assert_close(lat[b], ols[b], elem=ELEM_TOL_DEEP, what=("latent", b))
+        assert_close(rec[b], O.decode(ols[b], k, enc, dec, hw[2], hw[3], slope=slope), elem=ELEM_TOL_DEEP,
+                     what=("reconstruction", b))
     ctx.close(); ae.close()
 
 

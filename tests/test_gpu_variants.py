@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2103_08870_amd import synth
-from test_gpu_parity import B, REL_L2_TOL, dev, make_ae, rel_l2, same_bits  # noqa: F401  (B is a fixture)
+from test_gpu_parity import B, REL_L2_TOL, assert_close, dev, make_ae, rel_l2, same_bits  # noqa: F401  (B is a fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -114,12 +114,12 @@ def test_ring_allreduce_iterations(B, oracle, cfg, n):
         assert same_bits(vals, ovals) and same_bits(dv, v) and same_bits(du, u)
         olat = np.stack([oracle.encode(ovals[b], enc, ew, eb).ravel() for b in range(K)])
         for b in range(K):
-            assert rel_l2(lat[b], olat[b]) <= REL_L2_TOL
+            assert_close(lat[b], olat[b], what=("latent", b))
         lat_h = lat.cpu().numpy()
         assert same_bits(avg[0], oracle.average(lat_h, 1.0 / K))              # exact on the same input
         oavg = oracle.average(olat, 1.0 / K)
         orec = oracle.decode(oavg.reshape(w.ae_channels[-1], -1), k, enc, dec, dw, db)
-        assert rel_l2(rec[0], orec) <= 2 * REL_L2_TOL
+        assert_close(rec[0], orec, factor=2.0, what="reconstruction of the average")
         ref = np.zeros(n, np.float32)
         oracle.scatter(rec[0].cpu().numpy(), oidx, 1.0, ref)
         assert same_bits(dense, ref)
