@@ -115,6 +115,35 @@ lgc_status lgc_accumulate_topk(lgc_ctx *ctx, const float *g, float *u, float *v,
                                float *out_vals, uint32_t *out_idx, void *stream);
 
 /*
+ * lgc_accumulate_topk for callers that cannot allocate device memory and cannot
+ * hold a context that did: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results bit for bit as
+ * lgc_accumulate_topk, but no lgc_ctx: the selection scratch (candidate bitmap,
+ * row counts, candidate list, histograms) is a fixed array of
+ * LGC_STATIC_SCRATCH_BYTES in the library's device image, which every GPU
+ * that runs the library holds until the process ends.  The call allocates and
+ * frees nothing, on the device or through the HIP runtime, and never
+ * synchronises.  The first call on a device looks the array's address up once.
+ *  - Limit: the scratch a context for exactly (n, k, batch) would need must fit
+ *    the array: about batch * (n / 8 + 12 * (1.5 k + 9 sqrt(k n / 65536)) + 1 MB)
+ *    bytes, e.g. 4 nodes x 25.6 M elements with k = 25 600, or one node of
+ *    2^27 elements with k = 2^17.  Larger inputs are rejected with LGC_EINVAL
+ *    (the message names the sizes); use a context for them.
+ *  - All calls on one GPU share that GPU's array: calls that overlap in time
+ *    on one GPU (different streams or threads) race.  The array keeps the last
+ *    call's contents; every call clears what it needs at zero with a fill
+ *    kernel of its own (no memset), so any number of calls may be recorded
+ *    into one HIP graph.
+ *  - `device` is the HIP device the pointers live on.  lgc_last_error(NULL)
+ *    gives the message of a failing call.  The counters of lgc_stats are not
+ *    available through this entry point.
+ */
+#define LGC_STATIC_SCRATCH_BYTES (32u << 20)
+lgc_status lgc_accumulate_topk_static(int device, const float *g, float *u, float *v, uint64_t n, int batch,
+                                      uint64_t stride, float momentum, uint64_t k, float *out_vals,
+                                      uint32_t *out_idx, void *stream);
+
+/*
  * Autoencoder description — Sec. IV-C, Tables I and II: a stack of 1-D
  * convolutions (encoder) and 1-D transposed convolutions (decoder).
  * Each layer has kernel size 1 or 3, stride 1 or 2 and padding (ksize-1)/2, so

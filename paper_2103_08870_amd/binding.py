@@ -21,7 +21,7 @@ LGC_OPT_SELECT_PATH, LGC_OPT_PROFILE = 0, 1
 
 EXPORTS = [
     "lgc_create", "lgc_destroy", "lgc_last_error", "lgc_status_string",
-    "lgc_accumulate", "lgc_topk", "lgc_accumulate_topk",
+    "lgc_accumulate", "lgc_topk", "lgc_accumulate_topk", "lgc_accumulate_topk_static",
     "lgc_ae_create", "lgc_ae_destroy", "lgc_latent_len", "lgc_encode", "lgc_decode",
     "lgc_scatter", "lgc_set_option", "lgc_stats", "lgc_profile_read",
     "lgc_gather", "lgc_accumulate_gather", "lgc_average",
@@ -68,6 +68,8 @@ def lib() -> C.CDLL:
     l.lgc_topk.restype = i32
     l.lgc_accumulate_topk.argtypes = [vp, vp, vp, vp, u64, i32, u64, f32, u64, vp, vp, vp]
     l.lgc_accumulate_topk.restype = i32
+    l.lgc_accumulate_topk_static.argtypes = [i32, vp, vp, vp, u64, i32, u64, f32, u64, vp, vp, vp]
+    l.lgc_accumulate_topk_static.restype = i32
     l.lgc_ae_create.argtypes = [C.POINTER(vp), i32, i32, C.POINTER(_Layer), i32, C.POINTER(_Layer), f32,
                                 C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
     l.lgc_ae_create.restype = i32
@@ -249,6 +251,18 @@ def lgc_accumulate_topk(ctx: Context, g: torch.Tensor, u: torch.Tensor, v: torch
     _check(lib().lgc_accumulate_topk(ctx.h, _ptr(g, torch.float32), _ptr(u, torch.float32), _ptr(v, torch.float32),
                                      n, batch, stride, momentum, k, _ptr(out_vals, torch.float32),
                                      _ptr(out_idx, torch.int32), _stream()), ctx.h)
+
+
+def lgc_accumulate_topk_static(g: torch.Tensor, u: torch.Tensor, v: torch.Tensor, momentum: float, k: int,
+                               out_vals: torch.Tensor, out_idx: torch.Tensor) -> None:
+    """lgc_accumulate_topk without a context: the scratch is the library's fixed device array."""
+    n, batch, stride = _layout(v)
+    _require(_layout(g) == _layout(u) == (n, batch, stride), "g, u, v must share n, batch and row stride")
+    _require(out_vals.is_contiguous() and out_idx.is_contiguous() and out_vals.numel() == out_idx.numel() == batch * k,
+             "out_vals / out_idx must be contiguous with batch * k elements")
+    _check(lib().lgc_accumulate_topk_static(v.device.index or 0, _ptr(g, torch.float32), _ptr(u, torch.float32),
+                                            _ptr(v, torch.float32), n, batch, stride, momentum, k,
+                                            _ptr(out_vals, torch.float32), _ptr(out_idx, torch.int32), _stream()), None)
 
 
 def lgc_latent_len(ae: Autoencoder, k: int) -> int:

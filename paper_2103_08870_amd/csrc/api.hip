@@ -7,6 +7,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -19,7 +20,8 @@ struct lgc_ctx {
     uint64_t max_n = 0, max_k = 0;
     int max_batch = 0;
     uint32_t cap = 0;
-    void *scratch = nullptr;  // one device allocation, carved below
+    void *scratch = nullptr;  // one device allocation, carved by scratch_layout (not owned when the context is a view of the static scratch)
+    bool single_state = false;  // one state set, cleared by a launch of its own at the start of every call
     Stats *stats = nullptr;
     // two state sets (Sel records, histograms, chunk and block counts), used by alternate calls
     uint32_t *state[2] = {nullptr, nullptr};
@@ -184,6 +186,59 @@ StateLayout state_layout(int max_batch, uint32_t status_cand_stride, uint32_t st
     return L;
 }
 
+// The selection scratch of a context for (max_n, max_k, max_batch): byte offsets of its parts in one block of
+// device memory.  Everything before `samples` (statistics, state sets) must start at zero.
+struct ScratchLayout {
+    bool ok = false;
+    uint32_t cap = 0, rows = 0, supers = 0, status_cand_stride = 0, status_exact_stride = 0, state_words = 0;
+    size_t stats = 0, state[2] = {0, 0}, samples = 0, row_count = 0, row_super = 0, bitmap = 0, cand_idx = 0, cand_val = 0;
+    size_t bytes = 0;
+};
+
+ScratchLayout scratch_layout(uint64_t max_n, uint64_t max_k, int max_batch, bool two_state_sets) {
+    ScratchLayout s;
+    s.cap = candidate_capacity(max_n, max_k);
+    s.rows = (uint32_t)align_up((max_n + kRow - 1) / kRow, 4);
+    s.status_exact_stride = (uint32_t)((max_n + kChunk - 1) / kChunk);
+    s.status_cand_stride = (s.cap + kChunk - 1) / kChunk;
+    const StateLayout L = state_layout(max_batch, s.status_cand_stride, s.status_exact_stride);
+    if (L.words >= (1ull << 31)) return s;
+    s.state_words = (uint32_t)L.words;
+    s.supers = (s.rows + kSuperRows - 1) / kSuperRows;
+    const size_t B = (size_t)max_batch, A = 256;
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, A); return o; };
+    s.stats = carve(sizeof(Stats));
+    s.state[0] = carve(L.words * 4);
+    s.state[1] = two_state_sets ? carve(L.words * 4) : s.state[0];
+    s.samples = carve(B * kSample * 4);
+    s.row_count = carve(B * s.rows * 4);
+    s.row_super = carve(B * s.supers * 4);
+    s.bitmap = carve(B * (size_t)s.rows * kRowWords * 8);
+    s.cand_idx = carve(B * (size_t)s.cap * 4);
+    s.cand_val = carve(B * (size_t)s.cap * 4);
+    s.bytes = off;
+    s.ok = true;
+    return s;
+}
+
+void bind_scratch(lgc_ctx *c, void *base_ptr, const ScratchLayout &s) {
+    char *base = (char *)base_ptr;
+    c->scratch = base_ptr;
+    c->cap = s.cap; c->rows = s.rows; c->supers = s.supers;
+    c->status_cand_stride = s.status_cand_stride; c->status_exact_stride = s.status_exact_stride;
+    c->state_words = s.state_words;
+    c->stats = (Stats *)(base + s.stats);
+    c->state[0] = (uint32_t *)(base + s.state[0]);
+    c->state[1] = (uint32_t *)(base + s.state[1]);
+    c->samples = (uint32_t *)(base + s.samples);
+    c->row_count = (uint32_t *)(base + s.row_count);
+    c->row_super = (uint32_t *)(base + s.row_super);
+    c->bitmap = (unsigned long long *)(base + s.bitmap);
+    c->cand_idx = (uint32_t *)(base + s.cand_idx);
+    c->cand_val = (uint32_t *)(base + s.cand_val);
+}
+
 SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, uint64_t stride, float m,
                   uint64_t k, float *out_vals, uint32_t *out_idx) {
     SelArgs a;
@@ -202,7 +257,7 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     a.sample_hist = cur + L.sample_hist; a.fine_hist = cur + L.fine_hist; a.level2_hist = cur + L.level2_hist; a.radix_hist = cur + L.radix_hist;
     a.status_cand = (unsigned long long *)(cur + L.status_cand);
     a.status_exact = (unsigned long long *)(cur + L.status_exact);
-    a.next_state = c->state[c->cur ^ 1]; a.next_words = c->state_words;
+    a.next_state = c->state[c->cur ^ 1]; a.next_words = c->single_state ? 0u : c->state_words;
     a.samples = c->samples; a.row_count = c->row_count; a.bitmap = c->bitmap;
     a.row_super = c->row_super; a.supers = c->supers;
     a.cand_idx = c->cand_idx; a.cand_val = c->cand_val;
@@ -275,56 +330,29 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
     lgc_ctx *c = new (std::nothrow) lgc_ctx;
     if (!c) return fail(nullptr, LGC_ENOMEM, "out of host memory");
     c->device = device; c->max_n = max_n; c->max_k = max_k; c->max_batch = max_batch;
-    c->cap = candidate_capacity(max_n, max_k);
     {
         hipDeviceProp_t prop;
         hipError_t pe = hipGetDeviceProperties(&prop, device);
         if (pe != hipSuccess) { delete c; return fail(nullptr, LGC_EHIP, "hipGetDeviceProperties: %s", hipGetErrorString(pe)); }
         c->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
     }
-    c->rows = (uint32_t)align_up((max_n + kRow - 1) / kRow, 4);
-    c->status_exact_stride = (uint32_t)((max_n + kChunk - 1) / kChunk);
-    c->status_cand_stride = (c->cap + kChunk - 1) / kChunk;
-    const StateLayout L = state_layout(max_batch, c->status_cand_stride, c->status_exact_stride);
-    if (L.words >= (1ull << 31)) { delete c; return fail(nullptr, LGC_EINVAL, "max_n * max_batch too large"); }
-    c->state_words = (uint32_t)L.words;
-
-    const size_t B = (size_t)max_batch, A = 256;
-    size_t off = 0;
-    auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, A); return o; };
-    const size_t o_stats = carve(sizeof(Stats));
-    const size_t o_state0 = carve(L.words * 4);
-    const size_t o_state1 = carve(L.words * 4);
-    const size_t o_samples = carve(B * kSample * 4);
-    const size_t o_rcount = carve(B * c->rows * 4);
-    c->supers = (c->rows + kSuperRows - 1) / kSuperRows;
-    const size_t o_rsuper = carve(B * c->supers * 4);
-    const size_t o_bitmap = carve(B * (size_t)c->rows * kRowWords * 8);
-    const size_t o_cidx = carve(B * (size_t)c->cap * 4);
-    const size_t o_cval = carve(B * (size_t)c->cap * 4);
-    hipError_t e = hipMalloc(&c->scratch, off);
+    const ScratchLayout L = scratch_layout(max_n, max_k, max_batch, true);
+    if (!L.ok) { delete c; return fail(nullptr, LGC_EINVAL, "max_n * max_batch too large"); }
+    void *block = nullptr;
+    hipError_t e = hipMalloc(&block, L.bytes);
     if (e != hipSuccess) {
         delete c;
-        return fail(nullptr, LGC_ENOMEM, "hipMalloc of %zu bytes of scratch: %s", off, hipGetErrorString(e));
+        return fail(nullptr, LGC_ENOMEM, "hipMalloc of %zu bytes of scratch: %s", L.bytes, hipGetErrorString(e));
     }
     // only the statistics and the two state sets must start at zero
-    e = hipMemset(c->scratch, 0, o_samples);
+    e = hipMemset(block, 0, L.samples);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
-        (void)hipFree(c->scratch);
+        (void)hipFree(block);
         delete c;
         return fail(nullptr, LGC_EHIP, "hipMemset: %s", hipGetErrorString(e));
     }
-    char *base = (char *)c->scratch;
-    c->stats = (Stats *)(base + o_stats);
-    c->state[0] = (uint32_t *)(base + o_state0);
-    c->state[1] = (uint32_t *)(base + o_state1);
-    c->samples = (uint32_t *)(base + o_samples);
-    c->row_count = (uint32_t *)(base + o_rcount);
-    c->row_super = (uint32_t *)(base + o_rsuper);
-    c->bitmap = (unsigned long long *)(base + o_bitmap);
-    c->cand_idx = (uint32_t *)(base + o_cidx);
-    c->cand_val = (uint32_t *)(base + o_cval);
+    bind_scratch(c, block, L);
     *out = c;
     return LGC_OK;
 }
@@ -400,6 +428,85 @@ extern "C" lgc_status lgc_accumulate_topk(lgc_ctx *ctx, const float *g, float *u
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
     return run_select(ctx, g, u, v, n, batch, stride, momentum, k, out_vals, out_idx, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------ a1 + a2 without any allocation
+
+// Selection scratch for callers that cannot allocate (see lgc_accumulate_topk_static in lgc.h): a fixed array in
+// device memory, one copy on every GPU that loads the library, held until the process ends.  In host code this
+// NAME is only a handle for hipGetSymbolAddress; the array's memory on a given GPU is reached through the
+// address that call returns for that GPU (static_dev[].ptr), never through the name.
+constexpr size_t kStaticScratchBytes = (size_t)LGC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char lgc_static_scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxStaticDevices = 64;
+struct StaticDev {
+    unsigned char *ptr = nullptr;   // this GPU's copy of lgc_static_scratch
+    int cus = 1;
+    bool ready = false;
+};
+StaticDev static_dev[kMaxStaticDevices];
+std::mutex static_dev_mutex;
+
+// once per device, with that device current
+lgc_status static_dev_setup(int device, StaticDev **out) {
+    std::lock_guard<std::mutex> lock(static_dev_mutex);
+    StaticDev &d = static_dev[device];
+    if (!d.ready) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(lgc_static_scratch));
+        if (e != hipSuccess || !p)
+            return fail(nullptr, LGC_EHIP, "hipGetSymbolAddress(lgc_static_scratch) on device %d: %s", device, hipGetErrorString(e));
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+        if (e != hipSuccess) return fail(nullptr, LGC_EHIP, "hipDeviceGetAttribute: %s", hipGetErrorString(e));
+        d.ptr = (unsigned char *)p;
+        d.cus = cus > 0 ? cus : 1;
+        d.ready = true;
+    }
+    *out = &d;
+    return LGC_OK;
+}
+}  // namespace
+
+extern "C" lgc_status lgc_accumulate_topk_static(int device, const float *g, float *u, float *v, uint64_t n, int batch,
+                                                 uint64_t stride, float momentum, uint64_t k, float *out_vals,
+                                                 uint32_t *out_idx, void *stream) {
+    if (n == 0 || n >= (1ull << 31)) return fail(nullptr, LGC_EINVAL, "n must be in [1, 2^31)");
+    if (batch < 1 || batch > 4096) return fail(nullptr, LGC_EINVAL, "batch must be in [1, 4096]");
+    if (batch > 1 && stride < n) return fail(nullptr, LGC_EINVAL, "stride < n");
+    if (k > n) return fail(nullptr, LGC_EINVAL, "k = %llu > n = %llu", (unsigned long long)k, (unsigned long long)n);
+    if (!g || !u || !v) return fail(nullptr, LGC_EINVAL, "g, u and v must not be NULL");
+    if (k > 0 && (!out_vals || !out_idx)) return fail(nullptr, LGC_EINVAL, "out_vals and out_idx must not be NULL");
+    if (!aligned(g, 4) || !aligned(u, 4) || !aligned(v, 4) || !aligned(out_vals, 4) || !aligned(out_idx, 4))
+        return fail(nullptr, LGC_EINVAL, "pointer not 4-byte aligned");
+    // the same scratch a context for exactly (n, k, batch) would own, with one state set instead of two
+    const ScratchLayout L = scratch_layout(n, k, batch, false);
+    if (!L.ok || L.bytes > kStaticScratchBytes)
+        return fail(nullptr, LGC_EINVAL,
+                    "lgc_accumulate_topk_static: n = %llu, k = %llu, batch = %d need %zu bytes of scratch, the static "
+                    "scratch holds %zu (about batch * (n / 8 + 1 MB)); use a context (lgc_create) for larger inputs",
+                    (unsigned long long)n, (unsigned long long)k, batch, L.ok ? L.bytes : (size_t)0, kStaticScratchBytes);
+    int ndev = 0;
+    HIP_TRY(nullptr, hipGetDeviceCount(&ndev));
+    if (device < 0 || device >= ndev || device >= kMaxStaticDevices) return fail(nullptr, LGC_EINVAL, "no HIP device %d", device);
+    DeviceGuard guard(device);
+    if (!guard.ok) return fail(nullptr, LGC_EHIP, "cannot select device %d", device);
+    StaticDev *sd = nullptr;
+    lgc_status s = static_dev_setup(device, &sd);
+    if (s != LGC_OK) return s;
+
+    lgc_ctx view;   // a view of the static scratch for this call; lives on the stack, owns nothing
+    view.device = device; view.max_n = n; view.max_k = k; view.max_batch = batch;
+    view.cus = sd->cus;
+    view.single_state = true;
+    bind_scratch(&view, sd->ptr, L);
+    hipStream_t st = (hipStream_t)stream;
+    // the array keeps the last call's contents: statistics and the state set start every call at zero
+    // (a fill kernel, not a memset, so that the call can be recorded into a HIP graph)
+    if (k > 0) launch_clear((uint32_t *)sd->ptr, (uint32_t)(L.samples / 4), st);
+    return run_select(&view, g, u, v, n, batch, stride, momentum, k, out_vals, out_idx, st);
 }
 
 // ------------------------------------------------------------------ autoencoder
