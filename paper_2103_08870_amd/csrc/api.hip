@@ -247,7 +247,7 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     a.stride = stride; a.n = (uint32_t)n; a.k = (uint32_t)k; a.momentum = m;
     a.rank = 0; a.cap = c->cap; a.rows = c->rows;
     a.status_cand_stride = c->status_cand_stride; a.status_exact_stride = c->status_exact_stride;
-    a.spin_limit = 1u << 20;
+    a.spin_limit = 1u << 22;
     a.force = 0;
     a.stats = c->stats;
     const StateLayout L = state_layout(c->max_batch, c->status_cand_stride, c->status_exact_stride);
@@ -304,7 +304,7 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
         a.force = 1;   // the exact kernel then also clears the next call's state set
     }
     // exact path: runs when forced (as five launches when the input is long), otherwise only for nodes the fast
-    // path handed back: one launch of one block per compute unit, which nearly always has nothing to do
+    // path handed back: one launch of one block per node, which nearly always has nothing to do
     launch_exact(a, batch, vec, ctx->cus, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));

@@ -57,8 +57,9 @@ static_assert(sizeof(Sel) == 64, "Sel is one 64-byte record");
 // live in a cache line of their own: a line that receives atomics from several XCDs must not
 // also receive plain stores in the same kernel (each XCD has its own, non-coherent L2).
 struct Ctr {
-    uint32_t barrier;     // exact path: arrivals at the node's barrier
-    uint32_t pad[31];
+    uint32_t ticket;      // exact path in one launch: next share to hand out (phase = ticket / shares)
+    uint32_t done[5];     // completed shares of each phase
+    uint32_t pad[26];
 };
 static_assert(sizeof(Ctr) == 128, "Ctr is one 128-byte line");
 
@@ -80,7 +81,7 @@ struct SelArgs {
     uint32_t cap;     // capacity of the gathered candidate list, per node
     uint32_t rows;    // bitmap rows per node (stride of row_count; bitmap stride is rows * kRowWords)
     uint32_t status_cand_stride, status_exact_stride;  // 64-bit words per node: chunk counts of the candidate list, block counts of the exact path
-    uint32_t spin_limit;      // bound of the wait at a node barrier
+    uint32_t spin_limit;      // bound of a wait for the shares of the previous phase (exact path in one launch)
     int force;                // exact path chosen by the host (ignore fast_ok)
     Stats *stats;
     // current state set

@@ -20,8 +20,9 @@
 //  The output over the candidates needs no communication between blocks either: short lists are
 //  read whole by every block, long lists are counted per 4096-candidate chunk by one kernel and
 //  written by the next.  The exact path is three radix passes, a count of every block's run of v, and the
-//  ordered output of the runs: one persistent kernel whose blocks meet at barriers when it is the fast path's
-//  fall-back or the input is short, five launches when it is chosen outright for a long input.
+//  ordered output of the runs: all in one block per node when it is the fast path's fall-back or the input is
+//  short, five launches of many blocks when it is chosen outright for a long input.  No block of any kernel
+//  here ever waits for another block.
 
 #include "device_helpers.h"
 
@@ -207,9 +208,10 @@ void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_
 // ------------------------------------------------------------------ candidate pass (the streaming kernel)
 
 // One full row of a wavefront: 4 x 256 consecutive elements, lane l holds elements 4l..4l+3 of
-// each 256.  All twelve 16-byte loads are issued before anything depends on them.  In the fused
-// pass every stream is touched once per call, so all loads and stores are non-temporal: on this
-// part that alone lifts the kernel from about 60 % to 72-77 % of the HBM peak.
+// each 256.  All twelve 16-byte loads are issued before anything depends on them.  Every stream
+// is touched once per call, so all loads and stores are non-temporal: on this part that alone
+// lifts the fused kernel from about 60 % to 72-77 % of the HBM peak (and the plain read of v in
+// the selection-only form likewise; the few candidates' values are read again by the gather).
 template <bool FUSED>
 __device__ __forceinline__ void full_row(const float *__restrict__ g, float *__restrict__ u, float *__restrict__ v,
                                          const float m, uint32_t (&bits)[4][4]) {
@@ -220,7 +222,7 @@ __device__ __forceinline__ void full_row(const float *__restrict__ g, float *__r
             gg[s] = __builtin_nontemporal_load((const f4 *)(g + s * 256));
             uu[s] = __builtin_nontemporal_load((const f4 *)(u + s * 256));
         }
-        vv[s] = FUSED ? __builtin_nontemporal_load((const f4 *)(v + s * 256)) : *(const f4 *)(v + s * 256);
+        vv[s] = __builtin_nontemporal_load((const f4 *)(v + s * 256));
     }
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -755,16 +757,17 @@ __global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
 
 // The threshold T* and the tie quota are known.  The selected elements (key > T*, and the first
 // `quota` elements with key == T*) are written to the output in index order and zeroed in v
-// (and u), reading v itself.  Every block of the node owns a run of consecutive 4096-element chunks.
+// (and u), reading v itself.  Every block of the node (THREADS threads) owns a run of consecutive chunks of
+// 16 * THREADS elements: kRows rows of 4 * THREADS, four consecutive elements per thread and row.
 // load_chunk: the value bits of this thread's 16 elements of a chunk and their flags (bit r*4+j).
-template <bool VEC>
+template <bool VEC, int THREADS>
 __device__ __forceinline__ void load_chunk(const float *__restrict__ v, const uint32_t base, const uint32_t n,
                                            const uint32_t thr, uint32_t (&bits)[kRows][4], uint32_t &gtm, uint32_t &eqm) {
     const int tid = threadIdx.x;
     gtm = 0; eqm = 0;
 #pragma unroll
     for (int r = 0; r < kRows; ++r) {
-        const uint32_t e0 = base + r * kRowElems + tid * 4;
+        const uint32_t e0 = base + r * (THREADS * 4) + tid * 4;
         f4 vv = {0.f, 0.f, 0.f, 0.f};
         if (VEC && e0 + 3 < n) vv = *(const f4 *)(v + e0);
         else { for (int j = 0; j < 4; ++j) if (e0 + j < n) vv[j] = v[e0 + j]; }
@@ -779,20 +782,20 @@ __device__ __forceinline__ void load_chunk(const float *__restrict__ v, const ui
     }
 }
 
-// Phase 1 (before the node's barrier): the block's counts of "greater" and "equal" over its run, stored as
-// totals[blockIdx.x] = greater << 32 | equal.  Phase 2 (after it): the counts of the blocks before this one
-// place the run in the output; the run is then written chunk by chunk with a running offset.  Nothing
-// waits for anything: the barrier between the phases is the only exchange.
-template <bool VEC>
+// count_run: the counts of "greater" and "equal" over run number `run` of the node, stored as
+// totals[run] = greater << 32 | equal.  emit_run (once all runs are counted): the counts of the runs before
+// this one place the run in the output; the run is then written chunk by chunk with a running offset.
+template <bool VEC, int THREADS>
 __device__ __forceinline__ void count_run(const SelArgs &a, const int node, const uint32_t thr,
-                                          const uint32_t c_lo, const uint32_t c_hi) {
-    __shared__ uint32_t sh_cnt[2][kWaves];
+                                          const uint32_t c_lo, const uint32_t c_hi, const uint32_t run) {
+    constexpr int W = THREADS / 64;
+    __shared__ uint32_t sh_cnt[2][W];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *v = a.v + (size_t)node * a.stride;
     uint32_t g = 0, e = 0;
     for (uint32_t chunk = c_lo; chunk < c_hi; ++chunk) {
         uint32_t bits[kRows][4], gtm, eqm;
-        load_chunk<VEC>(v, chunk * (uint32_t)kChunk, a.n, thr, bits, gtm, eqm);
+        load_chunk<VEC, THREADS>(v, chunk * (uint32_t)(16 * THREADS), a.n, thr, bits, gtm, eqm);
         g += (uint32_t)__popc(gtm); e += (uint32_t)__popc(eqm);
     }
     g = wave_sum(g); e = wave_sum(e);
@@ -800,26 +803,29 @@ __device__ __forceinline__ void count_run(const SelArgs &a, const int node, cons
     __syncthreads();
     if (tid == 0) {
         uint32_t bg = 0, be = 0;
-        for (int w = 0; w < kWaves; ++w) { bg += sh_cnt[0][w]; be += sh_cnt[1][w]; }
-        st_agent(&a.status_exact[(size_t)node * a.status_exact_stride + blockIdx.x], ((unsigned long long)bg << 32) | be);
+        for (int w = 0; w < W; ++w) { bg += sh_cnt[0][w]; be += sh_cnt[1][w]; }
+        st_agent(&a.status_exact[(size_t)node * a.status_exact_stride + run], ((unsigned long long)bg << 32) | be);
     }
 }
 
-template <bool VEC>
+template <bool VEC, int THREADS>
 __device__ __forceinline__ void emit_run(const SelArgs &a, const int node, const uint32_t thr, const uint32_t quota,
-                                         const uint32_t c_lo, const uint32_t c_hi, const uint32_t nchunks) {
-    __shared__ uint32_t sh_gt[kRows][kWaves], sh_eq[kRows][kWaves];
-    __shared__ uint32_t sh_pre[2][kWaves];
+                                         const uint32_t c_lo, const uint32_t c_hi, const uint32_t nchunks,
+                                         const uint32_t run) {
+    constexpr int W = THREADS / 64;
+    __shared__ uint32_t sh_gt[kRows][W], sh_eq[kRows][W];
+    __shared__ uint32_t sh_pre[2][W];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t off = (size_t)node * a.stride;
     float *u = a.u ? a.u + off : nullptr;
     float *v = a.v + off;
     uint32_t *oidx = a.out_idx + (size_t)node * a.k;
     float *oval = a.out_vals + (size_t)node * a.k;
-    // selected-or-tied elements of the blocks before this one (their totals were stored before the barrier)
+    // selected-or-tied elements of the runs before this one (their totals are complete)
     const unsigned long long *totals = a.status_exact + (size_t)node * a.status_exact_stride;
     uint32_t pg = 0, pe = 0;
-    for (uint32_t b = tid; b < blockIdx.x; b += kBlock) {
+    __syncthreads();   // a block that emits several runs: the previous run's readers of sh_pre are done
+    for (uint32_t b = tid; b < run; b += THREADS) {
         const unsigned long long t = ld_agent(&totals[b]);
         pg += (uint32_t)(t >> 32); pe += (uint32_t)t;
     }
@@ -828,12 +834,12 @@ __device__ __forceinline__ void emit_run(const SelArgs &a, const int node, const
     __syncthreads();
     uint32_t pre_gt = 0, pre_eq = 0;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) { pre_gt += sh_pre[0][w]; pre_eq += sh_pre[1][w]; }
+    for (int w = 0; w < W; ++w) { pre_gt += sh_pre[0][w]; pre_eq += sh_pre[1][w]; }
 
     for (uint32_t chunk = c_lo; chunk < c_hi; ++chunk) {   // c_lo, c_hi: the same for the whole block
-        const uint32_t base = chunk * (uint32_t)kChunk;
+        const uint32_t base = chunk * (uint32_t)(16 * THREADS);
         uint32_t bits[kRows][4], gtm, eqm;
-        load_chunk<VEC>(v, base, a.n, thr, bits, gtm, eqm);
+        load_chunk<VEC, THREADS>(v, base, a.n, thr, bits, gtm, eqm);
         // position of my flagged elements inside the chunk, in index order (row, wave, lane, j)
         uint32_t lane_gt[kRows], lane_eq[kRows];
         __syncthreads();   // the previous chunk's readers of sh_gt / sh_eq are done
@@ -855,7 +861,7 @@ __device__ __forceinline__ void emit_run(const SelArgs &a, const int node, const
 #pragma unroll
         for (int r = 0; r < kRows; ++r) {
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
+            for (int w = 0; w < W; ++w) {
                 if (w == wave) { off_gt[r] = blk_gt; off_eq[r] = blk_eq; }
                 blk_gt += sh_gt[r][w]; blk_eq += sh_eq[r][w];
             }
@@ -869,7 +875,7 @@ __device__ __forceinline__ void emit_run(const SelArgs &a, const int node, const
             for (int r = 0; r < kRows; ++r) {
                 uint32_t cg = pre_gt + off_gt[r] + lane_gt[r];
                 uint32_t ce = pre_eq + off_eq[r] + lane_eq[r];
-                const uint32_t e0 = base + r * kRowElems + tid * 4;
+                const uint32_t e0 = base + r * (THREADS * 4) + tid * 4;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const bool fg = (gtm >> (r * 4 + j)) & 1u, fe = (eqm >> (r * 4 + j)) & 1u;
@@ -1022,63 +1028,33 @@ void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hip
     hipLaunchKernelGGL(k_emit_scanned, dim3(chunks, batch), dim3(1024), 0, st, a);
 }
 
-// ------------------------------------------------------------------ exact path: one persistent kernel
-
-// Barrier over the blocks of one node.  All of them are resident (the host sizes the grid by
-// the kernel's occupancy), so the wait ends; it is bounded all the same, and a failure of any
-// wait in the library ends every other wait within a few polls.
-__device__ __forceinline__ bool node_barrier(const SelArgs &a, Ctr *s, uint32_t &epoch) {
-    __shared__ uint32_t sh_ok;
-    // Release: every wavefront waits until its own stores and atomics have been acknowledged (a wait, no
-    // cache operation), the block barrier collects them, and ONE thread then issues the device-scope fence
-    // (the write-back of this XCD's L2) before it arrives.  A fence by every thread is the same guarantee at
-    // an L2 write-back request per wavefront: about 20 us per barrier with 256 blocks of 4 wavefronts.
-    // Acquire: none.  Everything that crosses blocks after a barrier (the summed histograms, the blocks'
-    // counts) is read with device-scope atomic loads, which do not go through the non-coherent caches, and
-    // an invalidation of the L2 would only make the next pass over v miss it.
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): all of this wavefront's loads, stores and atomics are done
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        epoch += gridDim.x;
-        atomicAdd(&s->barrier, 1u);
-        uint32_t spins = 0, ok = 1;
-        while (ld_agent32(&s->barrier) < epoch) {
-            if (++spins > a.spin_limit) { atomicAdd(&a.stats->errors, 1u); ok = 0; break; }
-            if ((spins & 255u) == 0 && ld_agent32(&a.stats->errors) != 0) { ok = 0; break; }
-            __builtin_amdgcn_s_sleep(8);
-        }
-        sh_ok = ok;
-    }
-    __syncthreads();
-    return __builtin_amdgcn_readfirstlane(sh_ok) != 0;   // wave-uniform for the compiler: callers branch on it
-}
+// ------------------------------------------------------------------ exact path
 
 // Radix select of the exact k-th largest key over all of v (digits of 11, 10 and 10 bits: each
-// pass histograms one digit of the keys that match the digits fixed so far, all blocks then
-// fix the next digit from the summed histogram), followed by the ordered output compaction
-// of v with that key.  Runs for the nodes the fast path handed back, or for all when forced.
+// pass histograms one digit of the keys that match the digits fixed so far, the next digit is then
+// fixed from the histogram), followed by the ordered output compaction of v with that key.
+// Three forms:
+//  * k_exact_block: ONE block per node does all of it (three passes over the node's v with an LDS
+//    histogram, then the ordered output): short vectors.
+//  * k_exact: one launch of several blocks per node that share the phases out through tickets: the
+//    fall-back of the fast path (it exits at once for the nodes the fast path served, which is nearly
+//    always: the launch then costs little more than an empty one).
+//  * k_exact_step: the same phases as five launches of many blocks, for exact selection chosen
+//    outright on long vectors; the kernel boundaries are the only exchange between blocks.
 
-// One pass over v of this block's share: the histogram of digit `pass` among the keys whose higher digits
-// equal `prefix`, counted in LDS and added to the node's histogram of that pass.
-template <bool VEC>
-__device__ __forceinline__ void radix_count(const SelArgs &a, const int node, const int pass, const uint32_t prefix,
-                                            uint32_t *hist /*[kRadixBins]*/) {
-    const int tid = threadIdx.x;
-    const float *v = a.v + (size_t)node * a.stride;
-    const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock;
-    const int nb = pass == 0 ? kRadixBins : 1024;
-    uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
-    for (int i = tid; i < nb; i += kBlock) hist[i] = 0;
-    __syncthreads();
+// counts digit `pass` of the keys whose higher digits equal `prefix` into hist (LDS), this block's share of v
+template <bool VEC, int THREADS>
+__device__ __forceinline__ void radix_tally(const float *__restrict__ v, const uint32_t n, const uint32_t first,
+                                            const uint32_t nthreads, const int pass, const uint32_t prefix,
+                                            uint32_t *hist) {
     auto count = [&](uint32_t key) {
         if (pass == 0) atomicAdd(&hist[key >> 20], 1u);
         else if (pass == 1) { if ((key >> 20) == prefix) atomicAdd(&hist[(key >> 10) & 1023u], 1u); }
         else { if ((key >> 10) == prefix) atomicAdd(&hist[key & 1023u], 1u); }
     };
     if (VEC) {
-        const uint32_t n4 = a.n >> 2;
-        for (uint32_t i = gtid; i < n4; i += 4 * nthreads) {   // four 16-byte loads in flight per thread
+        const uint32_t n4 = n >> 2;
+        for (uint32_t i = first; i < n4; i += 4 * nthreads) {   // four 16-byte loads in flight per thread
             f4 vv[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -1092,23 +1068,31 @@ __device__ __forceinline__ void radix_count(const SelArgs &a, const int node, co
                 }
             }
         }
-        for (uint32_t i = (n4 << 2) + gtid; i < a.n; i += nthreads) count(key_of(v[i]));
+        for (uint32_t i = (n4 << 2) + first; i < n; i += nthreads) count(key_of(v[i]));
     } else {
-        for (uint32_t i = gtid; i < a.n; i += nthreads) count(key_of(v[i]));
+        for (uint32_t i = first; i < n; i += nthreads) count(key_of(v[i]));
     }
+}
+
+// One pass over share `run` of `nruns` of the node's v: the histogram of digit `pass` among the keys whose
+// higher digits equal `prefix`, counted in LDS and added to the node's histogram of that pass.
+template <bool VEC>
+__device__ __forceinline__ void radix_count(const SelArgs &a, const int node, const int pass, const uint32_t prefix,
+                                            uint32_t *hist /*[kRadixBins]*/, const uint32_t run, const uint32_t nruns) {
+    const int tid = threadIdx.x;
+    const int nb = pass == 0 ? kRadixBins : 1024;
+    uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
+    for (int i = tid; i < nb; i += kBlock) hist[i] = 0;
+    __syncthreads();
+    radix_tally<VEC, kBlock>(a.v + (size_t)node * a.stride, a.n, run * kBlock + tid, nruns * kBlock, pass, prefix, hist);
     __syncthreads();
     for (int i = tid; i < nb; i += kBlock) { const uint32_t h = hist[i]; if (h) atomicAdd(&gh[i], h); }
 }
 
-// Once every block's counts of `pass` are in the node's histogram: the digit that holds the rank-th largest
-// key, appended to prefix; rank becomes the rank inside that digit's keys.  Block-wide, the same in all blocks.
-__device__ __forceinline__ void radix_fix(const SelArgs &a, const int node, const int pass, uint32_t *hist,
-                                          uint32_t *wave_tmp, uint32_t *res, uint32_t &prefix, uint32_t &rank) {
-    const int tid = threadIdx.x;
-    const int nb = pass == 0 ? kRadixBins : 1024;
-    const uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
-    for (int i = tid; i < kRadixBins; i += kBlock) hist[i] = i < nb ? ld_agent32(&gh[i]) : 0u;
-    __syncthreads();
+// From a finished histogram of `pass` in LDS: the digit that holds the rank-th largest key, appended to prefix;
+// rank becomes the rank inside that digit's keys.  Block-wide.
+__device__ __forceinline__ void radix_digit(const int pass, const uint32_t *hist, uint32_t *wave_tmp, uint32_t *res,
+                                            uint32_t &prefix, uint32_t &rank) {
     if (pass == 0) find_rank_bin<kRadixBins>(hist, rank, wave_tmp, res);
     else find_rank_bin<1024>(hist, rank, wave_tmp, res);
     const uint32_t digit = res[0] == 0xffffffffu ? 0u : res[0];
@@ -1117,49 +1101,135 @@ __device__ __forceinline__ void radix_fix(const SelArgs &a, const int node, cons
     __syncthreads();
 }
 
-// this block's run of chunks in the ordered output: block b owns the chunks [b * per, (b + 1) * per) of the node
-__device__ __forceinline__ void block_run(const SelArgs &a, uint32_t &c_lo, uint32_t &c_hi, uint32_t &nchunks) {
+// Once every block's counts of `pass` are in the node's histogram (the launch before): fix the next digit.
+__device__ __forceinline__ void radix_fix(const SelArgs &a, const int node, const int pass, uint32_t *hist,
+                                          uint32_t *wave_tmp, uint32_t *res, uint32_t &prefix, uint32_t &rank) {
+    const int tid = threadIdx.x;
+    const int nb = pass == 0 ? kRadixBins : 1024;
+    const uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
+    for (int i = tid; i < kRadixBins; i += kBlock) hist[i] = i < nb ? ld_agent32(&gh[i]) : 0u;
+    __syncthreads();
+    radix_digit(pass, hist, wave_tmp, res, prefix, rank);
+}
+
+// run number `run` of `nruns` in the ordered output: the chunks [run * per, (run + 1) * per) of the node
+__device__ __forceinline__ void block_run(const SelArgs &a, const uint32_t run, const uint32_t nruns, uint32_t &c_lo,
+                                          uint32_t &c_hi, uint32_t &nchunks) {
     nchunks = (a.n + kChunk - 1) / kChunk;
-    const uint32_t per = (nchunks + gridDim.x - 1) / gridDim.x;
-    c_lo = blockIdx.x * per < nchunks ? blockIdx.x * per : nchunks;
+    const uint32_t per = (nchunks + nruns - 1) / nruns;
+    c_lo = run * per < nchunks ? run * per : nchunks;
     c_hi = c_lo + per < nchunks ? c_lo + per : nchunks;
 }
 
-// The whole path in one kernel whose blocks meet at node-wide barriers: all of them must be resident.
+// One block of 1024 threads per node (grid (1, nodes)), everything in that block.
+template <bool VEC>
+__global__ __launch_bounds__(1024) void k_exact_block(SelArgs a) {
+    __shared__ uint32_t hist[kRadixBins];
+    __shared__ uint32_t wave_tmp[16], res[2];
+    const int node = blockIdx.y, tid = threadIdx.x;
+    Sel *s = a.sel + node;
+    if (!a.force && s->fast_ok) return;   // the same for the whole block
+    if (a.force) {   // no sampling kernel ran in this call: the next call's state set is cleared here
+        for (uint32_t i = blockIdx.y * 1024u + tid; i < a.next_words; i += gridDim.y * 1024u) a.next_state[i] = 0;
+    }
+    const float *v = a.v + (size_t)node * a.stride;
+    uint32_t prefix = 0, rank = a.k;
+    for (int pass = 0; pass < 3; ++pass) {
+        for (int i = tid; i < kRadixBins; i += 1024) hist[i] = 0;
+        __syncthreads();
+        radix_tally<VEC, 1024>(v, a.n, tid, 1024u, pass, prefix, hist);
+        __syncthreads();
+        radix_digit(pass, hist, wave_tmp, res, prefix, rank);
+    }
+    // prefix is now the full key T*; rank the number of ties to take
+    if (tid == 0) { s->thr = prefix; s->quota = rank; }
+    const uint32_t nchunks = (a.n + 16383u) / 16384u;
+    emit_run<VEC, 1024>(a, node, prefix, rank, 0u, nchunks, nchunks, 0u);
+}
+
+// The same phases in one launch of several blocks per node, for the fast path's fall-back on long vectors (it
+// exits at once for the nodes the fast path served).  The shares of the five phases (three radix passes,
+// count, output; R shares each) are handed out through a ticket counter, phase by phase, to whichever blocks
+// are running; a block that draws a share of phase p first waits until the R shares of phase p - 1 are
+// complete.  Every share it waits for was drawn before its own, hence by a block that is running and that
+// waits, in turn, only for shares drawn still earlier: the waits end whatever number of the kernel's blocks
+// the device holds at a time, and whatever else runs beside them (there is no condition on residency; one
+// block alone would work through all the shares).  The waits are bounded all the same: an expired wait is
+// counted as a device error (lgc_stats) and ends every other wait within a few polls.
+__device__ __forceinline__ bool phase_wait(const SelArgs &a, const Ctr *c, const int phase, const uint32_t shares) {
+    __shared__ uint32_t sh_ok;
+    if (threadIdx.x == 0) {
+        uint32_t spins = 0, ok = 1;
+        while (ld_agent32(&c->done[phase]) < shares) {
+            if (++spins > a.spin_limit) { atomicAdd(&a.stats->errors, 1u); ok = 0; break; }
+            if ((spins & 255u) == 0 && ld_agent32(&a.stats->errors) != 0) { ok = 0; break; }
+            __builtin_amdgcn_s_sleep(8);
+        }
+        sh_ok = ok;
+    }
+    __syncthreads();
+    return __builtin_amdgcn_readfirstlane(sh_ok) != 0;   // wave-uniform for the compiler: callers branch on it
+}
+
+// Completion of a share.  Every wavefront waits until its own stores and atomics have been acknowledged (a
+// wait, no cache operation), the block barrier collects them, and ONE thread issues the device-scope release
+// (the write-back of this XCD's L2) before it counts the share.  No acquire on the other side: everything that
+// crosses blocks (the summed histograms, the runs' counts) is read with device-scope atomic loads, which do
+// not go through the non-coherent caches.
+__device__ __forceinline__ void phase_done(Ctr *c, const int phase) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        atomicAdd(&c->done[phase], 1u);
+    }
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
     __shared__ uint32_t hist[kRadixBins];
-    __shared__ uint32_t wave_tmp[kWaves], res[2];
+    __shared__ uint32_t wave_tmp[kWaves], res[2], sh_ticket;
     const int node = blockIdx.y, tid = threadIdx.x;
     Sel *s = a.sel + node;
     if (!a.force && s->fast_ok) return;
-    const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock;
-    uint32_t epoch = 0, prefix = 0, rank = a.k;
     if (a.force) {   // no sampling kernel ran in this call: the next call's state set is cleared here
-        const uint32_t all = gridDim.y * nthreads;
+        const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock, all = gridDim.y * nthreads;
         for (uint32_t i = blockIdx.y * nthreads + gtid; i < a.next_words; i += all) a.next_state[i] = 0;
     }
-    for (int pass = 0; pass < 3; ++pass) {
-        radix_count<VEC>(a, node, pass, prefix, hist);
-        if (!node_barrier(a, a.ctr + node, epoch)) return;   // a wait expired somewhere: give up, lgc_stats reports it
-        radix_fix(a, node, pass, hist, wave_tmp, res, prefix, rank);
+    Ctr *c = a.ctr + node;
+    const uint32_t shares = gridDim.x;   // per phase: as many as the node has blocks (each draws one per phase if all run)
+    uint32_t prefix = 0, rank = a.k;
+    int fixed = 0;                       // digits of T* this block has worked out so far
+    for (;;) {
+        __syncthreads();                 // the previous round's readers of sh_ticket are done
+        if (tid == 0) sh_ticket = atomicAdd(&c->ticket, 1u);
+        __syncthreads();
+        const uint32_t t = __builtin_amdgcn_readfirstlane(sh_ticket);
+        if (t >= 5u * shares) break;
+        const int phase = (int)(t / shares);
+        const uint32_t run = t % shares;
+        if (phase > 0 && !phase_wait(a, c, phase - 1, shares)) return;   // a wait expired somewhere: give up, lgc_stats reports it
+        for (; fixed < (phase < 3 ? phase : 3); ++fixed) radix_fix(a, node, fixed, hist, wave_tmp, res, prefix, rank);
+        if (phase < 3) {
+            radix_count<VEC>(a, node, phase, prefix, hist, run, shares);
+        } else {
+            uint32_t c_lo, c_hi, nchunks;
+            block_run(a, run, shares, c_lo, c_hi, nchunks);
+            if (phase == 3) {
+                if (run == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }   // prefix is the full key T*, rank the ties to take
+                count_run<VEC, kBlock>(a, node, prefix, c_lo, c_hi, run);
+            } else {
+                emit_run<VEC, kBlock>(a, node, prefix, rank, c_lo, c_hi, nchunks, run);
+            }
+        }
+        phase_done(c, phase);
     }
-    // prefix is now the full key T*; rank the number of ties to take
-    if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }
-    uint32_t c_lo, c_hi, nchunks;
-    block_run(a, c_lo, c_hi, nchunks);
-    count_run<VEC>(a, node, prefix, c_lo, c_hi);
-    if (!node_barrier(a, a.ctr + node, epoch)) return;
-    emit_run<VEC>(a, node, prefix, rank, c_lo, c_hi, nchunks);
 }
 
-// The same path as five launches, for forced exact selection of long vectors: the kernel boundaries take the
-// place of the barriers, so the blocks need not be resident together (several contexts may run it at the same
-// time, whatever else the device is doing) and their number is chosen for the passes over v alone.  From 2^20
-// elements per call on this form is also the faster one (selection alone, one kernel with barriers against
-// five launches: 2^19 34 / 36 us, 2^20 51 / 39 us, 2^24 181 / 109 us, 4 x 2^24 374 / 256 us, 4 x 2^26 1225 / 987 us).  step 0..2: the radix pass of that digit (the digits before it are
-// fixed again from their finished histograms: a few microseconds, no exchange); step 3: T*, the tie quota and
-// the counts of every block's run; step 4: the ordered output.
+// Five launches: step 0..2: the radix pass of that digit (the digits before it are fixed again from their
+// finished histograms: a few microseconds, no exchange); step 3: T*, the tie quota and the counts of every
+// block's run; step 4: the ordered output.  The blocks need not be resident together, and their number is
+// chosen for the passes over v alone.
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_exact_step(SelArgs a, int step) {
     __shared__ uint32_t hist[kRadixBins];
@@ -1171,37 +1241,30 @@ __global__ __launch_bounds__(kBlock) void k_exact_step(SelArgs a, int step) {
         for (uint32_t i = blockIdx.y * nthreads + gtid; i < a.next_words; i += all) a.next_state[i] = 0;
     }
     uint32_t c_lo, c_hi, nchunks;
-    block_run(a, c_lo, c_hi, nchunks);
+    block_run(a, blockIdx.x, gridDim.x, c_lo, c_hi, nchunks);
     if (step == 4) {
-        emit_run<VEC>(a, node, s->thr, s->quota, c_lo, c_hi, nchunks);
+        emit_run<VEC, kBlock>(a, node, s->thr, s->quota, c_lo, c_hi, nchunks, blockIdx.x);
         return;
     }
     uint32_t prefix = 0, rank = a.k;
     for (int pass = 0; pass < (step < 3 ? step : 3); ++pass) radix_fix(a, node, pass, hist, wave_tmp, res, prefix, rank);
     if (step < 3) {
-        radix_count<VEC>(a, node, step, prefix, hist);
+        radix_count<VEC>(a, node, step, prefix, hist, blockIdx.x, gridDim.x);
         return;
     }
     if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }
-    count_run<VEC>(a, node, prefix, c_lo, c_hi);
+    count_run<VEC, kBlock>(a, node, prefix, c_lo, c_hi, blockIdx.x);
 }
 
 constexpr uint64_t kStepMinElems = 1ull << 20;   // forced exact selection of this many elements (all nodes) and more: five launches
+constexpr uint32_t kBlockMaxElems = 1u << 15;    // vectors up to this length: one block per node does everything
 
 void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st) {
-    // The kernel with barriers needs all its blocks on the device at the same time: at most one block per
-    // compute unit, shared by the nodes (the device holds three of this kernel per unit, so several such
-    // kernels fit side by side).  Every block more makes the four barriers dearer (an L2 write-back per block
-    // and barrier), every block less the five passes over v slower.  It serves the fast path's fall-back (one
-    // launch that nearly always has nothing to do) and short forced calls.
-    uint32_t per_node = (uint32_t)(cus / batch);
     const uint32_t chunks = (a.n + kChunk - 1) / kChunk;
-    if (per_node > chunks) per_node = chunks;
-    if (per_node < 1) per_node = 1;
     if (a.force && (uint64_t)a.n * batch >= kStepMinElems) {
-        // five launches, no barriers, no need to be resident together: about four blocks per compute unit in
-        // all (fewer make a block's share of a pass long, more make the histogram flushes dear)
-        per_node = (uint32_t)(4 * cus / batch);
+        // five launches: about four blocks per compute unit in all (fewer make a block's share of a pass long,
+        // more make the histogram flushes dear)
+        uint32_t per_node = (uint32_t)(4 * cus / batch);
         if (per_node > chunks) per_node = chunks;
         if (per_node < 1) per_node = 1;
         dim3 grid2(per_node, batch);
@@ -1211,6 +1274,16 @@ void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st
         }
         return;
     }
+    if (a.n <= kBlockMaxElems) {
+        if (vec) hipLaunchKernelGGL(k_exact_block<true>, dim3(1, batch), dim3(1024), 0, st, a);
+        else hipLaunchKernelGGL(k_exact_block<false>, dim3(1, batch), dim3(1024), 0, st, a);
+        return;
+    }
+    // one launch, about one block per compute unit shared by the nodes: each block more makes the phase
+    // changes dearer (a device-scope release per share), each block less the five passes over v slower
+    uint32_t per_node = (uint32_t)(cus / batch);
+    if (per_node > chunks) per_node = chunks;
+    if (per_node < 1) per_node = 1;
     dim3 grid(per_node, batch);
     if (vec) hipLaunchKernelGGL(k_exact<true>, grid, dim3(kBlock), 0, st, a);
     else hipLaunchKernelGGL(k_exact<false>, grid, dim3(kBlock), 0, st, a);

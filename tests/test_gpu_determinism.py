@@ -92,7 +92,7 @@ def test_resume_from_saved_residuals(B, selection):
 @pytest.mark.parametrize("force_exact,n", [(False, 1_500_000), (True, 1_500_000), (True, 6_000_000)])
 def test_two_contexts_on_two_streams(B, force_exact, n):
     """Two contexts, each on a stream of its own, run their iterations at the same time on the one GPU (the
-    exact path's kernels of both share the compute units: one kernel with barriers each at the shorter
+    exact path's kernels of both share the compute units: one launch that hands out its work through tickets each at the shorter
     length, five launches each at the longer): each gives what it gives alone."""
     w = synth.workload(2, n=n, nodes=2)
     K, n, k = w.nodes, w.n, w.k
@@ -133,4 +133,40 @@ def test_two_contexts_on_two_streams(B, force_exact, n):
         assert B.lgc_stats(ctxs[c])[2] == 0
         for key in alone[c]:
             assert bits_equal(together[c][key], alone[c][key]), (c, key)
+        ctxs[c].close()
+
+
+def test_six_contexts_falling_back_at_the_same_time(B, oracle):
+    """Six contexts on six streams whose selections all fall back to the exact path on the device at the same
+    time (every magnitude of node 0 equal: the candidate list overflows), more such kernels than the device
+    holds side by side.  The fall-back hands its work out through tickets to whichever of its blocks are
+    running, so it needs no particular number of them on the device: every context must give the oracle's
+    result, with no device-side error."""
+    n, k, K = 3_000_000, 3000, 2
+    rng = np.random.default_rng(6)
+    v0 = np.empty((K, n), np.float32)
+    v0[0] = 0.25
+    v0[0, ::3] = -0.25
+    v0[1] = rng.standard_normal(n)
+    ref = []
+    for b in range(K):
+        vb = v0[b].copy()
+        vals, idx = oracle.topk(vb, None, k)
+        ref.append((vals, idx, vb))
+    ctxs = [B.Context(n, k, K) for _ in range(6)]
+    streams = [torch.cuda.Stream() for _ in range(6)]
+    vs = [torch.from_numpy(v0).cuda() for _ in range(6)]
+    outs = [(torch.zeros((K, k), device="cuda"), torch.zeros((K, k), device="cuda", dtype=torch.int32)) for _ in range(6)]
+    torch.cuda.synchronize()
+    for c in range(6):
+        with torch.cuda.stream(streams[c]):
+            B.lgc_topk(ctxs[c], vs[c], None, k, outs[c][0], outs[c][1])
+    torch.cuda.synchronize()
+    for c in range(6):
+        assert B.lgc_stats(ctxs[c]) == (1, 1, 0), c          # node 1 by the fast path, node 0 fell back, no error
+        for b in range(K):
+            vals, idx, vb = ref[b]
+            assert (outs[c][1][b].cpu().numpy().astype(np.uint32) == idx).all(), (c, b)
+            assert bits_equal(outs[c][0][b], torch.from_numpy(vals).cuda()), (c, b)
+            assert bits_equal(vs[c][b], torch.from_numpy(vb).cuda()), (c, b)
         ctxs[c].close()
