@@ -22,9 +22,28 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 ALGO_BYTES_PER_ELEM = 20       # read g,u,v + write u,v, fp32: what accumulate+select must move
-# HBM bytes per launch of the streaming kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a
-# plain copy of known size (profiles/k_candidates_resnet50_hbm_traffic.md); known for workload 2 only
-MEASURED_TRAFFIC = {2: 2.0614e9}
+
+
+def measured_traffic(cfg, ratio_index, selection, pattern):
+    """HBM bytes per launch of the streaming kernel as counted by rocprofv3 (FETCH_SIZE and WRITE_SIZE passes, each
+    scaled by a plain copy of known size), from profiles/hbm_traffic.json.  The file names the sources the counted
+    kernel was built from (their sha256); the figure is reported only while those sources are unchanged: None
+    (printed as null) means "not counted for this workload, or the kernel changed since it was counted"."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        table = json.load(open(path))
+        digest = hashlib.sha256()
+        for rel in table["kernel_sources"]:
+            digest.update(open(os.path.join(ROOT, rel), "rb").read())
+        if digest.hexdigest() != table["kernel_sources_sha256"]:
+            return None, "the streaming kernel's sources changed since the counters were read"
+        for e in table["entries"]:
+            if (e["workload"], e["ratio_index"], e["selection"], e["pattern"]) == (cfg, ratio_index, selection, pattern):
+                return e["bytes_per_launch"], f"{e['source']} (counted at commit {table['commit']})"
+    except (OSError, KeyError, ValueError):
+        pass
+    return None, "not counted for this workload"
 
 
 def parse():
@@ -113,15 +132,15 @@ def ae_report(enc, dec, k, dec_batch, enc_batch, stages, which):
     return {"shape": which, "encode_mac_per_node": enc_mac, "decode_mac_per_node": dec_mac,
             "encode_TFLOPs": enc_tf, "decode_TFLOPs": dec_tf, "bound": "mfma", "peak": peak, "unit": "TFLOP/s",
             "encode_frac": enc_tf / peak, "decode_frac": dec_tf / peak,
-            "note": "fp32 in, fp32 accumulate; meaningful for --ae paper (the two-layer stacks are launch-latency bound)"}
+            "note": "fp32 in, fp32 accumulate: the roofline is the fp32 MFMA peak"}
 
 
 def plain_kernel_rates():
-    """Runs the stand-alone program built beside the library (csrc/hbm_rates.hip): the rates of a
+    """Runs the stand-alone program built from hbm_rates.hip beside this file: the rates of a
     plain read, a plain copy and a plain 3-reads-2-writes kernel on arrays of the ResNet50-sized
     workload, and of the runtime's device-to-device copy.  None if it is not built or fails."""
     import subprocess
-    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2103_08870_amd", "hbm_rates")
+    exe = os.path.join(ROOT, "hbm_rates")
     if not os.path.exists(exe):
         return None
     try:
@@ -188,6 +207,7 @@ def main():
     ew, eb, dw, db = synth.ae_weights(enc, dec, device="cuda")
     ae = B.Autoencoder(enc, dec, ew, eb, dw, db, slope=slope)
     ctx = B.Context(n, k, K)
+    B.lgc_reserve(ctx, ae, k, K, seg)     # all the scratch the step needs exists before the first call
 
     grads = [synth.gradients(w, t, device="cuda", k_for_ties=(k,)) for t in range(sets)]
     u = torch.zeros((K, n), device="cuda")
@@ -299,8 +319,10 @@ def main():
         stages["innovation"] = timed(lambda t: B.lgc_innovation(ctx, inv_seg, vals, innov))
     B.lgc_stats(ctx)
     torch.cuda.synchronize()
+    ratio_index = args.ratio_index % len(w.ks)
+    traffic, traffic_source = measured_traffic(w.cfg, ratio_index, args.selection, args.pattern)
     roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
-                "traffic": MEASURED_TRAFFIC.get(w.cfg) if args.ratio_index in (-1, len(w.ks) - 1) and seg is None else None, "kernel": f"lgc::k_candidates<true, true, {'false' if seg is None else 'true'}> (fused accumulate + candidate bitmap, all nodes in one launch)",
+                "traffic": traffic, "traffic_source": traffic_source, "kernel": f"lgc::k_candidates<true, true, {'false' if seg is None else 'true'}> (fused accumulate + candidate bitmap, all nodes in one launch)",
                 "algorithmic_bytes_per_launch": ALGO_BYTES_PER_ELEM * K * n}
     if kern_launches:
         # ps: one streaming launch per step covers all K nodes; rar: the selecting node's launch and
@@ -311,7 +333,7 @@ def main():
                         launches=kern_launches)
         if args.pattern == "rar":
             roofline.update(kernel="lgc::k_candidates<true, true, false> (selecting node) + lgc::k_accumulate<true> "
-                                   "(other nodes): the streaming launches of one step", traffic=None)
+                                   "(other nodes): the streaming launches of one step")
 
     if plain is not None:
         roofline["plain_kernels"] = plain
@@ -345,9 +367,10 @@ def main():
                                  "ms_median_of_5": reps[2], "ms_min_of_5": reps[0],
                                  "note": "same buffers, measured after the timed region"},
         "stages_ms": {name: round(ms, 5) for name, ms in stages.items()},
-        "autoencoder": ae_report(enc, dec, k, 1 if args.pattern == "rar" else K, K, stages, args.ae),
         "roofline": roofline,
     }
+    if args.ae == "paper":   # only the Table I / II shapes are contractions worth a matrix-core roofline
+        out["autoencoder"] = ae_report(enc, dec, k, 1 if args.pattern == "rar" else K, K, stages, args.ae)
 
     if not args.no_cpu_baseline:
         host_w = [[t.cpu().numpy() for t in xs] for xs in (ew, eb, dw, db)]

@@ -34,9 +34,10 @@
  *    of what the device holds, so several of them fit side by side; its waits
  *    are bounded all the same (an expired wait gives invalid outputs, a
  *    non-zero error count in lgc_stats and LGC_EDEVICE, never a hang).
- *  - The calls can be recorded into a HIP graph (stream capture) once the
- *    context's scratch has grown to its size (one warm-up call of each kind):
- *    they allocate nothing then, never synchronise and use no memset.  The
+ *  - No call between lgc_create / lgc_reserve and lgc_destroy allocates or
+ *    frees device memory or synchronises (lgc_stats and lgc_profile_read, which
+ *    read back, aside), and none uses a memset: the calls can be recorded into
+ *    a HIP graph (stream capture).  The
  *    selection calls alternate between two sets of scratch state from call
  *    to call, so a graph that is replayed must hold an EVEN number of
  *    selection calls (lgc_topk, lgc_accumulate_topk and their per-layer forms)
@@ -176,8 +177,9 @@ uint64_t lgc_latent_len(const lgc_ae *ae, uint64_t k);
 /* a3. Encoder g^c = E_c(g~) (Sec. IV, Table I).  vals: [batch][k];
  * latent: [batch][C_latent][L_latent] (channel-major per node).
  * fp32 arithmetic with fp32 accumulation.  k == 0 is a no-op.
- * The first call with a larger (k, batch, autoencoder) than seen before grows
- * the context's activation scratch (one device allocation). */
+ * Stacks other than two kernel-3 / stride-2 layers of up to 16 channels keep
+ * their intermediate tensors in the context's activation scratch, which must
+ * have been reserved (lgc_reserve); the call itself never allocates. */
 lgc_status lgc_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, uint64_t k, int batch,
                       float *latent, void *stream);
 
@@ -227,8 +229,8 @@ uint64_t lgc_segments_total_k(const lgc_segments *seg); /* sum of ks: outputs pe
  *                     then segment 1's, ... — ascending overall
  *   out_vals[b*K ..)  v at those positions, bit-exact
  * then v <- +0 and (unless u is NULL) u <- +0 there.  n is the plan's n; it and
- * K must fit the context (max_n, max_k).  The first call with a plan grows the
- * context's scratch (device allocation); later calls allocate nothing.
+ * K must fit the context (max_n, max_k).  The scratch for the plan must have
+ * been reserved (lgc_reserve); the call itself never allocates.
  */
 lgc_status lgc_topk_segmented(lgc_ctx *ctx, const lgc_segments *seg, float *v, float *u /* nullable */,
                               int batch, uint64_t stride, float *out_vals, uint32_t *out_idx, void *stream);
@@ -298,6 +300,25 @@ lgc_status lgc_accumulate_gather(lgc_ctx *ctx, const float *g, float *u, float *
  */
 lgc_status lgc_average(lgc_ctx *ctx, const float *x, uint64_t len, int batch, float scale, float *out,
                        void *stream);
+
+/* ---- reservation ---- */
+
+/*
+ * Reserves, ahead of the hot path, the scratch that lgc_create cannot size:
+ *   ae  (nullable): the activation buffers lgc_encode / lgc_decode /
+ *        lgc_decode_innovation need with this autoencoder for inputs of up to
+ *        k values per node and up to `batch` nodes (the largest intermediate
+ *        tensor of either stack, twice; nothing for stacks that run as one
+ *        launch);
+ *   seg (nullable): the per-layer thresholds and the candidate list of
+ *        lgc_topk_segmented / lgc_accumulate_topk_segmented with this plan.
+ * A later reservation only ever grows the buffers, so one call per
+ * autoencoder and plan in use covers them all.  May allocate and, when it
+ * replaces a smaller buffer, synchronises the device first.  Without the
+ * reservation the calls named above return LGC_EINVAL and say so.
+ */
+lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k, int batch,
+                       const lgc_segments *seg /* nullable */);
 
 /* ---- diagnostics (never needed on the hot path) ---- */
 

@@ -23,7 +23,7 @@ EXPORTS = [
     "lgc_create", "lgc_destroy", "lgc_last_error", "lgc_status_string",
     "lgc_accumulate", "lgc_topk", "lgc_accumulate_topk", "lgc_accumulate_topk_static",
     "lgc_ae_create", "lgc_ae_destroy", "lgc_latent_len", "lgc_encode", "lgc_decode",
-    "lgc_scatter", "lgc_set_option", "lgc_stats", "lgc_profile_read",
+    "lgc_scatter", "lgc_reserve", "lgc_set_option", "lgc_stats", "lgc_profile_read",
     "lgc_gather", "lgc_accumulate_gather", "lgc_average",
     "lgc_segments_create", "lgc_segments_destroy", "lgc_segments_total_k",
     "lgc_topk_segmented", "lgc_accumulate_topk_segmented",
@@ -103,6 +103,8 @@ def lib() -> C.CDLL:
     l.lgc_innovation.restype = i32
     l.lgc_decode_innovation.argtypes = [vp, vp, vp, vp, u64, i32, vp, vp]
     l.lgc_decode_innovation.restype = i32
+    l.lgc_reserve.argtypes = [vp, vp, u64, i32, vp]
+    l.lgc_reserve.restype = i32
     l.lgc_set_option.argtypes = [vp, i32, C.c_int64]
     l.lgc_set_option.restype = i32
     l.lgc_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]
@@ -363,6 +365,13 @@ def lgc_average(ctx: Context, x: torch.Tensor, scale: float, out: torch.Tensor) 
     _require(x.dim() == 2 and x.is_contiguous() and out.is_contiguous() and out.numel() == x.shape[1], "x.dim() == 2 and x.is_contiguous() and out.is_contiguous() and out.numel() == x.shape[1]")
     _check(lib().lgc_average(ctx.h, _ptr(x, torch.float32), x.shape[1], x.shape[0], scale,
                              _ptr(out, torch.float32), _stream()), ctx.h)
+
+
+def lgc_reserve(ctx: Context, ae: Optional[Autoencoder] = None, k: int = 0, batch: int = 1,
+                seg: Optional[Segments] = None) -> None:
+    """Reserves the context's activation scratch for (ae, k, batch) and / or the per-layer scratch for seg."""
+    _check(lib().lgc_reserve(ctx.h, ae.h if ae is not None else None, k, batch,
+                             seg.h if seg is not None else None), ctx.h)
 
 
 def lgc_set_option(ctx: Context, opt: int, value: int) -> None:

@@ -1,5 +1,6 @@
-"""Builds liblgc.so (HIP, gfx950) in-tree next to this file, and the stand-alone program hbm_rates
-(streaming rates of plain kernels, for comparison; bench.py runs it when it is there)."""
+"""Builds liblgc.so (HIP, gfx950) in-tree next to this file.  Also builds, when it can, the stand-alone
+measurement program hbm_rates beside bench.py at the repository root (streaming rates of plain kernels, for
+comparison; bench.py runs it when it is there); the library does not depend on it."""
 from __future__ import annotations
 
 import os
@@ -10,7 +11,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblgc.so")
-HBM_RATES = os.path.join(HERE, "hbm_rates")
+ROOT = os.path.dirname(HERE)
+HBM_RATES = os.path.join(ROOT, "hbm_rates")
 SOURCES = ["api.hip", "topk.hip", "segmented.hip", "autoencoder.hip", "ae_mfma.hip"]
 HEADERS = [os.path.join(CSRC, "lgc_internal.h"), os.path.join(CSRC, "device_helpers.h"),
            os.path.join(os.path.dirname(HERE), "include", "lgc.h")]
@@ -51,12 +53,15 @@ def build(force: bool = True, verbose: bool = False) -> str:
         return obj
 
     def build_probe():
-        cmd = [hipcc] + [f for f in FLAGS if f != "-fPIC"] + [os.path.join(CSRC, "hbm_rates.hip"), "-o", HBM_RATES]
+        src = os.path.join(ROOT, "hbm_rates.hip")
+        if not os.path.exists(src):
+            return
+        cmd = [hipcc] + [f for f in FLAGS if f != "-fPIC"] + [src, "-o", HBM_RATES]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if verbose or r.returncode != 0:
             sys.stderr.write(" ".join(cmd) + "\n" + r.stdout + r.stderr)
-        if r.returncode != 0:
-            raise RuntimeError("hipcc failed on hbm_rates.hip")
+        if r.returncode != 0:   # the measurement program is optional: the library build goes on without it
+            sys.stderr.write("warning: hbm_rates.hip did not build; bench.py will leave out the plain-kernel rates\n")
 
     with ThreadPoolExecutor(max_workers=len(srcs) + 1) as ex:
         probe = ex.submit(build_probe)

@@ -7,6 +7,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -663,9 +664,29 @@ extern "C" uint64_t lgc_latent_len(const lgc_ae *ae, uint64_t k) {
     return len * (uint64_t)ae->enc.back().c_out;
 }
 
+// floats per activation buffer that encoder and decoder need for inputs of k values and `batch` nodes (the
+// largest intermediate tensor of either stack)
+static size_t act_need(const lgc_ae *ae, uint64_t k, int batch) {
+    size_t need = 0;
+    uint64_t len = k;
+    for (size_t l = 0; l < ae->enc.size(); ++l) {
+        len = conv_len(len, ae->enc[l]);
+        if (l + 1 < ae->enc.size()) need = std::max(need, (size_t)batch * ae->enc[l].c_out * (size_t)len);
+    }
+    const std::vector<uint64_t> out_len = dec_lengths(ae, k);
+    for (size_t l = 0; l + 1 < ae->dec.size(); ++l)
+        need = std::max(need, (size_t)batch * ae->dec[l].c_out * (size_t)out_len[l]);
+    return need;
+}
+
+// only from lgc_reserve: the hot-path calls never allocate
 static lgc_status ensure_act(lgc_ctx *ctx, size_t floats) {
     if (floats <= ctx->act_floats) return LGC_OK;
-    if (ctx->act[0]) { HIP_TRY(ctx, hipFree(ctx->act[0])); ctx->act[0] = ctx->act[1] = nullptr; ctx->act_floats = 0; }
+    if (ctx->act[0]) {
+        HIP_TRY(ctx, hipDeviceSynchronize());
+        HIP_TRY(ctx, hipFree(ctx->act[0]));
+        ctx->act[0] = ctx->act[1] = nullptr; ctx->act_floats = 0;
+    }
     floats = align_up(floats, 64);
     HIP_TRY(ctx, hipMalloc((void **)&ctx->act[0], 2 * floats * 4));
     ctx->act[1] = ctx->act[0] + floats;
@@ -705,7 +726,9 @@ static lgc_status run_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, 
         size_t f = (size_t)batch * ae->enc[l].c_out * len[l + 1];
         if (f > need) need = f;
     }
-    if ((s = ensure_act(ctx, need)) != LGC_OK) return s;
+    if (need > ctx->act_floats)
+        return fail(ctx, LGC_EINVAL, "lgc_encode: activation scratch for k = %llu, batch = %d not reserved: call "
+                                     "lgc_reserve(ctx, ae, k, batch, NULL) once beforehand", (unsigned long long)k, batch);
     const float *cur = vals;
     // a layer never writes the buffer it reads: the activation buffer that is not `cur`
     auto other = [&](const float *c) { return c == ctx->act[0] ? ctx->act[1] : ctx->act[0]; };
@@ -778,7 +801,9 @@ static lgc_status run_decode(lgc_ctx *ctx, const lgc_ae *ae, const float *latent
         size_t f = (size_t)batch * ae->dec[l].c_out * out_len[l];
         if (f > need) need = f;
     }
-    if ((s = ensure_act(ctx, need)) != LGC_OK) return s;
+    if (need > ctx->act_floats)
+        return fail(ctx, LGC_EINVAL, "lgc_decode: activation scratch for k = %llu, batch = %d not reserved: call "
+                                     "lgc_reserve(ctx, ae, k, batch, NULL) once beforehand", (unsigned long long)k, batch);
     const float *cur = latent;
     // a layer never writes the buffer it reads: the activation buffer that is not `cur`
     auto other = [&](const float *c) { return c == ctx->act[0] ? ctx->act[1] : ctx->act[0]; };
@@ -972,6 +997,12 @@ extern "C" void lgc_segments_destroy(lgc_segments *seg) {
 
 extern "C" uint64_t lgc_segments_total_k(const lgc_segments *seg) { return seg ? seg->total_k : 0; }
 
+static bool seg_scratch_fits(const lgc_ctx *ctx, const lgc_segments *seg) {
+    return (size_t)ctx->max_batch * seg->n_seg <= ctx->seg_t_words && ctx->seg_row_prefix &&
+           2 * (size_t)ctx->max_batch * seg->cap <= ctx->seg_cand_words;
+}
+
+// only from lgc_reserve: the hot-path calls never allocate
 static lgc_status ensure_seg_scratch(lgc_ctx *ctx, const lgc_segments *seg) {
     const size_t t_words = (size_t)ctx->max_batch * seg->n_seg;
     if (t_words > ctx->seg_t_words) {
@@ -1010,7 +1041,9 @@ static lgc_status run_segmented(lgc_ctx *ctx, const lgc_segments *seg, const flo
         if (fused) launch_accumulate(g, u, v, (uint32_t)seg->n, batch, stride, m, vec, st);
         return LGC_OK;
     }
-    if ((s = ensure_seg_scratch(ctx, seg)) != LGC_OK) return s;
+    if (!seg_scratch_fits(ctx, seg))
+        return fail(ctx, LGC_EINVAL, "per-layer selection: scratch for this segment plan not reserved: call "
+                                     "lgc_reserve(ctx, NULL, 0, 0, seg) once beforehand");
     SelArgs a = make_args(ctx, g, u, v, seg->n, stride, m, seg->total_k, out_vals, out_idx);
     a.n_seg = seg->n_seg; a.seg_off = seg->off; a.seg_k = seg->k; a.seg_out = seg->out; a.seg_rank = seg->rank;
     a.row_seg = seg->row_seg; a.seg_t = ctx->seg_t; a.row_prefix = ctx->seg_row_prefix;
@@ -1101,6 +1134,29 @@ extern "C" lgc_status lgc_average(lgc_ctx *ctx, const float *x, uint64_t len, in
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
     return LGC_OK;
+}
+
+// ------------------------------------------------------------------ reservation
+
+extern "C" lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae, uint64_t k, int batch, const lgc_segments *seg) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    if (ae) {
+        if (ae->device != ctx->device) return fail(ctx, LGC_EINVAL, "autoencoder and context live on different devices");
+        if (batch < 1 || batch > ctx->max_batch) return fail(ctx, LGC_EINVAL, "batch = %d outside [1, %d]", batch, ctx->max_batch);
+        if (k > ctx->max_k) return fail(ctx, LGC_EINVAL, "k exceeds the context's max_k");
+    }
+    if (seg) {
+        if (seg->device != ctx->device) return fail(ctx, LGC_EINVAL, "segment plan and context live on different devices");
+        if (seg->n > ctx->max_n || seg->total_k > ctx->max_k) return fail(ctx, LGC_EINVAL, "segment plan exceeds the context's max_n / max_k");
+    }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    return no_throw(ctx, [&]() -> lgc_status {
+        lgc_status s = LGC_OK;
+        if (ae && k > 0 && (s = ensure_act(ctx, act_need(ae, k, batch))) != LGC_OK) return s;
+        if (seg && (s = ensure_seg_scratch(ctx, seg)) != LGC_OK) return s;
+        return LGC_OK;
+    });
 }
 
 // ------------------------------------------------------------------ diagnostics

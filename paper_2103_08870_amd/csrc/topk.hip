@@ -352,24 +352,24 @@ void launch_candidates(const SelArgs &args, int batch, bool fused, bool vec, hip
 
 // ------------------------------------------------------------------ gather of the candidates
 
-__device__ __forceinline__ uint32_t block_sum_1024(uint32_t x, uint32_t *tmp /*[16]*/) {
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_sum(uint32_t x, uint32_t *tmp /*[16]*/) {
     x = wave_sum(x);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) tmp[threadIdx.x >> 6] = x;
     __syncthreads();
     uint32_t t = 0;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) t += tmp[w];
+    for (int w = 0; w < THREADS / 64; ++w) t += tmp[w];
     return t;
 }
 
-// kGatherRows bitmap rows per block of 1024 threads.  Lists the candidates of its rows, in index
+// ROWS bitmap rows per block of THREADS threads.  Lists the candidates of its rows, in index
 // order, behind those of all earlier rows of the node: position, and value re-read from v.
 // Counts them in the fine histogram of d = key - t_est (bins of 2^12, last bin open-ended) and
 // adds the block's count to the node's total.  The block's part of the bitmap is staged in LDS;
 // the work is balanced over the threads by output position (binary search of the owning row,
 // then of the bit inside the row), whatever the spread of the candidates.
-constexpr int kGatherRows = 128;
 // Long vectors (a.supers != 0): the candidates of every kSuperRows rows are summed by a kernel of their own, so
 // that a gather block adds up at most kSuperRows row counts (and a few sums) to find its place
 // instead of all the counts before it, which at 2^28 elements was most of the gather's time.
@@ -386,12 +386,15 @@ __global__ __launch_bounds__(1024) void k_row_sums(SelArgs a) {
         if (i0 + 3 < nrows) { const u4 x = *(const u4 *)(cnt + i0); part += x[0] + x[1] + x[2] + x[3]; }
         else for (uint32_t i = i0; i < nrows; ++i) part += cnt[i];
     }
-    const uint32_t total = block_sum_1024(part, tmp);
+    const uint32_t total = block_sum<1024>(part, tmp);
     if (threadIdx.x == 0) a.row_super[(size_t)blockIdx.y * a.supers + blockIdx.x] = total;
 }
 
-template <bool HIST>
-__global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
+template <bool HIST, int ROWS, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_gather(SelArgs a) {
+    constexpr int kGatherRows = ROWS;
+    constexpr int kPairs = (ROWS * kRowWords / 2 + THREADS - 1) / THREADS;   // pairs of bitmap words per thread
+    static_assert(ROWS % 64 == 0 && ROWS <= THREADS && (ROWS & (ROWS - 1)) == 0, "rows per block");
     __shared__ uint32_t hist[HIST ? kFineBins : 1];
     __shared__ unsigned long long rows_lds[kGatherRows * kRowWords];
     __shared__ uint32_t offs[kGatherRows];
@@ -408,10 +411,10 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
 
     // all independent loads first: my row's count, my slice of the bitmap, the counts before the block
     const uint32_t c = (uint32_t)tid < mine ? cnt[first + tid] : 0u;
-    ulonglong2 bm[kGatherRows * kRowWords / 2 / 1024];
+    ulonglong2 bm[kPairs];
 #pragma unroll
-    for (int q = 0; q < (int)(kGatherRows * kRowWords / 2 / 1024); ++q) {
-        const uint32_t w2 = q * 1024 + tid;   // pair of words
+    for (int q = 0; q < kPairs; ++q) {
+        const uint32_t w2 = q * THREADS + tid;   // pair of words
         bm[q] = (w2 * 2 < mine * kRowWords) ? *(const ulonglong2 *)(bitmap + (size_t)w2 * 2) : ulonglong2{0ull, 0ull};
     }
     const uint32_t t_est = HIST ? s->t_est : 0u;
@@ -419,20 +422,22 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
     // vector has more than one group), then the rows of the block's own group
     const uint32_t group = a.supers ? first / kSuperRows : 0u;
     uint32_t part = (uint32_t)tid < group ? a.row_super[(size_t)node * a.supers + tid] : 0u;
-    for (uint32_t i0 = group * kSuperRows + tid * 4; i0 < first; i0 += 4096 * 4) {   // first and the row stride are multiples of 4
+    for (uint32_t i0 = group * kSuperRows + tid * 4; i0 < first; i0 += 4 * THREADS * 4) {   // first and the row stride are multiples of 4
         u4 x[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) x[r] = (i0 + r * 4096 < first) ? *(const u4 *)(cnt + i0 + r * 4096) : (u4){0u, 0u, 0u, 0u};
+        for (int r = 0; r < 4; ++r) x[r] = (i0 + r * 4 * THREADS < first) ? *(const u4 *)(cnt + i0 + r * 4 * THREADS) : (u4){0u, 0u, 0u, 0u};
 #pragma unroll
         for (int r = 0; r < 4; ++r) part += x[r][0] + x[r][1] + x[r][2] + x[r][3];
     }
 #pragma unroll
-    for (int q = 0; q < (int)(kGatherRows * kRowWords / 2 / 1024); ++q) {
-        rows_lds[(q * 1024 + tid) * 2] = bm[q].x;
-        rows_lds[(q * 1024 + tid) * 2 + 1] = bm[q].y;
+    for (int q = 0; q < kPairs; ++q) {
+        if ((q * THREADS + tid) * 2 < kGatherRows * kRowWords) {
+            rows_lds[(q * THREADS + tid) * 2] = bm[q].x;
+            rows_lds[(q * THREADS + tid) * 2 + 1] = bm[q].y;
+        }
     }
-    if (HIST) for (int i = tid; i < kFineBins; i += 1024) hist[i] = 0;
-    const uint32_t before = block_sum_1024(part, tmp);   // contains barriers: LDS is filled for all
+    if (HIST) for (int i = tid; i < kFineBins; i += THREADS) hist[i] = 0;
+    const uint32_t before = block_sum<THREADS>(part, tmp);   // contains barriers: LDS is filled for all
     // exclusive scan of c over the first kGatherRows threads
     uint32_t incl = c;
 #pragma unroll
@@ -452,7 +457,7 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
     if (tid == 0 && block_total) atomicAdd(&s->cand_total, block_total);
     __syncthreads();
 
-    for (uint32_t p = tid; p < block_total; p += 1024) {
+    for (uint32_t p = tid; p < block_total; p += THREADS) {
         // last row r with offs[r] <= p: it is the one that holds output position p
         uint32_t r = 0;
 #pragma unroll
@@ -498,13 +503,20 @@ __global__ __launch_bounds__(1024) void k_gather(SelArgs a) {
     if (HIST) {
         __syncthreads();
         uint32_t *fine = a.fine_hist + node * kFineBins;
-        for (int i = tid; i < kFineBins; i += 1024) { const uint32_t h = hist[i]; if (h) atomicAdd(&fine[i], h); }
+        for (int i = tid; i < kFineBins; i += THREADS) { const uint32_t h = hist[i]; if (h) atomicAdd(&fine[i], h); }
     }
+}
+
+template <int ROWS, int THREADS>
+static void launch_gather_shape(const SelArgs &g, uint32_t nrows, int batch, hipStream_t st) {
+    const dim3 grid((nrows + ROWS - 1) / ROWS, batch);
+    // the per-layer selection has one threshold per segment, so no histogram above "the" estimate
+    if (g.seg_t) hipLaunchKernelGGL((k_gather<false, ROWS, THREADS>), grid, dim3(THREADS), 0, st, g);
+    else hipLaunchKernelGGL((k_gather<true, ROWS, THREADS>), grid, dim3(THREADS), 0, st, g);
 }
 
 void launch_gather(const SelArgs &a, int batch, hipStream_t st) {
     const uint32_t nrows = (a.n + kRow - 1) / kRow;
-    const dim3 grid((nrows + kGatherRows - 1) / kGatherRows, batch);
     // the sums per group pay for their launch from about 32 K rows on (measured: at 25 K rows the gather
     // gains 0.5 us from them, at 256 K rows 17 us)
     SelArgs g = a;
@@ -512,9 +524,10 @@ void launch_gather(const SelArgs &a, int batch, hipStream_t st) {
         hipLaunchKernelGGL(k_row_sums, dim3((nrows + kSuperRows - 1) / kSuperRows, batch), dim3(1024), 0, st, g);
     else
         g.supers = 0;
-    // the per-layer selection has one threshold per segment, so no histogram above "the" estimate
-    if (a.seg_t) hipLaunchKernelGGL(k_gather<false>, grid, dim3(1024), 0, st, g);
-    else hipLaunchKernelGGL(k_gather<true>, grid, dim3(1024), 0, st, g);
+    // 128 rows per block of 1024 threads; measured on the ResNet50-sized workload (4 nodes): 64 rows x 512
+    // threads 18.0 us, 64 x 1024 20.2, 128 x 512 19.8, 64 x 256 21.5, this shape 18.2 (the same within noise:
+    // what the kernel costs is its chain of dependent memory round trips, not the search work of its busiest block)
+    launch_gather_shape<128, 1024>(g, nrows, batch, st);
 }
 
 // Adds, for every candidate i < total that passes `member`, one count to hist[digit(d)], where

@@ -55,6 +55,7 @@ def test_null_context_is_rejected_without_touching_a_device(lib):
     assert lib.lgc_innovation(None, None, None, 1, None, None) == binding.LGC_EINVAL
     assert lib.lgc_decode_innovation(None, None, None, None, 1, 1, None, None) == binding.LGC_EINVAL
     assert lib.lgc_segments_total_k(None) == 0
+    assert lib.lgc_reserve(None, None, 0, 1, None) == binding.LGC_EINVAL
     h = C.c_void_p()
     assert lib.lgc_segments_create(C.byref(h), 0, 10, 1, None, None) == binding.LGC_EINVAL and not h.value
 

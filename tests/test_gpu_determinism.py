@@ -27,6 +27,8 @@ def one_run(B, w, iters, selection, ae_pack, state=None, first=0, force_exact=Fa
     if force_exact:
         B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 1)
     seg = B.Segments(off, ks) if selection == "layers" else None
+    if seg is not None:
+        B.lgc_reserve(ctx, seg=seg)
     u = torch.zeros((K, n), device="cuda") if state is None else state[0].clone()
     v = torch.zeros((K, n), device="cuda") if state is None else state[1].clone()
     outs = []

@@ -57,6 +57,7 @@ def make_innovation_ae(B, channels, slope=0.0):
 def test_decode_with_innovation(B, oracle, channels, k, batch, slope):
     ae, enc, dec, (ew, eb, dw, db) = make_innovation_ae(B, channels, slope)
     ctx = B.Context(1 << 20, 1 << 20, 4)
+    B.lgc_reserve(ctx, ae, k, batch)
     rng = np.random.default_rng(k)
     lat_len = B.lgc_latent_len(ae, k)
     latent = rng.standard_normal((batch, lat_len)).astype(np.float32)
@@ -90,6 +91,7 @@ def test_parameter_server_iteration_per_layer(B, oracle):
     seg = B.Segments(off, ks)
     inv_seg = B.Segments(out_off.tolist(), inv_ks)
     ae, enc, dec, (ew, eb, dw, db) = make_innovation_ae(B, w.ae_channels)
+    B.lgc_reserve(ctx, ae, mu, K, seg)
     u = np.zeros((K, n), np.float32); v = np.zeros((K, n), np.float32)
     du, dv = dev(u), dev(v)
     vals = torch.zeros((K, mu), device="cuda"); idx = torch.zeros((K, mu), device="cuda", dtype=torch.int32)

@@ -400,7 +400,7 @@ def make_ae(B, channels=None, paper=False, slope=0.0):
                                               ((1, 8, 4), 2, 3), ((1, 8, 4), 1027, 8)])
 def test_encode_decode(B, oracle, channels, k, batch):
     ae, enc, dec, (ew, eb, dw, db) = make_ae(B, channels)
-    ctx = B.Context(max(k, 16), max(k, 16), batch)
+    ctx = B.Context(max(k, 16), max(k, 16), batch)    # (these two-layer stacks run as one launch: nothing to reserve)
     rng = np.random.default_rng(k)
     x = rng.laplace(0, 1e-2, (batch, k)).astype(np.float32)
     lat_len = B.lgc_latent_len(ae, k)
@@ -429,6 +429,7 @@ def test_paper_size_autoencoder(B, oracle, k, batch):
     # short ragged inputs, the benchmark's k, and 8 nodes x 44 500 values (the oracle is run on three of them)
     ae, enc, dec, (ew, eb, dw, db) = make_ae(B, paper=True, slope=0.01)
     ctx = B.Context(1 << 16, 1 << 16, batch)
+    B.lgc_reserve(ctx, ae, k, batch)
     x = np.random.default_rng(0).laplace(0, 1e-2, (batch, k)).astype(np.float32)
     lat = torch.zeros((batch, B.lgc_latent_len(ae, k)), device="cuda")
     rec = torch.zeros((batch, k), device="cuda")
@@ -467,6 +468,7 @@ def test_autoencoder_of_other_shapes(B, oracle, stack, k):
     ae = B.Autoencoder(enc, dec, ew, eb, dw, db, slope=0.05)
     hw = [[t.cpu().numpy() for t in xs] for xs in (ew, eb, dw, db)]
     ctx = B.Context(1 << 16, 1 << 16, 3)
+    B.lgc_reserve(ctx, ae, k, 3)
     x = np.random.default_rng(k).laplace(0, 1e-2, (3, k)).astype(np.float32)
     lat = torch.zeros((3, B.lgc_latent_len(ae, k)), device="cuda")
     rec = torch.zeros((3, k), device="cuda")
@@ -657,7 +659,24 @@ def test_argument_errors_on_device(B):
                          torch.zeros((3, 100), device="cuda"), 0.9)
     B.lgc_topk(ctx, v, None, 0, ov[:0], oi[:0])          # k == 0 is valid
     assert B.lgc_stats(ctx) == (0, 0, 0)
-    ctx.close()
+    # the hot-path calls never allocate: scratch that lgc_create cannot size must have been reserved
+    ae, enc, dec, _ = make_ae(B, paper=True)
+    x, lat = torch.zeros((2, 10), device="cuda"), torch.zeros((2, B.lgc_latent_len(ae, 10)), device="cuda")
+    with pytest.raises(B.LgcError) as e:
+        B.lgc_encode(ctx, ae, x, lat)
+    assert e.value.status == B.LGC_EINVAL and "lgc_reserve" in str(e.value)
+    with pytest.raises(B.LgcError):
+        B.lgc_reserve(ctx, ae, 11, 2)                    # beyond the context's max_k
+    B.lgc_reserve(ctx, ae, 10, 2)
+    B.lgc_encode(ctx, ae, x, lat)
+    seg = B.Segments([0, 600, 1000], [3, 3])
+    with pytest.raises(B.LgcError) as e:
+        B.lgc_topk_segmented(ctx, seg, v, None, torch.zeros(6, device="cuda"), torch.zeros(6, device="cuda", dtype=torch.int32))
+    assert "lgc_reserve" in str(e.value)
+    B.lgc_reserve(ctx, seg=seg)
+    B.lgc_topk_segmented(ctx, seg, v, None, torch.zeros(6, device="cuda"), torch.zeros(6, device="cuda", dtype=torch.int32))
+    assert B.lgc_stats(ctx)[2] == 0
+    seg.close(); ae.close(); ctx.close()
 
 
 # ------------------------------------------------------------------------------ full benchmark sizes

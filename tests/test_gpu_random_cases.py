@@ -123,6 +123,7 @@ def case_seg(B, O, rng, desc):
     total = sum(ks)
     ctx = B.Context(n, max(total, 1), batch)
     seg = B.Segments(off, ks)
+    B.lgc_reserve(ctx, seg=seg)
     u = values(rng, (batch, n), 0) * np.float32(1e-3); v = values(rng, (batch, n), kind)
     du, dv = torch.from_numpy(u.copy()).cuda(), torch.from_numpy(v.copy()).cuda()
     for it in range(iters):
@@ -206,6 +207,7 @@ def case_ae(B, O, rng, desc):
     ae = B.Autoencoder(enc, dec, ew, eb, dw, db, slope=slope)
     hw = [[t.cpu().numpy() for t in xs] for xs in (ew, eb, dw, db)]
     ctx = B.Context(1 << 16, 1 << 16, batch)
+    B.lgc_reserve(ctx, ae, k, batch)
     x = rng.laplace(0, 1e-2, (batch, k)).astype(np.float32)
     lat = torch.zeros((batch, B.lgc_latent_len(ae, k)), device="cuda")
     B.lgc_encode(ctx, ae, torch.from_numpy(x).cuda(), lat)
@@ -289,6 +291,7 @@ def case_reuse(B, O, rng, desc):
                 ks[int(np.argmax(ks))] //= 2
             total = sum(ks)
             seg = B.Segments(off, ks)
+            B.lgc_reserve(ctx, seg=seg)
             ovals = torch.full((batch, total), 7.0, device="cuda"); oidx = torch.full((batch, total), -1, device="cuda", dtype=torch.int32)
             B.lgc_accumulate_topk_segmented(ctx, seg, dg, du, dv, 0.9, ovals, oidx)
             seg.close()

@@ -67,6 +67,7 @@ def test_small_segments_selected_from_v(B, oracle, n, n_seg, batch, pad):
     ks[0] = min(1, lens[0]); ks[-1] = lens[-1] if lens[-1] < 3000 else 7       # k_l = 1, k_l = n_l
     ctx = B.Context(n, max(int(ks.sum()), 1), batch)
     seg = B.Segments(off.tolist(), ks.tolist())
+    B.lgc_reserve(ctx, seg=seg)
     assert seg.total_k == int(ks.sum())
     for trial in range(2):
         if trial == 0:
@@ -100,6 +101,7 @@ def test_mixed_segments(B, oracle, fused, aligned_base):
     rng = np.random.default_rng(11 + fused)
     ctx = B.Context(n + 1, int(ks.sum()), batch)
     seg = B.Segments(off.tolist(), ks.tolist())
+    B.lgc_reserve(ctx, seg=seg)
     scale = np.repeat(np.exp(rng.uniform(np.log(1e-5), np.log(1e-2), len(ks))), np.diff(off)).astype(np.float32)
     v0 = (rng.laplace(0, 1, (batch, n)) * scale).astype(np.float32)
     u0 = (rng.standard_normal((batch, n)) * scale).astype(np.float32)
@@ -139,6 +141,7 @@ def test_candidate_overflow_falls_back_to_v(B, oracle):
     v0[0, off[1]:off[2]:3] = -0.5
     ctx = B.Context(n, int(ks.sum()), 1)
     seg = B.Segments(off.tolist(), ks.tolist())
+    B.lgc_reserve(ctx, seg=seg)
     assert run_segmented(B, oracle, ctx, seg, off, ks, v0, None) == (0, 4)
     seg.close(); ctx.close()
 
@@ -149,6 +152,7 @@ def test_fused_equals_accumulate_then_segmented(B):
     K = sum(ks)
     ctx = B.Context(w.n, K, w.nodes)
     seg = B.Segments(off, ks)
+    B.lgc_reserve(ctx, seg=seg)
     g = synth.gradients(w, 0, device="cuda")
     u1 = torch.randn((w.nodes, w.n), device="cuda") * 1e-4
     v1 = torch.randn((w.nodes, w.n), device="cuda") * 1e-4
@@ -171,6 +175,7 @@ def test_workload_iterations(B, oracle, cfg, n):
     off, ks = synth.layer_plan(w)
     ctx = B.Context(n, sum(ks), w.nodes)
     seg = B.Segments(off, ks)
+    B.lgc_reserve(ctx, seg=seg)
     u = np.zeros((w.nodes, n), np.float32); v = np.zeros((w.nodes, n), np.float32)
     for t in range(3):
         g = synth.gradients(w, t, device="cpu").numpy()
@@ -190,6 +195,7 @@ def test_full_size_resnet50_layers(B, oracle):
     sampled = sum(1 for a, b in zip(off, off[1:]) if b - a >= 16_384)
     ctx = B.Context(w.n, K, w.nodes)
     seg = B.Segments(off, ks)
+    B.lgc_reserve(ctx, seg=seg)
     u = torch.zeros((w.nodes, w.n), device="cuda"); v = torch.zeros((w.nodes, w.n), device="cuda")
     vals = torch.zeros((w.nodes, K), device="cuda"); idx = torch.zeros((w.nodes, K), device="cuda", dtype=torch.int32)
     hu = np.zeros((2, w.n), np.float32); hv = np.zeros((2, w.n), np.float32)
@@ -233,6 +239,7 @@ def test_adversarial_layouts_per_layer(B, oracle):
     ks = np.maximum(1, lens // 60)
     ctx = B.Context(n, int(ks.sum()), 1)
     seg = B.Segments(off.tolist(), ks.tolist())
+    B.lgc_reserve(ctx, seg=seg)
     u0 = rng.standard_normal((1, n)).astype(np.float32)
     for name, v in adversarial_inputs(n, int(ks.sum()), rng):
         run_segmented(B, oracle, ctx, seg, off, ks, v[None, :].copy(), u0)
