@@ -13,7 +13,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblgc.so")
 ROOT = os.path.dirname(HERE)
 HBM_RATES = os.path.join(ROOT, "hbm_rates")
-SOURCES = ["api.hip", "topk.hip", "segmented.hip", "autoencoder.hip", "ae_mfma.hip"]
+SOURCES = ["api.hip", "streaming.hip", "topk.hip", "segmented.hip", "autoencoder.hip", "ae_mfma.hip"]
 HEADERS = [os.path.join(CSRC, "lgc_internal.h"), os.path.join(CSRC, "device_helpers.h"),
            os.path.join(os.path.dirname(HERE), "include", "lgc.h")]
 
