@@ -329,8 +329,10 @@ def main():
         # the other nodes' launches together cover them, so the bytes are counted per step
         per_step_ms = kern_ms / args.steps
         ach = ALGO_BYTES_PER_ELEM * K * n / (per_step_ms * 1e-3) / 1e9
+        # large workloads stream in several launches per step (shares of about 2 GB): bytes are per launch
         roofline.update(achieved=ach, frac=ach / HBM_PEAK_GBS, kernel_avg_ms=kern_ms / kern_launches,
-                        launches=kern_launches)
+                        launches=kern_launches,
+                        algorithmic_bytes_per_launch=ALGO_BYTES_PER_ELEM * K * n * args.steps // kern_launches)
         if args.pattern == "rar":
             roofline.update(kernel="lgc::k_candidates<true, true, false> (selecting node) + lgc::k_accumulate<true> "
                                    "(other nodes): the streaming launches of one step")
