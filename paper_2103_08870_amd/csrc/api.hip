@@ -294,19 +294,20 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
         launch_candidates(a, batch, fused, vec, st);
         profile_end(ctx, st);
         launch_gather(a, batch, st);
-        launch_output_from_candidates(a, batch, expected_candidates((double)n, (double)k) <= 131072.0, st);
         a.force = 0;
+        // the exact path as fall-back, for nodes the fast path hands back: with short candidate lists it rides in
+        // the output launch, otherwise one launch of its own that nearly always has nothing to do
+        if (!launch_output_from_candidates(a, batch, expected_candidates((double)n, (double)k) <= 131072.0, vec, ctx->cus, st))
+            launch_exact(a, batch, vec, ctx->cus, st);
     } else {
         if (fused) {
             profile_begin(ctx, st);
             launch_accumulate(g, u, v, (uint32_t)n, batch, stride, m, vec, st);
             profile_end(ctx, st);
         }
-        a.force = 1;   // the exact kernel then also clears the next call's state set
+        a.force = 1;   // exact path chosen outright (as five launches when the input is long); it also clears the next call's state set
+        launch_exact(a, batch, vec, ctx->cus, st);
     }
-    // exact path: runs when forced (as five launches when the input is long), otherwise only for nodes the fast
-    // path handed back: one launch of one block per node, which nearly always has nothing to do
-    launch_exact(a, batch, vec, ctx->cus, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ctx, LGC_EHIP, "kernel launch: %s", hipGetErrorString(e));
     return LGC_OK;

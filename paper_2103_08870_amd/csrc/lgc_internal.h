@@ -125,7 +125,7 @@ void launch_clear(uint32_t *words, uint32_t count, hipStream_t st);
 void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
 void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
 void launch_gather(const SelArgs &a, int batch, hipStream_t st);
-void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hipStream_t st);
+bool launch_output_from_candidates(const SelArgs &a, int batch, bool direct, bool vec, int cus, hipStream_t st);
 void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st);
 // per-layer selection (segmented.hip)
 void launch_seg_estimate(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);

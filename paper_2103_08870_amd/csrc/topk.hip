@@ -425,9 +425,9 @@ __global__ __launch_bounds__(1024) void k_select_level2(SelArgs a) {
 // blocks.  Writes the selected elements in index order and zeroes them in v (and u).
 constexpr int kKeep = 16;   // 16-byte key groups per thread held in registers
 
-__global__ __launch_bounds__(1024) void k_output_direct(SelArgs a) {
-    __shared__ uint32_t hist[kFineBins];
-    __shared__ uint32_t wave_tmp[16], res[2], sh_pg[16], sh_pe[16], sh_tg[16], sh_te[16];
+__device__ __forceinline__ void output_direct(const SelArgs &a, uint32_t *hist /*[kFineBins]*/, uint32_t *wave_tmp /*[16]*/,
+                                              uint32_t *res /*[2]*/) {
+    __shared__ uint32_t sh_pg[16], sh_pe[16], sh_tg[16], sh_te[16];
     const int node = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Sel *s = a.sel + node;
     const uint32_t total = s->cand_total;
@@ -662,12 +662,24 @@ __device__ __forceinline__ void emit_run(const SelArgs &a, const int node, const
         }
         __syncthreads();
         uint32_t off_gt[kRows], off_eq[kRows], blk_gt = 0, blk_eq = 0;
+        if constexpr (W <= 4) {
 #pragma unroll
-        for (int r = 0; r < kRows; ++r) {
+            for (int r = 0; r < kRows; ++r) {
 #pragma unroll
-            for (int w = 0; w < W; ++w) {
-                if (w == wave) { off_gt[r] = blk_gt; off_eq[r] = blk_eq; }
-                blk_gt += sh_gt[r][w]; blk_eq += sh_eq[r][w];
+                for (int w = 0; w < W; ++w) {
+                    if (w == wave) { off_gt[r] = blk_gt; off_eq[r] = blk_eq; }
+                    blk_gt += sh_gt[r][w]; blk_eq += sh_eq[r][w];
+                }
+            }
+        } else {
+            // many wavefronts: lane w takes wavefront w's totals and the sums go over the lanes (reading all
+            // kRows x W totals into registers at once is what a block of 16 wavefronts has no room for)
+#pragma unroll 1
+            for (int r = 0; r < kRows; ++r) {
+                const uint32_t tg = lane < W ? sh_gt[r][lane] : 0u, te = lane < W ? sh_eq[r][lane] : 0u;
+                off_gt[r] = blk_gt + wave_sum(lane < wave ? tg : 0u);
+                off_eq[r] = blk_eq + wave_sum(lane < wave ? te : 0u);
+                blk_gt += wave_sum(tg); blk_eq += wave_sum(te);
             }
         }
         if (tid == 0 && chunk == nchunks - 1) {   // the last chunk of the node sees everything: the selection must add up to k
@@ -817,21 +829,6 @@ __global__ __launch_bounds__(1024) void k_emit_scanned(SelArgs a) {
     }
 }
 
-// direct = true: short candidate lists (each block reads the whole list); false: long lists
-// (second-level histogram by many blocks, counts per chunk, output).
-void launch_output_from_candidates(const SelArgs &a, int batch, bool direct, hipStream_t st) {
-    if (direct) {
-        hipLaunchKernelGGL(k_output_direct, dim3((a.cap + 4095) / 4096, batch), dim3(1024), 0, st, a);
-        return;
-    }
-    uint32_t blocks = (a.cap + 16383) / 16384;
-    if (blocks > 256) blocks = 256;
-    hipLaunchKernelGGL(k_select_level2, dim3(blocks, batch), dim3(1024), 0, st, a);
-    const uint32_t chunks = (a.cap + kChunk - 1) / kChunk;
-    hipLaunchKernelGGL(k_count_chunks, dim3((chunks + kCountChunks - 1) / kCountChunks, batch), dim3(1024), 0, st, a);
-    hipLaunchKernelGGL(k_emit_scanned, dim3(chunks, batch), dim3(1024), 0, st, a);
-}
-
 // ------------------------------------------------------------------ exact path
 
 // Radix select of the exact k-th largest key over all of v (digits of 11, 10 and 10 bits: each
@@ -880,17 +877,17 @@ __device__ __forceinline__ void radix_tally(const float *__restrict__ v, const u
 
 // One pass over share `run` of `nruns` of the node's v: the histogram of digit `pass` among the keys whose
 // higher digits equal `prefix`, counted in LDS and added to the node's histogram of that pass.
-template <bool VEC>
+template <bool VEC, int THREADS>
 __device__ __forceinline__ void radix_count(const SelArgs &a, const int node, const int pass, const uint32_t prefix,
                                             uint32_t *hist /*[kRadixBins]*/, const uint32_t run, const uint32_t nruns) {
     const int tid = threadIdx.x;
     const int nb = pass == 0 ? kRadixBins : 1024;
     uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
-    for (int i = tid; i < nb; i += kBlock) hist[i] = 0;
+    for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
     __syncthreads();
-    radix_tally<VEC, kBlock>(a.v + (size_t)node * a.stride, a.n, run * kBlock + tid, nruns * kBlock, pass, prefix, hist);
+    radix_tally<VEC, THREADS>(a.v + (size_t)node * a.stride, a.n, run * THREADS + tid, nruns * THREADS, pass, prefix, hist);
     __syncthreads();
-    for (int i = tid; i < nb; i += kBlock) { const uint32_t h = hist[i]; if (h) atomicAdd(&gh[i], h); }
+    for (int i = tid; i < nb; i += THREADS) { const uint32_t h = hist[i]; if (h) atomicAdd(&gh[i], h); }
 }
 
 // From a finished histogram of `pass` in LDS: the digit that holds the rank-th largest key, appended to prefix;
@@ -906,20 +903,22 @@ __device__ __forceinline__ void radix_digit(const int pass, const uint32_t *hist
 }
 
 // Once every block's counts of `pass` are in the node's histogram (the launch before): fix the next digit.
+template <int THREADS>
 __device__ __forceinline__ void radix_fix(const SelArgs &a, const int node, const int pass, uint32_t *hist,
                                           uint32_t *wave_tmp, uint32_t *res, uint32_t &prefix, uint32_t &rank) {
     const int tid = threadIdx.x;
     const int nb = pass == 0 ? kRadixBins : 1024;
     const uint32_t *gh = a.radix_hist + (node * 3 + pass) * kRadixBins;
-    for (int i = tid; i < kRadixBins; i += kBlock) hist[i] = i < nb ? ld_agent32(&gh[i]) : 0u;
+    for (int i = tid; i < kRadixBins; i += THREADS) hist[i] = i < nb ? ld_agent32(&gh[i]) : 0u;
     __syncthreads();
     radix_digit(pass, hist, wave_tmp, res, prefix, rank);
 }
 
 // run number `run` of `nruns` in the ordered output: the chunks [run * per, (run + 1) * per) of the node
+template <int THREADS>
 __device__ __forceinline__ void block_run(const SelArgs &a, const uint32_t run, const uint32_t nruns, uint32_t &c_lo,
                                           uint32_t &c_hi, uint32_t &nchunks) {
-    nchunks = (a.n + kChunk - 1) / kChunk;
+    nchunks = (a.n + 16u * THREADS - 1) / (16u * THREADS);   // a chunk: 16 elements per thread
     const uint32_t per = (nchunks + nruns - 1) / nruns;
     c_lo = run * per < nchunks ? run * per : nchunks;
     c_hi = c_lo + per < nchunks ? c_lo + per : nchunks;
@@ -989,19 +988,14 @@ __device__ __forceinline__ void phase_done(Ctr *c, const int phase) {
     }
 }
 
-template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
-    __shared__ uint32_t hist[kRadixBins];
-    __shared__ uint32_t wave_tmp[kWaves], res[2], sh_ticket;
-    const int node = blockIdx.y, tid = threadIdx.x;
+// The ticket loop of one block; `shares` = shares per phase = blocks of the node that run this loop.
+template <bool VEC, int THREADS>
+__device__ __forceinline__ void exact_tickets(const SelArgs &a, const int node, const uint32_t shares, uint32_t *hist /*[kRadixBins]*/,
+                                              uint32_t *wave_tmp /*[THREADS / 64]*/, uint32_t *res /*[2]*/) {
+    __shared__ uint32_t sh_ticket;
+    const int tid = threadIdx.x;
     Sel *s = a.sel + node;
-    if (!a.force && s->fast_ok) return;
-    if (a.force) {   // no sampling kernel ran in this call: the next call's state set is cleared here
-        const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock, all = gridDim.y * nthreads;
-        for (uint32_t i = blockIdx.y * nthreads + gtid; i < a.next_words; i += all) a.next_state[i] = 0;
-    }
     Ctr *c = a.ctr + node;
-    const uint32_t shares = gridDim.x;   // per phase: as many as the node has blocks (each draws one per phase if all run)
     uint32_t prefix = 0, rank = a.k;
     int fixed = 0;                       // digits of T* this block has worked out so far
     for (;;) {
@@ -1013,21 +1007,60 @@ __global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
         const int phase = (int)(t / shares);
         const uint32_t run = t % shares;
         if (phase > 0 && !phase_wait(a, c, phase - 1, shares)) return;   // a wait expired somewhere: give up, lgc_stats reports it
-        for (; fixed < (phase < 3 ? phase : 3); ++fixed) radix_fix(a, node, fixed, hist, wave_tmp, res, prefix, rank);
+        for (; fixed < (phase < 3 ? phase : 3); ++fixed) radix_fix<THREADS>(a, node, fixed, hist, wave_tmp, res, prefix, rank);
         if (phase < 3) {
-            radix_count<VEC>(a, node, phase, prefix, hist, run, shares);
+            radix_count<VEC, THREADS>(a, node, phase, prefix, hist, run, shares);
         } else {
             uint32_t c_lo, c_hi, nchunks;
-            block_run(a, run, shares, c_lo, c_hi, nchunks);
+            block_run<THREADS>(a, run, shares, c_lo, c_hi, nchunks);
             if (phase == 3) {
                 if (run == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }   // prefix is the full key T*, rank the ties to take
-                count_run<VEC, kBlock>(a, node, prefix, c_lo, c_hi, run);
+                count_run<VEC, THREADS>(a, node, prefix, c_lo, c_hi, run);
             } else {
-                emit_run<VEC, kBlock>(a, node, prefix, rank, c_lo, c_hi, nchunks, run);
+                emit_run<VEC, THREADS>(a, node, prefix, rank, c_lo, c_hi, nchunks, run);
             }
         }
         phase_done(c, phase);
     }
+}
+
+// Exact selection as one launch of its own: about one block of 256 threads per compute unit, shared by the nodes.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
+    __shared__ uint32_t hist[kRadixBins];
+    __shared__ uint32_t wave_tmp[kWaves], res[2];
+    const int node = blockIdx.y, tid = threadIdx.x;
+    if (!a.force && a.sel[node].fast_ok) return;
+    if (a.force) {   // no sampling kernel ran in this call: the next call's state set is cleared here
+        const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock, all = gridDim.y * nthreads;
+        for (uint32_t i = blockIdx.y * nthreads + gtid; i < a.next_words; i += all) a.next_state[i] = 0;
+    }
+    exact_tickets<VEC, kBlock>(a, node, gridDim.x, hist, wave_tmp, res);
+}
+
+// Output for short candidate lists and the fall-back in ONE launch: blocks 0 .. out_blocks - 1 of a node are
+// the output blocks (output_direct), the blocks after them stand by for the exact path.  Each of those decides
+// for itself, from the candidate count and the fine histogram, whether the output blocks can serve the node
+// (the same test they make: enough candidates, none lost, T* inside the histogram's range) and leaves if so,
+// which is nearly always and costs them one block-wide search; otherwise they run the ticket loop.  A launch
+// of its own for the fall-back costs 4.5 us per call even when it has nothing to do.
+template <bool VEC>
+__global__ __launch_bounds__(1024) void k_output_or_exact(SelArgs a, uint32_t out_blocks) {
+    __shared__ uint32_t hist[kFineBins];
+    __shared__ uint32_t wave_tmp[16], res[2];
+    if (blockIdx.x < out_blocks) { output_direct(a, hist, wave_tmp, res); return; }
+    const int node = blockIdx.y, tid = threadIdx.x;
+    const uint32_t total = a.sel[node].cand_total;
+    bool ok = total >= a.k && total <= a.cap;
+    if (ok) {   // the same for the whole block
+        for (int i = tid; i < kFineBins; i += 1024) hist[i] = a.fine_hist[node * kFineBins + i];
+        __syncthreads();
+        find_rank_bin<kFineBins>(hist, a.k, wave_tmp, res);
+        ok = res[0] < (uint32_t)kFineBins - 1;
+        __syncthreads();
+    }
+    if (ok) return;
+    exact_tickets<VEC, 1024>(a, node, gridDim.x - out_blocks, hist, wave_tmp, res);
 }
 
 // Five launches: step 0..2: the radix pass of that digit (the digits before it are fixed again from their
@@ -1045,15 +1078,15 @@ __global__ __launch_bounds__(kBlock) void k_exact_step(SelArgs a, int step) {
         for (uint32_t i = blockIdx.y * nthreads + gtid; i < a.next_words; i += all) a.next_state[i] = 0;
     }
     uint32_t c_lo, c_hi, nchunks;
-    block_run(a, blockIdx.x, gridDim.x, c_lo, c_hi, nchunks);
+    block_run<kBlock>(a, blockIdx.x, gridDim.x, c_lo, c_hi, nchunks);
     if (step == 4) {
         emit_run<VEC, kBlock>(a, node, s->thr, s->quota, c_lo, c_hi, nchunks, blockIdx.x);
         return;
     }
     uint32_t prefix = 0, rank = a.k;
-    for (int pass = 0; pass < (step < 3 ? step : 3); ++pass) radix_fix(a, node, pass, hist, wave_tmp, res, prefix, rank);
+    for (int pass = 0; pass < (step < 3 ? step : 3); ++pass) radix_fix<kBlock>(a, node, pass, hist, wave_tmp, res, prefix, rank);
     if (step < 3) {
-        radix_count<VEC>(a, node, step, prefix, hist, blockIdx.x, gridDim.x);
+        radix_count<VEC, kBlock>(a, node, step, prefix, hist, blockIdx.x, gridDim.x);
         return;
     }
     if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }
@@ -1091,6 +1124,31 @@ void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st
     dim3 grid(per_node, batch);
     if (vec) hipLaunchKernelGGL(k_exact<true>, grid, dim3(kBlock), 0, st, a);
     else hipLaunchKernelGGL(k_exact<false>, grid, dim3(kBlock), 0, st, a);
+}
+
+// direct = true: short candidate lists (each block reads the whole list; the fall-back rides in the same
+// launch); false: long lists (second-level histogram by many blocks, counts per chunk, output).  Returns
+// whether the fall-back to the exact path is part of what was launched.
+bool launch_output_from_candidates(const SelArgs &a, int batch, bool direct, bool vec, int cus, hipStream_t st) {
+    if (direct) {
+        const uint32_t out_blocks = (a.cap + 4095) / 4096;
+        // stand-by blocks of 1024 threads: as many threads per node as the stand-alone fall-back has
+        const uint32_t chunks = (a.n + 16383u) / 16384u;
+        uint32_t standby = (uint32_t)(cus / batch) / 4;
+        if (standby > chunks) standby = chunks;
+        if (standby < 1) standby = 1;
+        const dim3 grid(out_blocks + standby, batch);
+        if (vec) hipLaunchKernelGGL(k_output_or_exact<true>, grid, dim3(1024), 0, st, a, out_blocks);
+        else hipLaunchKernelGGL(k_output_or_exact<false>, grid, dim3(1024), 0, st, a, out_blocks);
+        return true;
+    }
+    uint32_t blocks = (a.cap + 16383) / 16384;
+    if (blocks > 256) blocks = 256;
+    hipLaunchKernelGGL(k_select_level2, dim3(blocks, batch), dim3(1024), 0, st, a);
+    const uint32_t chunks = (a.cap + kChunk - 1) / kChunk;
+    hipLaunchKernelGGL(k_count_chunks, dim3((chunks + kCountChunks - 1) / kCountChunks, batch), dim3(1024), 0, st, a);
+    hipLaunchKernelGGL(k_emit_scanned, dim3(chunks, batch), dim3(1024), 0, st, a);
+    return false;
 }
 
 }  // namespace lgc
