@@ -73,14 +73,18 @@ constexpr int kWRegs = kCiChunk * 3 * 64 / 256;                      // 12
 // [b][1][l_head], head_w [c_in][1][3] and head_b [c_in] its weights, and every staged input h[ci][q] =
 // act(head_b[ci] + sum_t head_w[ci][t] x[2q - 1 + t]) comes from a 259-value stretch of x kept in LDS: no
 // intermediate tensor, no launch for the first layer, no global loads of inputs in the contraction loop.
-template <bool TAIL, bool HEAD>
+// SPLIT: the contraction is cut into `splits` equal runs of input channels, one block each (blockIdx.y =
+// split * (c_out / 64) + channel block); a block then stores its raw partial sums (no bias, no non-linearity) to
+// out[b][split][co][p], and k_splitk_finish adds them up.  For layers with too few output tiles to fill the
+// device (Table I: conv4 256 -> 64 has 25 tiles per node).
+template <bool TAIL, bool HEAD, bool SPLIT = false>
 __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ in, float *__restrict__ out,
                                                       const float *__restrict__ wt, const float *__restrict__ bias,
                                                       int c_in, int c_out, uint32_t l_in, uint32_t l_out, int act,
                                                       float slope, const float *__restrict__ tail_w /*[tail_c][64]*/,
                                                       const float *__restrict__ tail_b, int tail_c, int tail_act,
                                                       const float *__restrict__ head_w, const float *__restrict__ head_b,
-                                                      uint32_t l_head) {
+                                                      uint32_t l_head, int splits) {
     // the last slot of the input buffer takes the stores of staging slots that hold nothing
     // (a second pair of buffers, with one barrier per chunk, was tried: it costs a resident block per
     // compute unit and gains nothing)
@@ -91,9 +95,14 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, half = lane >> 5, col = lane & 31;
     const uint32_t p0 = blockIdx.x * kPosTile;
-    const int co0 = blockIdx.y * 64;
+    const int co_blocks = c_out / 64;
+    const int co0 = (SPLIT ? (int)blockIdx.y % co_blocks : (int)blockIdx.y) * 64;
+    const int split = SPLIT ? (int)blockIdx.y / co_blocks : 0;
+    const int c_per = SPLIT ? c_in / splits : c_in;          // a multiple of kCiChunk (the launcher sees to it)
+    const int c_lo = split * c_per, c_hi = c_lo + c_per;
     in += (size_t)blockIdx.z * (HEAD ? (size_t)l_head : (size_t)c_in * l_in);
-    out += (size_t)blockIdx.z * (TAIL ? tail_c : c_out) * l_out;
+    out += SPLIT ? ((size_t)blockIdx.z * splits + split) * c_out * l_out
+                 : (size_t)blockIdx.z * (TAIL ? tail_c : c_out) * l_out;
     if (HEAD) {
         for (int i = tid; i < 4 * kPosTile + 3; i += 256) {
             const long long q = 4ll * p0 - 3 + i;
@@ -169,12 +178,12 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 
-    fetch(0);
-    for (int c0 = 0; c0 < c_in; c0 += kCiChunk) {
+    fetch(c_lo);
+    for (int c0 = c_lo; c0 < c_hi; c0 += kCiChunk) {
         __syncthreads();   // the previous chunk's readers are done
         stage(c0);
         __syncthreads();
-        if (c0 + kCiChunk < c_in) fetch(c0 + kCiChunk);   // in flight during the multiplications below
+        if (c0 + kCiChunk < c_hi) fetch(c0 + kCiChunk);   // in flight during the multiplications below
         // contraction index of step s: lanes 0..31 take channel s / 3 of the chunk's first eight, lanes
         // 32..63 the same of its last eight, tap s % 3: both halves read at the same constant offsets
         // from their own base, so the reads of two steps pair into one LDS instruction
@@ -187,6 +196,14 @@ __global__ __launch_bounds__(256) void k_conv3s2_mfma(const float *__restrict__ 
         }
     }
     const uint32_t p = p0 + wn * 32 + col;
+    if (SPLIT) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int co = co0 + wm * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+            if (p < l_out) out[(size_t)co * l_out + p] = acc[r];
+        }
+        return;
+    }
     if (!TAIL) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -241,10 +258,91 @@ bool launch_conv3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_
     dim3 grid((l_out + kPosTile - 1) / kPosTile, l.c_out / 64, batch);
     if (tail)
         hipLaunchKernelGGL((k_conv3s2_mfma<true, false>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
-                           l_out, (int)act, slope, tail->w, tail->b, tail->c_out, (int)tail_act, nullptr, nullptr, 0u);
+                           l_out, (int)act, slope, tail->w, tail->b, tail->c_out, (int)tail_act, nullptr, nullptr, 0u, 1);
     else
         hipLaunchKernelGGL((k_conv3s2_mfma<false, false>), grid, dim3(256), 0, st, in, out, l.wt, l.b, l.c_in, l.c_out, l_in,
-                           l_out, (int)act, slope, nullptr, nullptr, 0, 0, nullptr, nullptr, 0u);
+                           l_out, (int)act, slope, nullptr, nullptr, 0, 0, nullptr, nullptr, 0u, 1);
+    return true;
+}
+
+// ---- split contraction for layers with few output tiles ----------------------------------------------
+// How many runs the contraction of layer `l` is cut into for outputs of length l_out and `batch` nodes: 1 (no
+// split) unless the unsplit launch would leave most compute units without a block and the layer is deep.
+int conv3s2_mfma_splits(const LayerDev &l, uint32_t l_out, int batch) {
+    if (!l.wt || l.ksize != 3 || l.stride != 2 || l.c_in % kCiChunk != 0 || l.c_out % 64 != 0 || l.c_in < 128) return 1;
+    const uint64_t blocks = (uint64_t)((l_out + kPosTile - 1) / kPosTile) * (l.c_out / 64) * batch;
+    if (blocks == 0 || blocks >= 192) return 1;
+    int best = 1;
+    for (int s = 2; s <= 8; s *= 2)   // 2, 4 or 8 equal runs of whole chunks, at most about two blocks per compute unit
+        if ((l.c_in / kCiChunk) % s == 0 && blocks * s <= 512) best = s;
+    return best;
+}
+
+// Adds up the partial sums of a split contraction: y[co][p] = act(bias[co] + sum_s part[b][s][co][p]), summed in
+// the order s = 0, 1, ..  (fixed, so the result does not depend on which block ran when).  tail_c == 0: out is
+// [b][c_out][l_out].  tail_c > 0 (<= 4): a following kernel-1 / stride-1 layer to tail_c channels is applied here
+// as well and out is [b][tail_c][l_out].  Block: 64 positions (one per lane) x 16 wavefronts that take every
+// sixteenth channel each (all of a thread's loads are independent and in flight together: the kernel is a
+// latency chain otherwise); the tail's sums of the sixteen meet in LDS.
+template <int SPLITS>
+__global__ __launch_bounds__(1024) void k_splitk_finish(const float *__restrict__ part, float *__restrict__ out,
+                                                        const float *__restrict__ bias, int c_out, uint32_t l_out, int act,
+                                                        float slope, const float *__restrict__ tail_w /*[tail_c][c_out]*/,
+                                                        const float *__restrict__ tail_b, int tail_c, int tail_act) {
+    __shared__ float red[16][4][64];   // [wavefront][tail channel][position]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t p = blockIdx.x * 64 + lane;
+    const bool live = p < l_out;
+    part += (size_t)blockIdx.y * SPLITS * c_out * l_out;
+    out += (size_t)blockIdx.y * (tail_c ? tail_c : c_out) * l_out;
+    float t[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int co = wave; co < c_out; co += 16) {
+        float x[SPLITS];
+#pragma unroll
+        for (int s = 0; s < SPLITS; ++s) x[s] = live ? part[((size_t)s * c_out + co) * l_out + p] : 0.f;
+        float y = x[0];
+#pragma unroll
+        for (int s = 1; s < SPLITS; ++s) y += x[s];
+        y += bias[co];
+        if (act) y = leaky_m(y, slope);
+        if (tail_c) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (c < tail_c) t[c] = fmaf(tail_w[c * c_out + co], y, t[c]);
+        } else if (live) {
+            out[(size_t)co * l_out + p] = y;
+        }
+    }
+    if (tail_c == 0) return;   // the same for the whole block
+#pragma unroll
+    for (int c = 0; c < 4; ++c) red[wave][c][lane] = t[c];
+    __syncthreads();
+    if (wave < tail_c && live) {   // wavefront c finishes tail channel c
+        float z = tail_b[wave];
+#pragma unroll
+        for (int w = 0; w < 16; ++w) z += red[w][wave][lane];
+        out[(size_t)wave * l_out + p] = tail_act ? leaky_m(z, slope) : z;
+    }
+}
+
+// Layer `l` with its contraction split `splits` ways (conv3s2_mfma_splits): partial sums to `part`
+// ([batch][splits][c_out][l_out] floats), then the finish kernel to `out`.  tail (nullable): a kernel-1 /
+// stride-1 layer from l.c_out to at most 4 channels applied in the finish kernel; `out` is then its output.
+bool launch_conv3s2_mfma_splitk(const float *in, float *part, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out,
+                                int batch, int splits, bool act, float slope, hipStream_t st, const LayerDev *tail,
+                                bool tail_act) {
+    if (!conv3s2_mfma_covers(l, l_in) || (splits != 2 && splits != 4 && splits != 8) || (l.c_in / kCiChunk) % splits != 0) return false;
+    if (tail && !(tail->ksize == 1 && tail->stride == 1 && tail->c_in == l.c_out && tail->c_out <= 4)) return false;
+    if (l_out == 0) return true;
+    dim3 grid((l_out + kPosTile - 1) / kPosTile, (l.c_out / 64) * splits, batch);
+    hipLaunchKernelGGL((k_conv3s2_mfma<false, false, true>), grid, dim3(256), 0, st, in, part, l.wt, l.b, l.c_in, l.c_out, l_in,
+                       l_out, 0, slope, nullptr, nullptr, 0, 0, nullptr, nullptr, 0u, splits);
+    const dim3 fgrid((l_out + 63) / 64, batch);
+#define LGC_FINISH(S) hipLaunchKernelGGL(k_splitk_finish<S>, fgrid, dim3(1024), 0, st, part, out, l.b, l.c_out, l_out, (int)act, slope, \
+                                         tail ? tail->w : nullptr, tail ? tail->b : nullptr, tail ? tail->c_out : 0, (int)tail_act)
+    if (splits == 2) LGC_FINISH(2); else if (splits == 4) LGC_FINISH(4); else LGC_FINISH(8);
+#undef LGC_FINISH
     return true;
 }
 
@@ -258,7 +356,7 @@ bool launch_conv3s2_mfma_head(const float *x, float *out, const LayerDev &head, 
     if (l_out == 0) return true;
     dim3 grid((l_out + kPosTile - 1) / kPosTile, l.c_out / 64, batch);
     hipLaunchKernelGGL((k_conv3s2_mfma<false, true>), grid, dim3(256), 0, st, x, out, l.wt, l.b, l.c_in, l.c_out, l_in, l_out,
-                       (int)act, slope, nullptr, nullptr, 0, 0, head.w, head.b, l_x);
+                       (int)act, slope, nullptr, nullptr, 0, 0, head.w, head.b, l_x, 1);
     return true;
 }
 

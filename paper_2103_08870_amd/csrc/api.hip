@@ -673,6 +673,10 @@ static size_t act_need(const lgc_ae *ae, uint64_t k, int batch) {
     for (size_t l = 0; l < ae->enc.size(); ++l) {
         len = conv_len(len, ae->enc[l]);
         if (l + 1 < ae->enc.size()) need = std::max(need, (size_t)batch * ae->enc[l].c_out * (size_t)len);
+        // a deep layer with few output tiles runs with its contraction split: room for the partial sums, which
+        // never exceed 512 tiles of 64 x 64 (smaller calls split further, up to that many blocks)
+        if (l > 0 && ae->enc_dev[l].wt && ae->enc[l].c_in >= 128 && ae->enc[l].c_out % 64 == 0)
+            need = std::max(need, (size_t)512 * 64 * 64);
     }
     const std::vector<uint64_t> out_len = dec_lengths(ae, k);
     for (size_t l = 0; l + 1 < ae->dec.size(); ++l)
@@ -723,8 +727,10 @@ static lgc_status run_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, 
         return LGC_OK;
     }
     size_t need = 0;
-    for (size_t l = 0; l + 1 < nl; ++l) {
-        size_t f = (size_t)batch * ae->enc[l].c_out * len[l + 1];
+    for (size_t l = 0; l < nl; ++l) {
+        size_t f = l + 1 < nl ? (size_t)batch * ae->enc[l].c_out * len[l + 1] : 0;
+        const int splits = l > 0 ? conv3s2_mfma_splits(ae->enc_dev[l], (uint32_t)len[l + 1], batch) : 1;
+        if (splits > 1) f = std::max(f, (size_t)splits * batch * ae->enc[l].c_out * len[l + 1]);
         if (f > need) need = f;
     }
     if (need > ctx->act_floats)
@@ -740,6 +746,23 @@ static lgc_status run_encode(lgc_ctx *ctx, const lgc_ae *ae, const float *vals, 
                                          (uint32_t)len[2], batch, true, ae->slope, st)) {
                 cur = ctx->act[1];
                 ++l;
+                continue;
+            }
+        }
+        // a deep layer with too few output tiles to fill the device: contraction split over several blocks, partial
+        // sums to the free activation buffer, then a finish kernel (which also applies a kernel-1 layer that follows)
+        const int splits = (cur == ctx->act[0] || cur == ctx->act[1])
+                               ? conv3s2_mfma_splits(ae->enc_dev[l], (uint32_t)len[l + 1], batch) : 1;
+        if (splits > 1) {
+            const LayerDev *tail = nullptr;
+            if (!last && ae->enc[l + 1].ksize == 1 && ae->enc[l + 1].stride == 1 && ae->enc[l + 1].c_out <= 4) tail = &ae->enc_dev[l + 1];
+            const bool out_is_last = tail ? l + 2 == nl : last;
+            float *part = other(cur);
+            float *dst = out_is_last ? latent : const_cast<float *>(cur);   // the layer's input is free once the partial sums exist
+            if (launch_conv3s2_mfma_splitk(cur, part, dst, ae->enc_dev[l], (uint32_t)len[l], (uint32_t)len[l + 1], batch, splits,
+                                           !last, ae->slope, st, tail, tail && !out_is_last)) {
+                cur = dst;
+                if (tail) ++l;
                 continue;
             }
         }

@@ -165,6 +165,11 @@ void launch_weights_contraction_major(const float *w, float *wt, int c_in, int c
 // (64 -> at most 4 channels after a convolution, 32 -> 1 after a transposed one); `out` is then the tail's output
 bool launch_conv3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
                          bool act, float slope, hipStream_t st, const LayerDev *tail = nullptr, bool tail_act = false);
+// split contraction: how many ways (1 = not at all), and the launch (partial sums to `part`, then a finish kernel)
+int conv3s2_mfma_splits(const LayerDev &l, uint32_t l_out, int batch);
+bool launch_conv3s2_mfma_splitk(const float *in, float *part, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out,
+                                int batch, int splits, bool act, float slope, hipStream_t st, const LayerDev *tail = nullptr,
+                                bool tail_act = false);
 bool launch_conv3s2_mfma_head(const float *x, float *out, const LayerDev &head, const LayerDev &l, uint32_t l_x,
                               uint32_t l_in, uint32_t l_out, int batch, bool act, float slope, hipStream_t st);
 bool launch_convt3s2_mfma(const float *in, float *out, const LayerDev &l, uint32_t l_in, uint32_t l_out, int batch,
