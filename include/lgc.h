@@ -27,13 +27,14 @@
  *    stride >= n).  batch = 1 is the single-node form.
  *  - A context owns only scratch memory.  One context serves one stream at a
  *    time and is not thread-safe; calls on one context that overlap race.
- *    Different contexts may work on different streams at the same time.  The
- *    one kernel of the library whose blocks wait for each other (the exact
- *    selection of short inputs, and the fall-back of a node whose sampled
- *    threshold failed) never has more than one block per compute unit, a third
- *    of what the device holds, so several of them fit side by side; its waits
- *    are bounded all the same (an expired wait gives invalid outputs, a
- *    non-zero error count in lgc_stats and LGC_EDEVICE, never a hang).
+ *    Different contexts may work on different streams at the same time, any
+ *    number of them.  In one kernel of the library blocks wait for other
+ *    blocks (the exact selection in one launch: the fall-back of a node whose
+ *    sampled threshold failed, and exact selection of mid-sized inputs): a
+ *    block there only ever waits for work that was handed out, earlier, to a
+ *    block that is already running, so the waits end whatever else shares the
+ *    device; they are bounded all the same (an expired wait gives invalid
+ *    outputs, a non-zero error count in lgc_stats and LGC_EDEVICE, never a hang).
  *  - No call between lgc_create / lgc_reserve and lgc_destroy allocates or
  *    frees device memory or synchronises (lgc_stats and lgc_profile_read, which
  *    read back, aside), and none uses a memset: the calls can be recorded into
