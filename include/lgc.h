@@ -323,14 +323,26 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
 
 /* ---- diagnostics (never needed on the hot path) ---- */
 
-/* LGC_OPT_SELECT_PATH: 0 = automatic (sampled-threshold fast path with the
- * exact radix path as on-device fall-back), 1 = always the exact radix path.
- * The results are the same either way.  Choose 1 for data on which the
- * fall-back is the rule (lgc_stats counts it): where very many magnitudes are
- * equal around the k-th largest, as in quantised gradients, no threshold
- * separates about k elements, and reaching the exact path through the failed
- * fast path costs more than taking it outright (4 nodes x 25.6 M elements of
- * seven distinct values: 1.73 ms against 0.96 ms per accumulate + top-k).
+/* LGC_OPT_SELECT_PATH: how lgc_topk / lgc_accumulate_topk select (the results
+ * are the same whichever way):
+ *   0 = automatic (default): the sampled-threshold fast path with the exact
+ *       radix path as on-device fall-back; once the library has seen
+ *       selections fall back, it takes the exact path outright for some
+ *       selections of the context before it tries the fast path again: 1
+ *       after the first fall-back, twice as many after each further one, 64
+ *       at most, and from 1 again once the fast path has served a selection.
+ *       It sees the outcomes without any synchronisation: each selection
+ *       stores its number to one of two pinned host words, which the host
+ *       reads when it queues the next selection, so the switch comes some
+ *       calls late when the host runs ahead of the device, and a recorded
+ *       HIP graph keeps the choice made when it was recorded.
+ *   1 = always the exact radix path.
+ *   2 = always the fast path first, whatever happened before.
+ * What the switch is for: where very many magnitudes are equal around the k-th
+ * largest, as in quantised gradients, no threshold separates about k elements,
+ * and reaching the exact path through the failed fast path costs more than
+ * taking it outright (4 nodes x 25.6 M elements of seven distinct values:
+ * 1.73 ms against 0.96 ms per accumulate + top-k).
  * LGC_OPT_PROFILE: 1 = bracket the streaming kernel launches of lgc_accumulate /
  * lgc_topk / lgc_accumulate_topk, their per-layer forms and lgc_accumulate_gather
  * with HIP events (read by lgc_profile_read). */

@@ -40,6 +40,12 @@ struct lgc_ctx {
     uint32_t *seg_t = nullptr, *seg_cand = nullptr, *seg_row_prefix = nullptr;
     size_t seg_t_words = 0, seg_cand_words = 0;
     int opt_path = 0, opt_profile = 0;
+    // Automatic path choice: a selection that falls back on the device stores its call number to a pinned host
+    // word; the host looks at that word (an ordinary read, no synchronisation) when it queues the next
+    // selection, and after a change takes the exact path outright for a while before it tries the fast path again.
+    uint32_t *fell_back_host = nullptr, *fell_back_dev = nullptr;
+    uint32_t call_number = 0, fell_back_seen = 0;
+    int exact_calls_left = 0, penalty = 0;
     std::vector<hipEvent_t> ev;  // pairs: start, stop
     size_t ev_used = 0;
     char err[256] = {0};
@@ -251,6 +257,8 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     a.spin_limit = 1u << 22;
     a.force = 0;
     a.stats = c->stats;
+    a.notify = c->fell_back_dev;
+    a.notify_value = 0;
     const StateLayout L = state_layout(c->max_batch, c->status_cand_stride, c->status_exact_stride);
     uint32_t *cur = c->state[c->cur];
     a.sel = (Sel *)(cur + L.sel);
@@ -265,6 +273,8 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     a.out_vals = out_vals; a.out_idx = out_idx;
     return a;
 }
+
+constexpr int kMaxExactCalls = 64;   // most selections in a row that take the exact path outright after fall-backs were seen
 
 // accumulate (optional) + select; g == nullptr means selection only
 lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t n, int batch, uint64_t stride,
@@ -281,11 +291,31 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
         return LGC_OK;
     }
     SelArgs a = make_args(ctx, g, u, v, n, stride, m, k, out_vals, out_idx);
-    bool fast = ctx->opt_path == 0 && n >= kMinFastN;
+    bool fast = ctx->opt_path != 1 && n >= kMinFastN;
     if (fast) {
         a.rank = choose_rank((uint32_t)n, (uint32_t)k);
         fast = a.rank <= kSample / 4 &&
                1.5 * expected_candidates((double)n, (double)k) + 4096.0 <= (double)ctx->cap;
+    }
+    if (fast && ctx->opt_path == 0 && ctx->fell_back_host) {
+        // data on which the fast path keeps failing (very many equal magnitudes around the k-th largest): reaching
+        // the exact path through the failed fast path costs nearly twice what taking it outright does.  Each newly
+        // seen fall-back doubles the number of selections that take the exact path outright before the fast path is
+        // tried again (1, 2, 4, ... 64); a fast-path success seen after the last fall-back resets it.
+        const uint32_t fell_back = ((volatile uint32_t *)ctx->fell_back_host)[0];
+        const uint32_t served = ((volatile uint32_t *)ctx->fell_back_host)[1];
+        if (fell_back != ctx->fell_back_seen) {
+            ctx->fell_back_seen = fell_back;
+            ctx->penalty = ctx->penalty ? (ctx->penalty * 2 > kMaxExactCalls ? kMaxExactCalls : ctx->penalty * 2) : 1;
+            ctx->exact_calls_left = ctx->penalty;
+        } else if ((int32_t)(served - fell_back) > 0) {
+            ctx->penalty = 0;
+        }
+        if (ctx->exact_calls_left > 0) { --ctx->exact_calls_left; fast = false; }
+    }
+    if (fast) {
+        if (++ctx->call_number == 0) ctx->call_number = 1;
+        a.notify_value = ctx->call_number;
     }
     ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
     if (fast) {
@@ -355,6 +385,18 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
         return fail(nullptr, LGC_EHIP, "hipMemset: %s", hipGetErrorString(e));
     }
     bind_scratch(c, block, L);
+    // the pinned word of the automatic path choice; without it (allocation refused) the choice is simply not adaptive
+    void *pinned = nullptr, *pinned_dev = nullptr;
+    if (hipHostMalloc(&pinned, 64, hipHostMallocMapped) == hipSuccess) {
+        memset(pinned, 0, 64);
+        if (hipHostGetDevicePointer(&pinned_dev, pinned, 0) == hipSuccess) {
+            c->fell_back_host = (uint32_t *)pinned;
+            c->fell_back_dev = (uint32_t *)pinned_dev;
+        } else {
+            (void)hipHostFree(pinned);
+        }
+    }
+    (void)hipGetLastError();
     *out = c;
     return LGC_OK;
 }
@@ -369,6 +411,7 @@ extern "C" void lgc_destroy(lgc_ctx *ctx) {
     if (ctx->seg_cand) (void)hipFree(ctx->seg_cand);
     if (ctx->seg_row_prefix) (void)hipFree(ctx->seg_row_prefix);
     if (ctx->scratch) (void)hipFree(ctx->scratch);
+    if (ctx->fell_back_host) (void)hipHostFree(ctx->fell_back_host);
     delete ctx;
 }
 
@@ -1189,8 +1232,10 @@ extern "C" lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value
     if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
     switch (opt) {
         case LGC_OPT_SELECT_PATH:
-            if (value != 0 && value != 1) return fail(ctx, LGC_EINVAL, "LGC_OPT_SELECT_PATH takes 0 or 1");
+            if (value < 0 || value > 2) return fail(ctx, LGC_EINVAL, "LGC_OPT_SELECT_PATH takes 0, 1 or 2");
             ctx->opt_path = (int)value;
+            ctx->exact_calls_left = ctx->penalty = 0;   // the automatic choice starts afresh: what fell back before the change does not count
+            if (ctx->fell_back_host) ctx->fell_back_seen = *(volatile uint32_t *)ctx->fell_back_host;
             return LGC_OK;
         case LGC_OPT_PROFILE:
             ctx->opt_profile = value != 0;

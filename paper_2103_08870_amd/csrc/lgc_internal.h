@@ -84,6 +84,9 @@ struct SelArgs {
     uint32_t spin_limit;      // bound of a wait for the shares of the previous phase (exact path in one launch)
     int force;                // exact path chosen by the host (ignore fast_ok)
     Stats *stats;
+    uint32_t *notify;         // two pinned host words (device address; null: none): a selection stores notify_value to word 0
+                              // when it falls back, to word 1 when the fast path served it
+    uint32_t notify_value;
     // current state set
     Sel *sel;
     Ctr *ctr;

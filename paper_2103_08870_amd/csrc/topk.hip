@@ -28,6 +28,11 @@
 
 namespace lgc {
 
+// A store to a word in pinned host memory that the host reads without synchronising with the stream.
+__device__ __forceinline__ void st_system32(uint32_t *p, uint32_t x) {
+    __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // ------------------------------------------------------------------ clearing of a state set
 
 __global__ __launch_bounds__(kBlock) void k_clear(uint32_t *words, uint32_t count) {
@@ -493,6 +498,7 @@ __device__ __forceinline__ void output_direct(const SelArgs &a, uint32_t *hist /
         s->fast_ok = ok;
         if (ok) { s->thr = thr; s->quota = quota; }
         atomicAdd(ok ? &a.stats->fast : &a.stats->fallback, 1u);
+        if (a.notify) st_system32(a.notify + (ok ? 1 : 0), a.notify_value);   // the host sees the outcome without synchronising
     }
     if (!ok || base >= total) return;
 
@@ -740,6 +746,7 @@ __global__ __launch_bounds__(1024) void k_count_chunks(SelArgs a) {
         s->fast_ok = ok;
         if (ok) { s->thr = thr; s->quota = quota; }
         atomicAdd(ok ? &a.stats->fast : &a.stats->fallback, 1u);
+        if (a.notify) st_system32(a.notify + (ok ? 1 : 0), a.notify_value);   // the host sees the outcome without synchronising
     }
     if (!ok || base >= total) return;
 #pragma unroll

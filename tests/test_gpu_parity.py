@@ -220,6 +220,53 @@ def test_topk_falls_back_on_device(B, oracle):
     ctx.close()
 
 
+def test_automatic_path_choice_after_fall_backs(B, oracle):
+    """Seven distinct magnitudes: no threshold separates about k elements, every selection that tries the fast path
+    falls back.  With the automatic choice (the default) the library notices, without any synchronisation of its
+    own, and takes the exact path outright for 1, 2, 4, ... selections between its tries of the fast path; once the
+    fast path serves a selection again the count starts over.  The results are the oracle's whichever way."""
+    n, k, K = 1 << 20, 3000, 2
+    rng = np.random.default_rng(7)
+    tied = (rng.integers(-3, 4, (K, n)) * 0.5).astype(np.float32)
+    spread = rng.standard_normal((K, n)).astype(np.float32)
+
+    def reference(v0):
+        ref = []
+        for b in range(K):
+            vb = v0[b].copy()
+            ref.append(oracle.topk(vb, None, k) + (vb,))
+        return v0, ref
+
+    tied, spread = reference(tied), reference(spread)
+
+    def run(ctx, data, calls):
+        v0, ref = data
+        outcomes = []
+        for t in range(calls):
+            dv = dev(v0)
+            ovals = torch.zeros((K, k), device="cuda")
+            oidx = torch.zeros((K, k), device="cuda", dtype=torch.int32)
+            B.lgc_topk(ctx, dv, None, k, ovals, oidx)
+            fast, fallback, errors = B.lgc_stats(ctx)             # synchronises: the host sees each call's outcome
+            assert errors == 0 and (fast, fallback) in ((0, 0), (K, 0), (0, K))
+            outcomes.append("x" if fallback else "f" if fast else "e")   # fell back / fast path / exact path outright
+            for b in range(K):
+                vals, idx, vb = ref[b]
+                assert (oidx[b].cpu().numpy().astype(np.uint32) == idx).all() and same_bits(ovals[b], vals)
+                assert same_bits(dv[b], vb)
+        return "".join(outcomes)
+
+    ctx = B.Context(n, k, K)
+    assert run(ctx, tied, 12) == "xexeexeeeexe"       # 1, 2, 4 exact selections between the tries; 7 of the next 8 still due
+    assert run(ctx, spread, 10) == "eeeeeeefff"       # those 7, then the fast path serves again
+    assert run(ctx, tied, 4) == "xexe"                # and the count has started over
+    B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 2)
+    assert run(ctx, tied, 4) == "xxxx"                # fast path first, every time
+    B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 0)
+    assert run(ctx, tied, 3) == "xex"                 # a change of the option starts the choice afresh
+    ctx.close()
+
+
 def test_topk_heavy_tail_beyond_histogram_range(B, oracle):
     # more than k elements far above the estimate: the k-th key lies in the histogram's
     # open-ended last bin, which the fast path leaves to the exact path
@@ -274,8 +321,7 @@ def test_topk_adversarial_layouts(B, oracle, n, k):
 def run_iterations(B, oracle, w, ks, iters, force_exact=False, check_every=1):
     n, K = w.n, w.nodes
     ctx = B.Context(n, max(ks), K)
-    if force_exact:
-        B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 1)
+    B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 1 if force_exact else 2)    # 2: the fast path first in every iteration
     du = torch.zeros((K, n), device="cuda")
     dv = torch.zeros((K, n), device="cuda")
     u = np.zeros((K, n), np.float32)
@@ -714,6 +760,7 @@ def test_full_size_workloads(B, oracle, cfg, ratio_index, iters, nodes_checked):
     w = synth.workload(cfg)
     K, n, k = w.nodes, w.n, w.ks[ratio_index]
     ctx = B.Context(n, k, K)
+    B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 2)                  # the fast path first in every iteration
     du = torch.zeros((K, n), device="cuda")
     dv = torch.zeros((K, n), device="cuda")
     u = [np.zeros(n, np.float32) for _ in range(nodes_checked)]
