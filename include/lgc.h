@@ -345,8 +345,23 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
  * 1.73 ms against 0.96 ms per accumulate + top-k).
  * LGC_OPT_PROFILE: 1 = bracket the streaming kernel launches of lgc_accumulate /
  * lgc_topk / lgc_accumulate_topk, their per-layer forms and lgc_accumulate_gather
- * with HIP events (read by lgc_profile_read). */
-typedef enum { LGC_OPT_SELECT_PATH = 0, LGC_OPT_PROFILE = 1 } lgc_option;
+ * with HIP events (read by lgc_profile_read).
+ * LGC_OPT_CARRY_THRESHOLD (default 1): the fast path of lgc_topk /
+ * lgc_accumulate_topk needs a threshold with a few more than k elements above
+ * it before its pass over the vector.  It samples the vector for one; with this
+ * option on it may instead take one worked out on the device from the exact
+ * k-th magnitudes of the context's last three selections (Alg. 1 / Alg. 2 run
+ * every iteration on the same residuals, whose k-th magnitude moves smoothly):
+ * their trend continued by one step, lowered by the margin that the last
+ * selection's own candidate count says holds half as many candidates again as
+ * k.  That threshold is offered only by a selection whose own k-th magnitude
+ * lay close (a third of the margin) to what the two before it predicted, and
+ * only to the next selection of the context with the same n and k.  Results do
+ * not depend on it: a threshold that turns out too high or too low sends that
+ * node to the exact path, as after a bad sample.  0 = always sample.  A HIP
+ * graph replays selections with the numbers they had when recorded, so in a
+ * replayed graph only selections after the graph's first can be served so. */
+typedef enum { LGC_OPT_SELECT_PATH = 0, LGC_OPT_PROFILE = 1, LGC_OPT_CARRY_THRESHOLD = 2 } lgc_option;
 lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value);
 
 /* Synchronises the device and reports, summed since the last call of
@@ -357,6 +372,11 @@ lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value);
  * of range or out of order in lgc_scatter / lgc_gather).  Returns LGC_EDEVICE
  * if errors != 0. */
 lgc_status lgc_stats(lgc_ctx *ctx, uint64_t *fast, uint64_t *fallback, uint64_t *errors);
+
+/* Synchronises and reports the selections (nodes) since the last call of this
+ * function whose candidate threshold was carried over from earlier selections
+ * instead of sampled (see LGC_OPT_CARRY_THRESHOLD). */
+lgc_status lgc_stats_carried(lgc_ctx *ctx, uint64_t *carried);
 
 /* Synchronises, then returns the summed duration (ms) and the number of
  * bracketed calls since the last read (a call's streaming work may be several

@@ -17,13 +17,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblgc.so")
 
 LGC_OK, LGC_EINVAL, LGC_ENOMEM, LGC_EHIP, LGC_EDEVICE = range(5)
-LGC_OPT_SELECT_PATH, LGC_OPT_PROFILE = 0, 1
+LGC_OPT_SELECT_PATH, LGC_OPT_PROFILE, LGC_OPT_CARRY_THRESHOLD = 0, 1, 2
 
 EXPORTS = [
     "lgc_create", "lgc_destroy", "lgc_last_error", "lgc_status_string",
     "lgc_accumulate", "lgc_topk", "lgc_accumulate_topk", "lgc_accumulate_topk_static",
     "lgc_ae_create", "lgc_ae_destroy", "lgc_latent_len", "lgc_encode", "lgc_decode",
-    "lgc_scatter", "lgc_reserve", "lgc_set_option", "lgc_stats", "lgc_profile_read",
+    "lgc_scatter", "lgc_reserve", "lgc_set_option", "lgc_stats", "lgc_stats_carried", "lgc_profile_read",
     "lgc_gather", "lgc_accumulate_gather", "lgc_average",
     "lgc_segments_create", "lgc_segments_destroy", "lgc_segments_total_k",
     "lgc_topk_segmented", "lgc_accumulate_topk_segmented",
@@ -109,6 +109,8 @@ def lib() -> C.CDLL:
     l.lgc_set_option.restype = i32
     l.lgc_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]
     l.lgc_stats.restype = i32
+    l.lgc_stats_carried.argtypes = [vp, C.POINTER(u64)]
+    l.lgc_stats_carried.restype = i32
     l.lgc_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u64)]
     l.lgc_profile_read.restype = i32
     _lib = l
@@ -385,6 +387,13 @@ def lgc_stats(ctx: Context, check: bool = True) -> Tuple[int, int, int]:
     if check:
         _check(st, ctx.h)
     return a.value, b.value, c.value
+
+
+def lgc_stats_carried(ctx: Context) -> int:
+    """Selections since the last call whose candidate threshold was carried over instead of sampled; synchronises."""
+    a = C.c_uint64()
+    _check(lib().lgc_stats_carried(ctx.h, C.byref(a)), ctx.h)
+    return a.value
 
 
 def lgc_profile_read(ctx: Context) -> Tuple[float, int]:

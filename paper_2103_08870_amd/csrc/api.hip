@@ -39,10 +39,14 @@ struct lgc_ctx {
     // per-layer selection: thresholds [max_batch][n_seg] and a candidate list of its own, grown on demand
     uint32_t *seg_t = nullptr, *seg_cand = nullptr, *seg_row_prefix = nullptr;
     size_t seg_t_words = 0, seg_cand_words = 0;
-    int opt_path = 0, opt_profile = 0;
-    // Automatic path choice: a selection that falls back on the device stores its call number to a pinned host
-    // word; the host looks at that word (an ordinary read, no synchronisation) when it queues the next
-    // selection, and after a change takes the exact path outright for a while before it tries the fast path again.
+    int opt_path = 0, opt_profile = 0, opt_carry = 1;
+    // Thresholds carried from one selection to the next (one record per node, device memory, see Carry); `serial`
+    // numbers the context's selections so that a record only serves the selection right after the one that wrote it.
+    Carry *carry = nullptr;
+    uint32_t serial = 0;
+    // Automatic path choice: a selection stores its call number to one of two pinned host words (fell back /
+    // served by the fast path); the host looks at them (an ordinary read, no synchronisation) when it queues the
+    // next selection, and after fall-backs takes the exact path outright for a while before it tries the fast path again.
     uint32_t *fell_back_host = nullptr, *fell_back_dev = nullptr;
     uint32_t call_number = 0, fell_back_seen = 0;
     int exact_calls_left = 0, penalty = 0;
@@ -194,11 +198,11 @@ StateLayout state_layout(int max_batch, uint32_t status_cand_stride, uint32_t st
 }
 
 // The selection scratch of a context for (max_n, max_k, max_batch): byte offsets of its parts in one block of
-// device memory.  Everything before `samples` (statistics, state sets) must start at zero.
+// device memory.  Everything before `samples` (statistics, carried thresholds, state sets) must start at zero.
 struct ScratchLayout {
     bool ok = false;
     uint32_t cap = 0, rows = 0, supers = 0, status_cand_stride = 0, status_exact_stride = 0, state_words = 0;
-    size_t stats = 0, state[2] = {0, 0}, samples = 0, row_count = 0, row_super = 0, bitmap = 0, cand_idx = 0, cand_val = 0;
+    size_t stats = 0, carry = 0, state[2] = {0, 0}, samples = 0, row_count = 0, row_super = 0, bitmap = 0, cand_idx = 0, cand_val = 0;
     size_t bytes = 0;
 };
 
@@ -216,6 +220,7 @@ ScratchLayout scratch_layout(uint64_t max_n, uint64_t max_k, int max_batch, bool
     size_t off = 0;
     auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, A); return o; };
     s.stats = carve(sizeof(Stats));
+    s.carry = carve(B * sizeof(Carry));
     s.state[0] = carve(L.words * 4);
     s.state[1] = two_state_sets ? carve(L.words * 4) : s.state[0];
     s.samples = carve(B * kSample * 4);
@@ -236,6 +241,7 @@ void bind_scratch(lgc_ctx *c, void *base_ptr, const ScratchLayout &s) {
     c->status_cand_stride = s.status_cand_stride; c->status_exact_stride = s.status_exact_stride;
     c->state_words = s.state_words;
     c->stats = (Stats *)(base + s.stats);
+    c->carry = (Carry *)(base + s.carry);
     c->state[0] = (uint32_t *)(base + s.state[0]);
     c->state[1] = (uint32_t *)(base + s.state[1]);
     c->samples = (uint32_t *)(base + s.samples);
@@ -259,6 +265,8 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     a.stats = c->stats;
     a.notify = c->fell_back_dev;
     a.notify_value = 0;
+    a.carry = c->opt_carry && !c->single_state ? c->carry : nullptr;
+    a.serial = 0;
     const StateLayout L = state_layout(c->max_batch, c->status_cand_stride, c->status_exact_stride);
     uint32_t *cur = c->state[c->cur];
     a.sel = (Sel *)(cur + L.sel);
@@ -291,6 +299,7 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
         return LGC_OK;
     }
     SelArgs a = make_args(ctx, g, u, v, n, stride, m, k, out_vals, out_idx);
+    a.serial = ++ctx->serial;
     bool fast = ctx->opt_path != 1 && n >= kMinFastN;
     if (fast) {
         a.rank = choose_rank((uint32_t)n, (uint32_t)k);
@@ -1116,6 +1125,8 @@ static lgc_status run_segmented(lgc_ctx *ctx, const lgc_segments *seg, const flo
     a.row_seg = seg->row_seg; a.seg_t = ctx->seg_t; a.row_prefix = ctx->seg_row_prefix;
     a.cap = seg->cap;
     a.cand_idx = ctx->seg_cand; a.cand_val = ctx->seg_cand + (size_t)ctx->max_batch * seg->cap;
+    a.carry = nullptr;
+    ++ctx->serial;   // a selection of another kind came between: the flat selection's carried thresholds lapse
     ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
     if (seg->n_sampled) {
         launch_seg_estimate(a, batch, fused, vec, st);   // also clears the next call's state set
@@ -1240,6 +1251,10 @@ extern "C" lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value
         case LGC_OPT_PROFILE:
             ctx->opt_profile = value != 0;
             return LGC_OK;
+        case LGC_OPT_CARRY_THRESHOLD:
+            ctx->opt_carry = value != 0;
+            ++ctx->serial;   // whatever has been recorded so far serves no later selection
+            return LGC_OK;
     }
     return fail(ctx, LGC_EINVAL, "unknown option %d", (int)opt);
 }
@@ -1251,11 +1266,23 @@ extern "C" lgc_status lgc_stats(lgc_ctx *ctx, uint64_t *fast, uint64_t *fallback
     HIP_TRY(ctx, hipDeviceSynchronize());
     Stats h;
     HIP_TRY(ctx, hipMemcpy(&h, ctx->stats, sizeof h, hipMemcpyDeviceToHost));
-    HIP_TRY(ctx, hipMemset(ctx->stats, 0, sizeof h));
+    HIP_TRY(ctx, hipMemset(ctx->stats, 0, offsetof(Stats, carried)));
     if (fast) *fast = h.fast;
     if (fallback) *fallback = h.fallback;
     if (errors) *errors = h.errors;
     if (h.errors) return fail(ctx, LGC_EDEVICE, "%u device-side failures since the last lgc_stats", h.errors);
+    return LGC_OK;
+}
+
+extern "C" lgc_status lgc_stats_carried(lgc_ctx *ctx, uint64_t *carried) {
+    if (!ctx) return fail(nullptr, LGC_EINVAL, "ctx is NULL");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    uint32_t h = 0;
+    HIP_TRY(ctx, hipMemcpy(&h, &ctx->stats->carried, sizeof h, hipMemcpyDeviceToHost));
+    HIP_TRY(ctx, hipMemset(&ctx->stats->carried, 0, sizeof h));
+    if (carried) *carried = h;
     return LGC_OK;
 }
 

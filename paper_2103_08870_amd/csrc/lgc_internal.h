@@ -49,7 +49,8 @@ struct Sel {
     uint32_t thr;         // exact k-th largest key T*
     uint32_t quota;       // how many elements with key == T* are taken (lowest indices first)
     uint32_t fast_ok;     // 1: the fast path produced this node's output
-    uint32_t pad[11];
+    uint32_t carried;     // 1: t_est was carried over from earlier selections, not sampled
+    uint32_t pad[10];
 };
 static_assert(sizeof(Sel) == 64, "Sel is one 64-byte record");
 
@@ -59,13 +60,29 @@ static_assert(sizeof(Sel) == 64, "Sel is one 64-byte record");
 struct Ctr {
     uint32_t ticket;      // exact path in one launch: next share to hand out (phase = ticket / shares)
     uint32_t done[5];     // completed shares of each phase
-    uint32_t pad[26];
+    uint32_t sampled;     // sampling blocks of the node that have finished (the last one works out the estimate)
+    uint32_t pad[25];
 };
 static_assert(sizeof(Ctr) == 128, "Ctr is one 128-byte line");
 
 struct Stats {
-    uint32_t fast, fallback, errors, pad;
+    uint32_t fast, fallback, errors;
+    uint32_t carried;     // selections whose candidate threshold was carried over instead of sampled
 };
+
+// Per-node record that outlives the call (it is in neither state set): the exact thresholds T* of the last
+// selections of the context, as log2 of their magnitude, and, when they have moved smoothly enough, the candidate
+// threshold that the next selection may use without sampling.  Written by the one thread that reports a
+// selection's outcome, read by the sampling kernel of the next selection.
+struct Carry {
+    uint32_t serial;      // number of the selection (per context, counted by the host) that wrote the record
+    uint32_t n, k;        // its vector length and k: the record only serves a selection of the same shape
+    uint32_t len;         // consecutive fast-path selections recorded, up to 3 (0: none)
+    float log2_t[3];      // log2 |T*| of the last `len` selections, latest first
+    uint32_t next_t_est;  // candidate threshold (key) for selection serial + 1; 0: sample
+    uint32_t pad[8];
+};
+static_assert(sizeof(Carry) == 64, "Carry is one 64-byte record");
 
 // Everything the selection kernels need; passed by value.
 struct SelArgs {
@@ -87,6 +104,8 @@ struct SelArgs {
     uint32_t *notify;         // two pinned host words (device address; null: none): a selection stores notify_value to word 0
                               // when it falls back, to word 1 when the fast path served it
     uint32_t notify_value;
+    Carry *carry;             // [batch] thresholds carried from selection to selection (null: always sample)
+    uint32_t serial;          // number of this selection
     // current state set
     Sel *sel;
     Ctr *ctr;

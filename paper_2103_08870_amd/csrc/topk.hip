@@ -55,15 +55,29 @@ __device__ __forceinline__ uint32_t mix32(uint32_t h) {
 
 // Four neighbouring elements per thread.  The keys that the accumulation WILL produce are sampled (the fused
 // source recomputes v + (m*u + g) without storing it); their first-level histogram (key >> 20)
-// is accumulated per block in LDS and flushed with a few atomics.
+// is accumulated per block in LDS and flushed with a few atomics.  The block of a node that finishes last then
+// works out the estimate: t_est = (roughly) the rank-th largest sampled key, to 2^-13 relative resolution (first
+// level from the histogram, second level from the keys).  Nobody waits for anybody.
+// A node whose record of carried thresholds offers a candidate threshold for this very selection (same shape, the
+// selection right after the one that wrote it) takes that one and samples nothing.
 // The kernel also clears the state set that the next call will use.
 template <bool FUSED, bool VEC>
 __global__ __launch_bounds__(1024) void k_sample(SelArgs a) {
     __shared__ uint32_t hist[kSampleBins];
+    __shared__ uint32_t wave_tmp[16], res[2];
+    __shared__ uint32_t sh_last;
     const int node = blockIdx.y, tid = threadIdx.x;
     {
         const uint32_t gt = (blockIdx.y * gridDim.x + blockIdx.x) * 1024u + tid, nt = gridDim.x * gridDim.y * 1024u;
         for (uint32_t i = gt; i < a.next_words; i += nt) a.next_state[i] = 0;
+    }
+    if (a.carry) {   // uniform over the node's blocks
+        const Carry *c = a.carry + node;
+        const uint32_t t = c->next_t_est;
+        if (t != 0 && c->serial + 1 == a.serial && c->n == a.n && c->k == a.k) {
+            if (blockIdx.x == 0 && tid == 0) { a.sel[node].t_est = t; a.sel[node].carried = 1; atomicAdd(&a.stats->carried, 1u); }
+            return;
+        }
     }
     const size_t off = (size_t)node * a.stride;
     // four neighbouring threads read one 64-byte cluster of 16 elements; the clusters sit at
@@ -103,19 +117,23 @@ __global__ __launch_bounds__(1024) void k_sample(SelArgs a) {
     *(u4 *)(smp + j * 4) = keys;
     __syncthreads();
     for (int i = tid; i < kSampleBins; i += 1024) { uint32_t h = hist[i]; if (h) atomicAdd(&sh[i], h); }
-}
 
-// One block per node: t_est = (roughly) the rank-th largest sampled key, to 2^-13 relative
-// resolution (first level from the histogram, second level from the keys).
-__global__ __launch_bounds__(1024) void k_estimate(SelArgs a) {
-    __shared__ uint32_t hist[kSampleBins];
-    __shared__ uint32_t wave_tmp[16], res[2];
-    const int node = blockIdx.x, tid = threadIdx.x;
-    const uint32_t *smp = a.samples + (size_t)node * kSample;
+    // Which block is the last of the node to get here?  Every wavefront first waits until its stores and atomics
+    // have been acknowledged, one thread releases them to the device and counts the block.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    if (tid == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        sh_last = atomicAdd(&a.ctr[node].sampled, 1u) == gridDim.x - 1 ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!sh_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // the other blocks' keys, through this XCD's caches
+
     u4 x[kSample / 4 / 1024];
 #pragma unroll
     for (int r = 0; r < (int)(kSample / 4 / 1024); ++r) x[r] = *(const u4 *)(smp + (r * 1024 + tid) * 4);
-    for (int i = tid; i < kSampleBins; i += 1024) hist[i] = a.sample_hist[node * kSampleBins + i];
+    for (int i = tid; i < kSampleBins; i += 1024) hist[i] = ld_agent32(&sh[i]);
     __syncthreads();
     find_rank_bin<kSampleBins>(hist, a.rank, wave_tmp, res);
     const uint32_t b1 = res[0], need = a.rank - res[1];
@@ -143,7 +161,6 @@ void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_
         if (vec) hipLaunchKernelGGL((k_sample<false, true>), grid, dim3(1024), 0, st, a);
         else hipLaunchKernelGGL((k_sample<false, false>), grid, dim3(1024), 0, st, a);
     }
-    hipLaunchKernelGGL(k_estimate, dim3(batch), dim3(1024), 0, st, a);
 }
 
 // ------------------------------------------------------------------ gather of the candidates
@@ -358,6 +375,51 @@ __device__ __forceinline__ void count_candidates(const uint32_t *cval, uint32_t 
 
 // ------------------------------------------------------------------ exact k-th key among the candidates
 
+// What the one thread that knows a selection's outcome on the fast path leaves behind: the node's state for the
+// kernels after it, the statistics, the word the host polls, and the record of carried thresholds.
+// The record: log2 |T*| of up to three selections in a row.  With three, T* of the next selection is predicted on
+// the line through the last two; the distance kept below the prediction is the one that would have put half as
+// many candidates again as k above this selection's T* (from this selection's own count: the candidates above
+// t_est were `total`, so log(count) falls by log(total / k) over log2 T* - log2 t_est).  The threshold is offered
+// only if this selection's T* lay within a third of that distance from what the two before it predicted;
+// a wrong offer costs the next selection its fast path (too few candidates, or too many for the list), never
+// its result.
+__device__ __forceinline__ void report_outcome(const SelArgs &a, const int node, Sel *s, const bool ok, const uint32_t thr,
+                                               const uint32_t quota, const uint32_t total, const uint32_t t_est) {
+    s->fast_ok = ok;
+    if (ok) { s->thr = thr; s->quota = quota; }
+    atomicAdd(ok ? &a.stats->fast : &a.stats->fallback, 1u);
+    // the host sees the outcome without synchronising; a carried threshold that failed says nothing about the data
+    if (a.notify && (ok || !s->carried)) st_system32(a.notify + (ok ? 1 : 0), a.notify_value);
+    if (!a.carry) return;
+    Carry *c = a.carry + node;
+    const bool follows = c->serial + 1 == a.serial && c->n == a.n && c->k == a.k;
+    const float l1 = c->log2_t[0], l2 = c->log2_t[1];
+    uint32_t len = 0, next = 0;
+    float l0 = 0.f;
+    constexpr uint32_t kMinNormal = 0x00800000u, kInf = 0x7f800000u;
+    if (ok && thr >= kMinNormal && thr < kInf && t_est >= kMinNormal && t_est < thr) {
+        l0 = log2f(__uint_as_float(thr));
+        len = follows ? (c->len < 2 ? c->len + 1 : 3u) : 1u;
+        const float ratio = log2f((float)total / (float)a.k);   // > 0: total >= k
+        if (len == 3 && ratio >= 0.05f) {
+            const float used = l0 - log2f(__uint_as_float(t_est));
+            float gap = used * (0.585f / ratio);                  // log2(1.5) = 0.585
+            gap = fminf(fmaxf(gap, 0.25f * used), 4.f * used);
+            const float miss = fabsf(l0 - (2.f * l1 - l2));
+            if (used > 0.f && gap <= 0.25f && 3.f * miss <= gap) {
+                const uint32_t t = __float_as_uint(exp2f(2.f * l0 - l1 - gap));
+                if (t >= kMinNormal && t < kInf) next = t;
+            }
+        }
+    }
+    c->serial = a.serial; c->n = a.n; c->k = a.k; c->len = len;
+    c->log2_t[0] = l0; c->log2_t[1] = l1; c->log2_t[2] = l2;
+    c->next_t_est = next;
+}
+
+
+
 // Block-wide: the exact k-th largest key T* and the number of ties to take, from the fine
 // histogram (first level, bins of 2^12 above t_est) and a second-level histogram of the low 12
 // bits inside the bin that holds the k-th key.  LOCAL = true: the second level is counted here
@@ -494,12 +556,7 @@ __device__ __forceinline__ void output_direct(const SelArgs &a, uint32_t *hist /
             quota = need - res[1];
         }
     }
-    if (blockIdx.x == 0 && tid == 0) {
-        s->fast_ok = ok;
-        if (ok) { s->thr = thr; s->quota = quota; }
-        atomicAdd(ok ? &a.stats->fast : &a.stats->fallback, 1u);
-        if (a.notify) st_system32(a.notify + (ok ? 1 : 0), a.notify_value);   // the host sees the outcome without synchronising
-    }
+    if (blockIdx.x == 0 && tid == 0) report_outcome(a, node, s, ok, thr, quota, total, t_est);
     if (!ok || base >= total) return;
 
     // selected-or-tied counts among the candidates before mine: groups r*1024 + tid, r < blockIdx.x
@@ -742,12 +799,7 @@ __global__ __launch_bounds__(1024) void k_count_chunks(SelArgs a) {
     }
     uint32_t thr = 0, quota = 0;
     const bool ok = find_threshold<false>(a, node, total, hist, wave_tmp, res, thr, quota);
-    if (blockIdx.x == 0 && tid == 0) {
-        s->fast_ok = ok;
-        if (ok) { s->thr = thr; s->quota = quota; }
-        atomicAdd(ok ? &a.stats->fast : &a.stats->fallback, 1u);
-        if (a.notify) st_system32(a.notify + (ok ? 1 : 0), a.notify_value);   // the host sees the outcome without synchronising
-    }
+    if (blockIdx.x == 0 && tid == 0) report_outcome(a, node, s, ok, thr, quota, total, s->t_est);
     if (!ok || base >= total) return;
 #pragma unroll
     for (int c = 0; c < kCountChunks; ++c) {

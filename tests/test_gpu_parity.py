@@ -259,7 +259,9 @@ def test_automatic_path_choice_after_fall_backs(B, oracle):
     ctx = B.Context(n, k, K)
     assert run(ctx, tied, 12) == "xexeexeeeexe"       # 1, 2, 4 exact selections between the tries; 7 of the next 8 still due
     assert run(ctx, spread, 10) == "eeeeeeefff"       # those 7, then the fast path serves again
-    assert run(ctx, tied, 4) == "xexe"                # and the count has started over
+    # the count has started over; the first of these selections took a threshold carried over from the three equal
+    # ones before it, and a carried threshold that fails says nothing about the data: it does not count
+    assert run(ctx, tied, 4) == "xxex"
     B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 2)
     assert run(ctx, tied, 4) == "xxxx"                # fast path first, every time
     B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 0)
@@ -351,6 +353,59 @@ def test_fused_iterations_match_oracle(B, oracle, cfg, n):
     w = synth.workload(cfg, n=n, nodes=min(synth.workload(cfg).nodes, 3))
     fast, fallback = run_iterations(B, oracle, w, w.ks, iters=4)
     assert fast + fallback == w.nodes
+
+
+def test_thresholds_carried_from_iteration_to_iteration(B, oracle):
+    """Alg. 1 / Alg. 2 run every iteration on the same residuals: 44 iterations, every one checked against the
+    oracle.  Once the k-th magnitude moves smoothly the library takes the candidate threshold from the trend of the
+    previous selections instead of sampling (lgc_stats_carried counts those); the gradients are then scaled by 6
+    and by 1 / 50 for an iteration each, so that a carried threshold is far off in either direction: the results
+    stay the oracle's (such a selection falls back to the exact path on the device).  With the option off nothing
+    is carried."""
+    w = synth.workload(2, n=1 << 21, nodes=2)
+    n, K, k = w.n, w.nodes, w.k
+    shocks = {36: 6.0, 40: 0.02}
+
+    def loop(carry):
+        ctx = B.Context(n, k, K)
+        if not carry:
+            B.lgc_set_option(ctx, B.LGC_OPT_CARRY_THRESHOLD, 0)
+        du = torch.zeros((K, n), device="cuda")
+        dv = torch.zeros((K, n), device="cuda")
+        u = np.zeros((K, n), np.float32)
+        v = np.zeros((K, n), np.float32)
+        carried, fell_back, outs = [], 0, []
+        for t in range(44):
+            dg = synth.gradients(w, t % 10, device="cuda") * shocks.get(t, 1.0)
+            g = dg.cpu().numpy()
+            ovals = torch.zeros((K, k), device="cuda")
+            oidx = torch.zeros((K, k), device="cuda", dtype=torch.int32)
+            B.lgc_accumulate_topk(ctx, dg, du, dv, w.momentum, k, ovals, oidx)
+            fast, fallback, errors = B.lgc_stats(ctx)
+            assert errors == 0
+            fell_back += fallback
+            carried.append(B.lgc_stats_carried(ctx))
+            if carry:
+                for b in range(K):
+                    oracle.accumulate(g[b], u[b], v[b], w.momentum)
+                    vals, idx = oracle.topk(v[b], u[b], k)
+                    assert (oidx[b].cpu().numpy().astype(np.uint32) == idx).all(), (t, b)
+                    assert same_bits(ovals[b], vals), (t, b)
+                assert same_bits(dv, v) and same_bits(du, u), t
+            outs.append((ovals, oidx))
+        ctx.close()
+        return carried, fell_back, outs, (du, dv)
+
+    carried, fell_back, outs, state = loop(True)
+    assert sum(carried[:3]) == 0                       # three selections must be on record first
+    assert sum(carried[:36]) >= K * 10, carried        # smooth stretch: most selections are served by the trend
+    assert fell_back <= 4 * K, fell_back               # the shocks may cost a fall-back each way, a smooth stretch none
+    plain_carried, _, plain_outs, plain_state = loop(False)
+    assert sum(plain_carried) == 0
+    for (a_vals, a_idx), (b_vals, b_idx) in zip(outs, plain_outs):
+        assert torch.equal(a_idx, b_idx) and torch.equal(a_vals.view(torch.int32), b_vals.view(torch.int32))
+    for x, y in zip(state, plain_state):
+        assert torch.equal(x.view(torch.int32), y.view(torch.int32))
 
 
 def test_fused_exact_path_iterations(B, oracle):
