@@ -358,7 +358,9 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
  * lay close (a third of the margin) to what the two before it predicted, and
  * only to the next selection of the context with the same n and k.  Results do
  * not depend on it: a threshold that turns out too high or too low sends that
- * node to the exact path, as after a bad sample.  0 = always sample.  A HIP
+ * node to the exact path, as after a bad sample, and doubles the number of
+ * selections in a row (3 at first, 96 at most) that must be on record before
+ * the next offer.  0 = always sample.  A HIP
  * graph replays selections with the numbers they had when recorded, so in a
  * replayed graph only selections after the graph's first can be served so. */
 typedef enum { LGC_OPT_SELECT_PATH = 0, LGC_OPT_PROFILE = 1, LGC_OPT_CARRY_THRESHOLD = 2 } lgc_option;

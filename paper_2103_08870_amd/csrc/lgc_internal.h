@@ -77,10 +77,13 @@ struct Stats {
 struct Carry {
     uint32_t serial;      // number of the selection (per context, counted by the host) that wrote the record
     uint32_t n, k;        // its vector length and k: the record only serves a selection of the same shape
-    uint32_t len;         // consecutive fast-path selections recorded, up to 3 (0: none)
-    float log2_t[3];      // log2 |T*| of the last `len` selections, latest first
+    uint32_t len;         // fast-path selections in a row so far (counted up to 255; 0: none)
+    float log2_t[3];      // log2 |T*| of the last min(len, 3) selections, latest first
     uint32_t next_t_est;  // candidate threshold (key) for selection serial + 1; 0: sample
-    uint32_t pad[8];
+    uint32_t fails;       // carried thresholds that sent their selection to the exact path, up to 5; each doubles the
+                          // selections in a row required before the next offer, 64 carried selections that held take one off
+    uint32_t held;        // carried selections that held since `fails` last changed
+    uint32_t pad[6];
 };
 static_assert(sizeof(Carry) == 64, "Carry is one 64-byte record");
 

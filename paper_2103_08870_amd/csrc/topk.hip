@@ -383,7 +383,7 @@ __device__ __forceinline__ void count_candidates(const uint32_t *cval, uint32_t 
 // t_est were `total`, so log(count) falls by log(total / k) over log2 T* - log2 t_est).  The threshold is offered
 // only if this selection's T* lay within a third of that distance from what the two before it predicted;
 // a wrong offer costs the next selection its fast path (too few candidates, or too many for the list), never
-// its result.
+// its result, and doubles the number of fast-path selections in a row that the next offer waits for (3, 6, ... 96).
 __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node, Sel *s, const bool ok, const uint32_t thr,
                                                const uint32_t quota, const uint32_t total, const uint32_t t_est) {
     s->fast_ok = ok;
@@ -395,14 +395,18 @@ __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node,
     Carry *c = a.carry + node;
     const bool follows = c->serial + 1 == a.serial && c->n == a.n && c->k == a.k;
     const float l1 = c->log2_t[0], l2 = c->log2_t[1];
-    uint32_t len = 0, next = 0;
+    uint32_t len = 0, next = 0, fails = follows ? c->fails : 0u, held = follows ? c->held : 0u;
+    if (s->carried) {
+        if (!ok) { fails = fails < 5 ? fails + 1 : 5u; held = 0; }
+        else if (++held >= 64) { fails = fails ? fails - 1 : 0u; held = 0; }
+    }
     float l0 = 0.f;
     constexpr uint32_t kMinNormal = 0x00800000u, kInf = 0x7f800000u;
     if (ok && thr >= kMinNormal && thr < kInf && t_est >= kMinNormal && t_est < thr) {
         l0 = log2f(__uint_as_float(thr));
-        len = follows ? (c->len < 2 ? c->len + 1 : 3u) : 1u;
+        len = follows ? (c->len < 255 ? c->len + 1 : 255u) : 1u;
         const float ratio = log2f((float)total / (float)a.k);   // > 0: total >= k
-        if (len == 3 && ratio >= 0.05f) {
+        if (len >= (3u << fails) && ratio >= 0.05f) {
             const float used = l0 - log2f(__uint_as_float(t_est));
             float gap = used * (0.585f / ratio);                  // log2(1.5) = 0.585
             gap = fminf(fmaxf(gap, 0.25f * used), 4.f * used);
@@ -415,7 +419,7 @@ __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node,
     }
     c->serial = a.serial; c->n = a.n; c->k = a.k; c->len = len;
     c->log2_t[0] = l0; c->log2_t[1] = l1; c->log2_t[2] = l2;
-    c->next_t_est = next;
+    c->next_t_est = next; c->fails = fails; c->held = held;
 }
 
 
