@@ -146,8 +146,9 @@ void profile_begin(lgc_ctx *c, hipStream_t st) {
     if (c->ev_used + 2 > c->ev.size()) {
         if (c->ev.size() >= 2 * 8192) return;  // pool exhausted: stop bracketing until the next read
         hipEvent_t a, b;
-        if (hipEventCreate(&a) != hipSuccess) return;
-        if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+        // timing only: no system-scope fence when the event completes (it would flush the caches around the kernel it times)
+        if (hipEventCreateWithFlags(&a, hipEventDisableSystemFence) != hipSuccess) return;
+        if (hipEventCreateWithFlags(&b, hipEventDisableSystemFence) != hipSuccess) { (void)hipEventDestroy(a); return; }
         try {
             c->ev.reserve(c->ev.size() + 2);
         } catch (...) {
@@ -300,6 +301,10 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
     }
     SelArgs a = make_args(ctx, g, u, v, n, stride, m, k, out_vals, out_idx);
     a.serial = ++ctx->serial;
+    {   // a carried threshold aims at 1.5 k candidates, or at what a sample would give where that is fewer (large k)
+        const double sampled = expected_candidates((double)n, (double)k) / (double)k;
+        a.carry_target = (float)log2(sampled < 1.5 ? sampled : 1.5);
+    }
     bool fast = ctx->opt_path != 1 && n >= kMinFastN;
     if (fast) {
         a.rank = choose_rank((uint32_t)n, (uint32_t)k);

@@ -109,6 +109,7 @@ struct SelArgs {
     uint32_t notify_value;
     Carry *carry;             // [batch] thresholds carried from selection to selection (null: always sample)
     uint32_t serial;          // number of this selection
+    float carry_target;       // log2 of (candidates aimed at by a carried threshold) / k
     // current state set
     Sel *sel;
     Ctr *ctr;

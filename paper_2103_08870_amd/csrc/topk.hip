@@ -379,7 +379,8 @@ __device__ __forceinline__ void count_candidates(const uint32_t *cval, uint32_t 
 // kernels after it, the statistics, the word the host polls, and the record of carried thresholds.
 // The record: log2 |T*| of up to three selections in a row.  With three, T* of the next selection is predicted on
 // the line through the last two; the distance kept below the prediction is the one that would have put half as
-// many candidates again as k above this selection's T* (from this selection's own count: the candidates above
+// many candidates again as k (or as many as a sample would give, if that is fewer) above this selection's T*
+// (from this selection's own count: the candidates above
 // t_est were `total`, so log(count) falls by log(total / k) over log2 T* - log2 t_est).  The threshold is offered
 // only if this selection's T* lay within a third of that distance from what the two before it predicted;
 // a wrong offer costs the next selection its fast path (too few candidates, or too many for the list), never
@@ -408,7 +409,7 @@ __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node,
         const float ratio = log2f((float)total / (float)a.k);   // > 0: total >= k
         if (len >= (3u << fails) && ratio >= 0.05f) {
             const float used = l0 - log2f(__uint_as_float(t_est));
-            float gap = used * (0.585f / ratio);                  // log2(1.5) = 0.585
+            float gap = used * (a.carry_target / ratio);
             gap = fminf(fmaxf(gap, 0.25f * used), 4.f * used);
             const float miss = fabsf(l0 - (2.f * l1 - l2));
             if (used > 0.f && gap <= 0.25f && 3.f * miss <= gap) {
