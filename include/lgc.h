@@ -350,16 +350,17 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
  * lgc_accumulate_topk needs a threshold with a few more than k elements above
  * it before its pass over the vector.  It samples the vector for one; with this
  * option on it may instead take one worked out on the device from the exact
- * k-th magnitudes of the context's last three selections (Alg. 1 / Alg. 2 run
+ * k-th magnitudes of the context's last selections (Alg. 1 / Alg. 2 run
  * every iteration on the same residuals, whose k-th magnitude moves smoothly):
  * their trend continued by one step, lowered by the margin that the last
  * selection's own candidate count says holds half as many candidates again as
- * k.  That threshold is offered only by a selection whose own k-th magnitude
- * lay close (a third of the margin) to what the two before it predicted, and
- * only to the next selection of the context with the same n and k.  Results do
+ * k.  That threshold is offered only after selections whose k-th magnitudes
+ * each lay close (a third of the margin) to what the two before them
+ * predicted, and only to the next selection of the context with the same n
+ * and k.  Results do
  * not depend on it: a threshold that turns out too high or too low sends that
  * node to the exact path, as after a bad sample, and doubles the number of
- * selections in a row (3 at first, 96 at most) that must be on record before
+ * selections in a row (4 at first, 128 at most) that must be on record before
  * the next offer.  0 = always sample.  A HIP
  * graph replays selections with the numbers they had when recorded, so in a
  * replayed graph only selections after the graph's first can be served so. */

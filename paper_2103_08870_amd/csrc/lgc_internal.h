@@ -83,7 +83,9 @@ struct Carry {
     uint32_t fails;       // carried thresholds that sent their selection to the exact path, up to 5; each doubles the
                           // selections in a row required before the next offer, 64 carried selections that held take one off
     uint32_t held;        // carried selections that held since `fails` last changed
-    uint32_t pad[6];
+    float miss;           // how far T* lay from the trend of the two selections before it (log2), largest of the
+                          // recent selections: each selection's own miss, or three quarters of the value before
+    uint32_t pad[5];
 };
 static_assert(sizeof(Carry) == 64, "Carry is one 64-byte record");
 

@@ -382,9 +382,10 @@ __device__ __forceinline__ void count_candidates(const uint32_t *cval, uint32_t 
 // many candidates again as k (or as many as a sample would give, if that is fewer) above this selection's T*
 // (from this selection's own count: the candidates above
 // t_est were `total`, so log(count) falls by log(total / k) over log2 T* - log2 t_est).  The threshold is offered
-// only if this selection's T* lay within a third of that distance from what the two before it predicted;
+// only if the recent selections' T* (this one's, and with fading weight those before it) each lay within a third of
+// that distance from what the two selections before them predicted;
 // a wrong offer costs the next selection its fast path (too few candidates, or too many for the list), never
-// its result, and doubles the number of fast-path selections in a row that the next offer waits for (3, 6, ... 96).
+// its result, and doubles the number of fast-path selections in a row that the next offer waits for (4, 8, ... 128).
 __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node, Sel *s, const bool ok, const uint32_t thr,
                                                const uint32_t quota, const uint32_t total, const uint32_t t_est) {
     s->fast_ok = ok;
@@ -401,17 +402,18 @@ __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node,
         if (!ok) { fails = fails < 5 ? fails + 1 : 5u; held = 0; }
         else if (++held >= 64) { fails = fails ? fails - 1 : 0u; held = 0; }
     }
-    float l0 = 0.f;
+    float l0 = 0.f, miss = 0.f;
     constexpr uint32_t kMinNormal = 0x00800000u, kInf = 0x7f800000u;
     if (ok && thr >= kMinNormal && thr < kInf && t_est >= kMinNormal && t_est < thr) {
         l0 = log2f(__uint_as_float(thr));
         len = follows ? (c->len < 255 ? c->len + 1 : 255u) : 1u;
+        if (len >= 3) miss = fmaxf(fabsf(l0 - (2.f * l1 - l2)), len > 3 ? 0.75f * c->miss : 0.f);
         const float ratio = log2f((float)total / (float)a.k);   // > 0: total >= k
-        if (len >= (3u << fails) && ratio >= 0.05f) {
+        // two misses on record at least (four selections), more after offers that failed
+        if (len >= (4u << fails) && ratio >= 0.05f) {
             const float used = l0 - log2f(__uint_as_float(t_est));
             float gap = used * (a.carry_target / ratio);
             gap = fminf(fmaxf(gap, 0.25f * used), 4.f * used);
-            const float miss = fabsf(l0 - (2.f * l1 - l2));
             if (used > 0.f && gap <= 0.25f && 3.f * miss <= gap) {
                 const uint32_t t = __float_as_uint(exp2f(2.f * l0 - l1 - gap));
                 if (t >= kMinNormal && t < kInf) next = t;
@@ -420,7 +422,7 @@ __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node,
     }
     c->serial = a.serial; c->n = a.n; c->k = a.k; c->len = len;
     c->log2_t[0] = l0; c->log2_t[1] = l1; c->log2_t[2] = l2;
-    c->next_t_est = next; c->fails = fails; c->held = held;
+    c->next_t_est = next; c->fails = fails; c->held = held; c->miss = miss;
 }
 
 

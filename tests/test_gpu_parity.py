@@ -258,8 +258,8 @@ def test_automatic_path_choice_after_fall_backs(B, oracle):
 
     ctx = B.Context(n, k, K)
     assert run(ctx, tied, 12) == "xexeexeeeexe"       # 1, 2, 4 exact selections between the tries; 7 of the next 8 still due
-    assert run(ctx, spread, 10) == "eeeeeeefff"       # those 7, then the fast path serves again
-    # the count has started over; the first of these selections took a threshold carried over from the three equal
+    assert run(ctx, spread, 12) == "eeeeeeefffff"     # those 7, then the fast path serves again
+    # the count has started over; the first of these selections took a threshold carried over from the equal
     # ones before it, and a carried threshold that fails says nothing about the data: it does not count
     assert run(ctx, tied, 4) == "xxex"
     B.lgc_set_option(ctx, B.LGC_OPT_SELECT_PATH, 2)
@@ -397,7 +397,7 @@ def test_thresholds_carried_from_iteration_to_iteration(B, oracle):
         return carried, fell_back, outs, (du, dv)
 
     carried, fell_back, outs, state = loop(True)
-    assert sum(carried[:3]) == 0                       # three selections must be on record first
+    assert sum(carried[:4]) == 0                       # four selections must be on record first
     assert sum(carried[:36]) >= K * 10, carried        # smooth stretch: most selections are served by the trend
     assert fell_back <= 4 * K, fell_back               # the shocks may cost a fall-back each way, a smooth stretch none
     plain_carried, _, plain_outs, plain_state = loop(False)
