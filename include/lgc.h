@@ -361,9 +361,11 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
  * not depend on it: a threshold that turns out too high or too low sends that
  * node to the exact path, as after a bad sample, and doubles the number of
  * selections in a row (4 at first, 128 at most) that must be on record before
- * the next offer.  0 = always sample.  A HIP
- * graph replays selections with the numbers they had when recorded, so in a
- * replayed graph only selections after the graph's first can be served so. */
+ * the next offer.  0 = always sample.  The
+ * record is kept and judged on the device, by the selections themselves (any
+ * other kind of selection on the context, exact or per-layer, leaves it
+ * empty), so it works the same in a replayed HIP graph.  Setting the option
+ * synchronises the device and empties the record. */
 typedef enum { LGC_OPT_SELECT_PATH = 0, LGC_OPT_PROFILE = 1, LGC_OPT_CARRY_THRESHOLD = 2 } lgc_option;
 lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value);
 

@@ -40,10 +40,8 @@ struct lgc_ctx {
     uint32_t *seg_t = nullptr, *seg_cand = nullptr, *seg_row_prefix = nullptr;
     size_t seg_t_words = 0, seg_cand_words = 0;
     int opt_path = 0, opt_profile = 0, opt_carry = 1;
-    // Thresholds carried from one selection to the next (one record per node, device memory, see Carry); `serial`
-    // numbers the context's selections so that a record only serves the selection right after the one that wrote it.
+    // Thresholds carried from one selection to the next (one record per node, device memory, see Carry)
     Carry *carry = nullptr;
-    uint32_t serial = 0;
     // Automatic path choice: a selection stores its call number to one of two pinned host words (fell back /
     // served by the fast path); the host looks at them (an ordinary read, no synchronisation) when it queues the
     // next selection, and after fall-backs takes the exact path outright for a while before it tries the fast path again.
@@ -267,7 +265,6 @@ SelArgs make_args(lgc_ctx *c, const float *g, float *u, float *v, uint64_t n, ui
     a.notify = c->fell_back_dev;
     a.notify_value = 0;
     a.carry = c->opt_carry && !c->single_state ? c->carry : nullptr;
-    a.serial = 0;
     const StateLayout L = state_layout(c->max_batch, c->status_cand_stride, c->status_exact_stride);
     uint32_t *cur = c->state[c->cur];
     a.sel = (Sel *)(cur + L.sel);
@@ -300,7 +297,6 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
         return LGC_OK;
     }
     SelArgs a = make_args(ctx, g, u, v, n, stride, m, k, out_vals, out_idx);
-    a.serial = ++ctx->serial;
     {   // a carried threshold aims at 1.5 k candidates, or at what a sample would give where that is fewer (large k)
         const double sampled = expected_candidates((double)n, (double)k) / (double)k;
         a.carry_target = (float)log2(sampled < 1.5 ? sampled : 1.5);
@@ -1130,8 +1126,6 @@ static lgc_status run_segmented(lgc_ctx *ctx, const lgc_segments *seg, const flo
     a.row_seg = seg->row_seg; a.seg_t = ctx->seg_t; a.row_prefix = ctx->seg_row_prefix;
     a.cap = seg->cap;
     a.cand_idx = ctx->seg_cand; a.cand_val = ctx->seg_cand + (size_t)ctx->max_batch * seg->cap;
-    a.carry = nullptr;
-    ++ctx->serial;   // a selection of another kind came between: the flat selection's carried thresholds lapse
     ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
     if (seg->n_sampled) {
         launch_seg_estimate(a, batch, fused, vec, st);   // also clears the next call's state set
@@ -1258,7 +1252,12 @@ extern "C" lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value
             return LGC_OK;
         case LGC_OPT_CARRY_THRESHOLD:
             ctx->opt_carry = value != 0;
-            ++ctx->serial;   // whatever has been recorded so far serves no later selection
+            {   // whatever has been recorded so far serves no later selection
+                DeviceGuard guard(ctx->device);
+                if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
+                HIP_TRY(ctx, hipDeviceSynchronize());
+                HIP_TRY(ctx, hipMemset(ctx->carry, 0, (size_t)ctx->max_batch * sizeof(Carry)));
+            }
             return LGC_OK;
     }
     return fail(ctx, LGC_EINVAL, "unknown option %d", (int)opt);

@@ -73,13 +73,15 @@ struct Stats {
 // Per-node record that outlives the call (it is in neither state set): the exact thresholds T* of the last
 // selections of the context, as log2 of their magnitude, and, when they have moved smoothly enough, the candidate
 // threshold that the next selection may use without sampling.  Written by the one thread that reports a
-// selection's outcome, read by the sampling kernel of the next selection.
+// selection's outcome, read by the sampling kernel of the next selection.  Every selection of the context ends by
+// writing it, on the device: the fast path its outcome, the exact path and the per-layer selection "nothing on
+// record" (len = 0, no offer); so the record is always the previous selection's, also in a replayed HIP graph.
 struct Carry {
-    uint32_t serial;      // number of the selection (per context, counted by the host) that wrote the record
+    uint32_t unused;
     uint32_t n, k;        // its vector length and k: the record only serves a selection of the same shape
     uint32_t len;         // fast-path selections in a row so far (counted up to 255; 0: none)
     float log2_t[3];      // log2 |T*| of the last min(len, 3) selections, latest first
-    uint32_t next_t_est;  // candidate threshold (key) for selection serial + 1; 0: sample
+    uint32_t next_t_est;  // candidate threshold (key) offered to the next selection; 0: sample
     uint32_t fails;       // carried thresholds that sent their selection to the exact path, up to 5; each doubles the
                           // selections in a row required before the next offer, 64 carried selections that held take one off
     uint32_t held;        // carried selections that held since `fails` last changed
@@ -110,7 +112,6 @@ struct SelArgs {
                               // when it falls back, to word 1 when the fast path served it
     uint32_t notify_value;
     Carry *carry;             // [batch] thresholds carried from selection to selection (null: always sample)
-    uint32_t serial;          // number of this selection
     float carry_target;       // log2 of (candidates aimed at by a carried threshold) / k
     // current state set
     Sel *sel;

@@ -305,6 +305,8 @@ __global__ __launch_bounds__(kSelThreads) void k_seg_select(SelArgs a) {
     __shared__ uint32_t wave_tmp[16], res[2], sh_g[16], sh_e[16];
     const uint32_t l = blockIdx.x;
     const int node = blockIdx.y;
+    // a selection of another kind on this context: the flat selection's carried thresholds lapse
+    if (a.carry && l == 0 && threadIdx.x == 0) { a.carry[node].len = 0; a.carry[node].next_t_est = 0; }
     const uint32_t k = a.seg_k[l];
     if (k == 0) return;
     const uint32_t lo = a.seg_off[l], hi = a.seg_off[l + 1];

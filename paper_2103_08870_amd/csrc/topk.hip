@@ -33,6 +33,11 @@ __device__ __forceinline__ void st_system32(uint32_t *p, uint32_t x) {
     __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
+// A selection that does not go through the fast path's report leaves "nothing on record" for the next one.
+__device__ __forceinline__ void carry_lapse(const SelArgs &a, const int node) {
+    if (a.carry) { a.carry[node].len = 0; a.carry[node].next_t_est = 0; }
+}
+
 // ------------------------------------------------------------------ clearing of a state set
 
 __global__ __launch_bounds__(kBlock) void k_clear(uint32_t *words, uint32_t count) {
@@ -74,7 +79,7 @@ __global__ __launch_bounds__(1024) void k_sample(SelArgs a) {
     if (a.carry) {   // uniform over the node's blocks
         const Carry *c = a.carry + node;
         const uint32_t t = c->next_t_est;
-        if (t != 0 && c->serial + 1 == a.serial && c->n == a.n && c->k == a.k) {
+        if (t != 0 && c->n == a.n && c->k == a.k) {
             if (blockIdx.x == 0 && tid == 0) { a.sel[node].t_est = t; a.sel[node].carried = 1; atomicAdd(&a.stats->carried, 1u); }
             return;
         }
@@ -395,9 +400,10 @@ __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node,
     if (a.notify && (ok || !s->carried)) st_system32(a.notify + (ok ? 1 : 0), a.notify_value);
     if (!a.carry) return;
     Carry *c = a.carry + node;
-    const bool follows = c->serial + 1 == a.serial && c->n == a.n && c->k == a.k;
+    const bool same = c->n == a.n && c->k == a.k;           // the record is the previous selection's, of this shape
+    const bool follows = same && c->len > 0;
     const float l1 = c->log2_t[0], l2 = c->log2_t[1];
-    uint32_t len = 0, next = 0, fails = follows ? c->fails : 0u, held = follows ? c->held : 0u;
+    uint32_t len = 0, next = 0, fails = same ? c->fails : 0u, held = same ? c->held : 0u;
     if (s->carried) {
         if (!ok) { fails = fails < 5 ? fails + 1 : 5u; held = 0; }
         else if (++held >= 64) { fails = fails ? fails - 1 : 0u; held = 0; }
@@ -420,7 +426,7 @@ __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node,
             }
         }
     }
-    c->serial = a.serial; c->n = a.n; c->k = a.k; c->len = len;
+    c->n = a.n; c->k = a.k; c->len = len;
     c->log2_t[0] = l0; c->log2_t[1] = l1; c->log2_t[2] = l2;
     c->next_t_est = next; c->fails = fails; c->held = held; c->miss = miss;
 }
@@ -1011,7 +1017,7 @@ __global__ __launch_bounds__(1024) void k_exact_block(SelArgs a) {
         radix_digit(pass, hist, wave_tmp, res, prefix, rank);
     }
     // prefix is now the full key T*; rank the number of ties to take
-    if (tid == 0) { s->thr = prefix; s->quota = rank; }
+    if (tid == 0) { s->thr = prefix; s->quota = rank; carry_lapse(a, node); }
     const uint32_t nchunks = (a.n + 16383u) / 16384u;
     emit_run<VEC, 1024>(a, node, prefix, rank, 0u, nchunks, nchunks, 0u);
 }
@@ -1080,7 +1086,7 @@ __device__ __forceinline__ void exact_tickets(const SelArgs &a, const int node, 
             uint32_t c_lo, c_hi, nchunks;
             block_run<THREADS>(a, run, shares, c_lo, c_hi, nchunks);
             if (phase == 3) {
-                if (run == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }   // prefix is the full key T*, rank the ties to take
+                if (run == 0 && tid == 0) { s->thr = prefix; s->quota = rank; carry_lapse(a, node); }   // prefix is the full key T*, rank the ties to take
                 count_run<VEC, THREADS>(a, node, prefix, c_lo, c_hi, run);
             } else {
                 emit_run<VEC, THREADS>(a, node, prefix, rank, c_lo, c_hi, nchunks, run);
@@ -1155,7 +1161,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_step(SelArgs a, int step) {
         radix_count<VEC, kBlock>(a, node, step, prefix, hist, blockIdx.x, gridDim.x);
         return;
     }
-    if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; }
+    if (blockIdx.x == 0 && tid == 0) { s->thr = prefix; s->quota = rank; carry_lapse(a, node); }
     count_run<VEC, kBlock>(a, node, prefix, c_lo, c_hi, blockIdx.x);
 }
 
