@@ -138,16 +138,18 @@ __global__ __launch_bounds__(1024) void k_seg_estimate(SelArgs a) {
             keys[j] = key_of(y);
         }
     }
-    uint32_t above;
-    const uint32_t t = block_radix_select<1024>(
-        [&](auto f) {
-            if (active) {
+    // the order statistic to 2^-11 relative resolution (exponent and 11 mantissa bits), rounded down: a threshold
+    // needs no more, and a lower one only flags a few more candidates (3 % where the counts are steepest)
+    auto each = [&](auto f) {
+        if (active) {
 #pragma unroll
-                for (int j = 0; j < 16; ++j) f(keys[j]);
-            }
-        },
-        rank, hist, wave_tmp, res, above);
-    if (tid == 0) *out = t;
+            for (int j = 0; j < 16; ++j) f(keys[j]);
+        }
+    };
+    uint32_t r = rank, prefix = 0, gt = 0;
+    radix_pass<0, 1024>(each, r, prefix, gt, hist, wave_tmp, res);
+    radix_pass<1, 1024>(each, r, prefix, gt, hist, wave_tmp, res);
+    if (tid == 0) *out = prefix << 12;
 }
 
 void launch_seg_estimate(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st) {
