@@ -342,7 +342,7 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
  * largest, as in quantised gradients, no threshold separates about k elements,
  * and reaching the exact path through the failed fast path costs more than
  * taking it outright (4 nodes x 25.6 M elements of seven distinct values:
- * 1.73 ms against 0.96 ms per accumulate + top-k).
+ * 1.31 ms against 0.96 ms per accumulate + top-k).
  * LGC_OPT_PROFILE: 1 = bracket the streaming kernel launches of lgc_accumulate /
  * lgc_topk / lgc_accumulate_topk, their per-layer forms and lgc_accumulate_gather
  * with HIP events (read by lgc_profile_read).

@@ -1096,18 +1096,18 @@ __device__ __forceinline__ void exact_tickets(const SelArgs &a, const int node, 
     }
 }
 
-// Exact selection as one launch of its own: about one block of 256 threads per compute unit, shared by the nodes.
+// Exact selection as one launch of its own: about one block of 1024 threads per compute unit, shared by the nodes.
 template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_exact(SelArgs a) {
+__global__ __launch_bounds__(1024) void k_exact(SelArgs a) {
     __shared__ uint32_t hist[kRadixBins];
-    __shared__ uint32_t wave_tmp[kWaves], res[2];
+    __shared__ uint32_t wave_tmp[16], res[2];
     const int node = blockIdx.y, tid = threadIdx.x;
     if (!a.force && a.sel[node].fast_ok) return;
     if (a.force) {   // no sampling kernel ran in this call: the next call's state set is cleared here
-        const uint32_t gtid = blockIdx.x * kBlock + tid, nthreads = gridDim.x * kBlock, all = gridDim.y * nthreads;
+        const uint32_t gtid = blockIdx.x * 1024u + tid, nthreads = gridDim.x * 1024u, all = gridDim.y * nthreads;
         for (uint32_t i = blockIdx.y * nthreads + gtid; i < a.next_words; i += all) a.next_state[i] = 0;
     }
-    exact_tickets<VEC, kBlock>(a, node, gridDim.x, hist, wave_tmp, res);
+    exact_tickets<VEC, 1024>(a, node, gridDim.x, hist, wave_tmp, res);
 }
 
 // Output for short candidate lists and the fall-back in ONE launch: blocks 0 .. out_blocks - 1 of a node are
@@ -1188,14 +1188,15 @@ void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st
         else hipLaunchKernelGGL(k_exact_block<false>, dim3(1, batch), dim3(1024), 0, st, a);
         return;
     }
-    // one launch, about one block per compute unit shared by the nodes: each block more makes the phase
-    // changes dearer (a device-scope release per share), each block less the five passes over v slower
+    // one launch, about one block of 1024 threads per compute unit shared by the nodes: each block more makes the
+    // phase changes dearer (a device-scope release per share), each block less the five passes over v slower
     uint32_t per_node = (uint32_t)(cus / batch);
-    if (per_node > chunks) per_node = chunks;
+    const uint32_t shares_max = (a.n + 16383u) / 16384u;
+    if (per_node > shares_max) per_node = shares_max;
     if (per_node < 1) per_node = 1;
     dim3 grid(per_node, batch);
-    if (vec) hipLaunchKernelGGL(k_exact<true>, grid, dim3(kBlock), 0, st, a);
-    else hipLaunchKernelGGL(k_exact<false>, grid, dim3(kBlock), 0, st, a);
+    if (vec) hipLaunchKernelGGL(k_exact<true>, grid, dim3(1024), 0, st, a);
+    else hipLaunchKernelGGL(k_exact<false>, grid, dim3(1024), 0, st, a);
 }
 
 // direct = true: short candidate lists (each block reads the whole list; the fall-back rides in the same
@@ -1204,9 +1205,13 @@ void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st
 bool launch_output_from_candidates(const SelArgs &a, int batch, bool direct, bool vec, int cus, hipStream_t st) {
     if (direct) {
         const uint32_t out_blocks = (a.cap + 4095) / 4096;
-        // stand-by blocks of 1024 threads: as many threads per node as the stand-alone fall-back has
+        // stand-by blocks of 1024 threads, about one per compute unit shared by the nodes, as in the stand-alone
+        // launch.  Measured on tie-heavy input, where every call falls back (4 nodes x 25.6 M elements / 8 nodes x
+        // 67 M; the exact path chosen outright: 0.96 / 4.9 ms): a quarter as many blocks 3.04 / 15.6 ms, half as
+        // many 1.85 / 9.4 ms, this many 1.31 / 6.4 ms, twice as many 1.37 / 6.5 ms; a call that does not fall back
+        // takes the same time with any of them (the blocks decide and leave while the output blocks work).
         const uint32_t chunks = (a.n + 16383u) / 16384u;
-        uint32_t standby = (uint32_t)(cus / batch) / 4;
+        uint32_t standby = (uint32_t)(cus / batch);
         if (standby > chunks) standby = chunks;
         if (standby < 1) standby = 1;
         const dim3 grid(out_blocks + standby, batch);
