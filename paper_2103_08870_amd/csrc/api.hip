@@ -386,7 +386,7 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
         delete c;
         return fail(nullptr, LGC_ENOMEM, "hipMalloc of %zu bytes of scratch: %s", L.bytes, hipGetErrorString(e));
     }
-    // only the statistics and the two state sets must start at zero
+    // only the statistics, the carried thresholds and the two state sets must start at zero
     e = hipMemset(block, 0, L.samples);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -395,7 +395,7 @@ extern "C" lgc_status lgc_create(lgc_ctx **out, int device, uint64_t max_n, uint
         return fail(nullptr, LGC_EHIP, "hipMemset: %s", hipGetErrorString(e));
     }
     bind_scratch(c, block, L);
-    // the pinned word of the automatic path choice; without it (allocation refused) the choice is simply not adaptive
+    // the pinned words of the automatic path choice; without them (allocation refused) the choice is simply not adaptive
     void *pinned = nullptr, *pinned_dev = nullptr;
     if (hipHostMalloc(&pinned, 64, hipHostMallocMapped) == hipSuccess) {
         memset(pinned, 0, 64);
