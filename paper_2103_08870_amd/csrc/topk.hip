@@ -1209,7 +1209,7 @@ bool launch_output_from_candidates(const SelArgs &a, int batch, bool direct, boo
         // launch.  Measured on tie-heavy input, where every call falls back (4 nodes x 25.6 M elements / 8 nodes x
         // 67 M; the exact path chosen outright: 0.96 / 4.9 ms): a quarter as many blocks 3.04 / 15.6 ms, half as
         // many 1.85 / 9.4 ms, this many 1.31 / 6.4 ms, twice as many 1.37 / 6.5 ms; a call that does not fall back
-        // takes the same time with any of them (the blocks decide and leave while the output blocks work).
+        // takes 368.3, 368.9, 369.0 and 372.0 us with them (the blocks decide and leave while the output blocks work).
         const uint32_t chunks = (a.n + 16383u) / 16384u;
         uint32_t standby = (uint32_t)(cus / batch);
         if (standby > chunks) standby = chunks;
