@@ -161,8 +161,10 @@ def test_two_steps_in_a_hip_graph_replay_like_eager_calls(B, oracle):
     """The calls only enqueue kernels (no allocation, no host synchronisation, no memset once the
     scratch exists), so a stream capture of the path replays correctly.  The selection scratch
     alternates between two state sets from call to call, so a graph must hold an even number of
-    selection calls.  Every replay is compared with the same steps made eagerly."""
-    w = synth.workload(1, n=1_200_000, nodes=2)
+    selection calls.  Every replay is compared with the same steps made eagerly; there are enough replays for the
+    selections to start taking their thresholds from the trend of the earlier ones (the record of those is kept
+    on the device, so a replayed graph carries thresholds like eager calls do)."""
+    w = synth.workload(2, n=1 << 21, nodes=2)
     K, n, k = w.nodes, w.n, w.k
     ae, enc, dec, _ = make_ae(B, w.ae_channels)
     gs = [synth.gradients(w, t, device="cuda") for t in range(2)]
@@ -189,20 +191,24 @@ def test_two_steps_in_a_hip_graph_replay_like_eager_calls(B, oracle):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         two_steps(ctx_g, graphed)             # recorded, not run
-    for replay in range(3):
+    replays = 20
+    for replay in range(replays):
         graph.replay()
         two_steps(ctx_e, eager)
         torch.cuda.synchronize()
         for key in eager:                     # u, v carry over from replay to replay; dense accumulates
             assert torch.equal(eager[key].view(torch.int32), graphed[key].view(torch.int32)), (replay, key)
     assert B.lgc_stats(ctx_g)[2] == 0 and B.lgc_stats(ctx_e)[2] == 0
+    carried_e, carried_g = B.lgc_stats_carried(ctx_e), B.lgc_stats_carried(ctx_g)
+    print(f"selections with a carried threshold: eager {carried_e}, replayed graph {carried_g}, of {2 * replays * K} each")
+    assert carried_e > 0 and carried_g > 0, (carried_e, carried_g)   # the counts differ at most by what the warm-up's two records change
     # and the eager side agrees with the oracle on the last selection (so both do)
     hu = np.zeros((K, n), np.float32); hv = np.zeros((K, n), np.float32)
-    for rep in range(3):
+    ghs = [g.cpu().numpy() for g in gs]
+    for rep in range(replays):
         for t in range(2):
-            gh = gs[t].cpu().numpy()
-            for b in range(K):
-                oracle.accumulate(gh[b], hu[b], hv[b], w.momentum)
+            for b in (K - 1,):
+                oracle.accumulate(ghs[t][b], hu[b], hv[b], w.momentum)
                 ovals, oidx = oracle.topk(hv[b], hu[b], k)
     assert (graphed["idx"][K - 1].cpu().numpy().astype(np.uint32) == oidx).all() and same_bits(graphed["vals"][K - 1], ovals)
     ctx_e.close(); ctx_g.close(); ae.close()
