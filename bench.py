@@ -68,6 +68,9 @@ def parse():
     p.add_argument("--ae", choices=["config", "paper"], default="config",
                    help="config: the workload's two-layer autoencoder (default); paper: Table I / Table II layer "
                         "shapes (1-64-128-256-64-4 / 4-4-32-64-128-32-1, leaky slope 0.01), deep layers on the matrix cores")
+    p.add_argument("--state-iters", type=int, default=40,
+                   help="iterations of the step run before the warm-up, untimed, to bring the residuals u, v from zero "
+                        "to those of a run in progress (0: start the warm-up from zero residuals)")
     p.add_argument("--graph", action="store_true",
                    help="record two steps into a HIP graph and time its replays (steps must be even)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -254,8 +257,16 @@ def main():
 
     step = {"ps": step_ps, "rar": step_rar, "ps-innovation": step_ps_innovation}[args.pattern]
 
-    for t in range(args.warmup):
+    # The residuals u, v are inputs of a step as much as the gradients are.  They start at zero, and from zero the
+    # k-th largest magnitude grows by tens of per cent per iteration for the first iterations, which no training run
+    # does for more than its first moments: the timed steps work on the residuals of a run in progress, produced
+    # here by the path itself on the same gradient sets.
+    t_first = args.state_iters
+    for t in range(t_first):
         step(t)
+    for t in range(args.warmup):
+        step(t_first + t)
+    t_first += args.warmup
     torch.cuda.synchronize()
     B.lgc_stats(ctx)
     B.lgc_stats_carried(ctx)
@@ -279,7 +290,7 @@ def main():
             graph.replay()
     else:
         for t in range(args.steps):
-            step(args.warmup + t)
+            step(t_first + t)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     B.lgc_set_option(ctx, B.LGC_OPT_PROFILE, 0)
@@ -354,6 +365,9 @@ def main():
                                f"momentum {w.momentum}, autoencoder "
                                f"{'->'.join(map(str, w.ae_channels)) if args.ae == 'config' else 'Table I / Table II shapes'}, "
                                f"{sets} gradient sets resident in HBM",
+                   "state": (f"residuals u, v of a run in progress: {args.state_iters} iterations of the same step from zero "
+                             "residuals, untimed, before the warm-up" if args.state_iters else
+                             "residuals u, v zero at the start of the warm-up"),
                    "step": ("accumulate+top-k (fused, all nodes in one call) + encode + decode + scatter"
                             if seg is None else
                             f"accumulate + per-layer top-k over {len(seg_ks)} layers (fused, all nodes in one call) "
