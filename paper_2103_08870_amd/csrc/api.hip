@@ -139,29 +139,29 @@ uint32_t choose_rank(uint32_t n, uint32_t k) {
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
-void profile_begin(lgc_ctx *c, hipStream_t st) {
-    if (!c->opt_profile) return;
+// The pair of events that times the next streaming call (LGC_OPT_PROFILE), or none.  The launches stamp the events
+// themselves (start time of the first launch, end time of the last): nothing else enters the queue.
+Bracket profile_bracket(lgc_ctx *c) {
+    Bracket br;
+    if (!c->opt_profile) return br;
     if (c->ev_used + 2 > c->ev.size()) {
-        if (c->ev.size() >= 2 * 8192) return;  // pool exhausted: stop bracketing until the next read
+        if (c->ev.size() >= 2 * 8192) return br;  // pool exhausted: stop timing until the next read
         hipEvent_t a, b;
-        // timing only: no system-scope fence when the event completes (it would flush the caches around the kernel it times)
-        if (hipEventCreateWithFlags(&a, hipEventDisableSystemFence) != hipSuccess) return;
-        if (hipEventCreateWithFlags(&b, hipEventDisableSystemFence) != hipSuccess) { (void)hipEventDestroy(a); return; }
+        if (hipEventCreateWithFlags(&a, hipEventDisableSystemFence) != hipSuccess) return br;
+        if (hipEventCreateWithFlags(&b, hipEventDisableSystemFence) != hipSuccess) { (void)hipEventDestroy(a); return br; }
         try {
             c->ev.reserve(c->ev.size() + 2);
         } catch (...) {
             (void)hipEventDestroy(a); (void)hipEventDestroy(b);
-            return;
+            return br;
         }
         c->ev.push_back(a);
         c->ev.push_back(b);
     }
-    (void)hipEventRecord(c->ev[c->ev_used], st);
-}
-void profile_end(lgc_ctx *c, hipStream_t st) {
-    if (!c->opt_profile || c->ev_used + 2 > c->ev.size()) return;
-    (void)hipEventRecord(c->ev[c->ev_used + 1], st);
+    br.start = c->ev[c->ev_used];
+    br.stop = c->ev[c->ev_used + 1];
     c->ev_used += 2;
+    return br;
 }
 
 lgc_status check_common(lgc_ctx *ctx, uint64_t n, int batch, uint64_t stride) {
@@ -290,9 +290,7 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
                      (batch == 1 || stride % 4 == 0);
     if (k == 0) {
         if (fused) {
-            profile_begin(ctx, st);
-            launch_accumulate(g, u, v, (uint32_t)n, batch, stride, m, vec, st);
-            profile_end(ctx, st);
+            launch_accumulate(g, u, v, (uint32_t)n, batch, stride, m, vec, st, profile_bracket(ctx));
         }
         return LGC_OK;
     }
@@ -330,9 +328,7 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
     ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
     if (fast) {
         launch_sample(a, batch, fused, vec, st);   // also clears the next call's state set
-        profile_begin(ctx, st);
-        launch_candidates(a, batch, fused, vec, st);
-        profile_end(ctx, st);
+        launch_candidates(a, batch, fused, vec, st, profile_bracket(ctx));
         launch_gather(a, batch, st);
         a.force = 0;
         // the exact path as fall-back, for nodes the fast path hands back: with short candidate lists it rides in
@@ -341,9 +337,7 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
             launch_exact(a, batch, vec, ctx->cus, st);
     } else {
         if (fused) {
-            profile_begin(ctx, st);
-            launch_accumulate(g, u, v, (uint32_t)n, batch, stride, m, vec, st);
-            profile_end(ctx, st);
+            launch_accumulate(g, u, v, (uint32_t)n, batch, stride, m, vec, st, profile_bracket(ctx));
         }
         a.force = 1;   // exact path chosen outright (as five launches when the input is long); it also clears the next call's state set
         launch_exact(a, batch, vec, ctx->cus, st);
@@ -1129,16 +1123,12 @@ static lgc_status run_segmented(lgc_ctx *ctx, const lgc_segments *seg, const flo
     ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
     if (seg->n_sampled) {
         launch_seg_estimate(a, batch, fused, vec, st);   // also clears the next call's state set
-        profile_begin(ctx, st);
-        launch_candidates(a, batch, fused, vec, st);
-        profile_end(ctx, st);
+        launch_candidates(a, batch, fused, vec, st, profile_bracket(ctx));
         launch_gather(a, batch, st);
     } else {
         launch_clear(a.next_state, a.next_words, st);
         if (fused) {
-            profile_begin(ctx, st);
-            launch_accumulate(g, u, v, (uint32_t)seg->n, batch, stride, m, vec, st);
-            profile_end(ctx, st);
+            launch_accumulate(g, u, v, (uint32_t)seg->n, batch, stride, m, vec, st, profile_bracket(ctx));
         }
     }
     launch_seg_select(a, batch, vec, st);
@@ -1176,9 +1166,7 @@ static lgc_status gather_common(lgc_ctx *ctx, const float *g, float *u, float *v
     hipStream_t st = (hipStream_t)stream;
     if (g) {
         const bool vec = aligned(v, 16) && aligned(u, 16) && aligned(g, 16) && (batch == 1 || stride % 4 == 0);
-        profile_begin(ctx, st);
-        launch_accumulate(g, u, v, (uint32_t)n, batch, stride, momentum, vec, st);
-        profile_end(ctx, st);
+        launch_accumulate(g, u, v, (uint32_t)n, batch, stride, momentum, vec, st, profile_bracket(ctx));
     }
     launch_gather_at(v, u, stride, (uint32_t)n, batch, idx, (uint32_t)k, out_vals, ctx->stats, st);
     hipError_t e = hipGetLastError();

@@ -148,11 +148,16 @@ struct SelArgs {
 };
 
 // launchers (topk.hip) — all asynchronous on `st`
+// Timing of a streaming call's launches (null events: none): `start` is given the start time of the first
+// launch, `stop` the end time of the last one, by the launches themselves, with no packet of their own in the queue.
+struct Bracket {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
 void launch_accumulate(const float *g, float *u, float *v, uint32_t n, int batch, uint64_t stride,
-                       float momentum, bool vec, hipStream_t st);
+                       float momentum, bool vec, hipStream_t st, Bracket br = Bracket());
 void launch_clear(uint32_t *words, uint32_t count, hipStream_t st);
 void launch_sample(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
-void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st);
+void launch_candidates(const SelArgs &a, int batch, bool fused, bool vec, hipStream_t st, Bracket br = Bracket());
 void launch_gather(const SelArgs &a, int batch, hipStream_t st);
 bool launch_output_from_candidates(const SelArgs &a, int batch, bool direct, bool vec, int cus, hipStream_t st);
 void launch_exact(const SelArgs &a, int batch, bool vec, int cus, hipStream_t st);

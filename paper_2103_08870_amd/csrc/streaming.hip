@@ -7,6 +7,8 @@
 // 1024 elements.  One wavefront per row, twelve 16-byte loads in flight before anything depends on them,
 // non-temporal loads and stores, no LDS, no barrier, no atomics, nothing shared between wavefronts.
 
+#include <hip/hip_ext.h>
+
 #include "device_helpers.h"
 
 namespace lgc {
@@ -71,35 +73,52 @@ __global__ __launch_bounds__(kBlock) void k_accumulate(const float *__restrict__
     }
 }
 
-// Calls launch(node0, nodes, row_begin, row_end) for equal shares of at most kRowsPerLaunch rows:
-// several whole nodes per launch while they fit, else one node in row ranges.
+// Calls launch(node0, nodes, row_begin, row_end, events) for equal shares of at most kRowsPerLaunch rows:
+// several whole nodes per launch while they fit, else one node in row ranges.  `events` carries the bracket's
+// start event for the first share and its stop event for the last one.
 template <typename F>
-static void for_each_share(uint32_t nrows, int batch, F launch) {
-    if ((uint64_t)nrows * batch <= kRowsPerLaunch) { launch(0u, batch, 0u, nrows); return; }
+static void for_each_share(uint32_t nrows, int batch, Bracket br, F launch) {
+    if ((uint64_t)nrows * batch <= kRowsPerLaunch) { launch(0u, batch, 0u, nrows, br); return; }
     if (nrows <= kRowsPerLaunch) {
         const int fit = (int)(kRowsPerLaunch / nrows);              // nodes that fit one launch
         const int launches = (batch + fit - 1) / fit;
         const int per = (batch + launches - 1) / launches;          // evened out
-        for (int b = 0; b < batch; b += per) launch((uint32_t)b, batch - b < per ? batch - b : per, 0u, nrows);
+        for (int b = 0; b < batch; b += per) {
+            Bracket e;
+            if (b == 0) e.start = br.start;
+            if (b + per >= batch) e.stop = br.stop;
+            launch((uint32_t)b, batch - b < per ? batch - b : per, 0u, nrows, e);
+        }
         return;
     }
     const uint32_t ranges = (nrows + kRowsPerLaunch - 1) / kRowsPerLaunch;
     const uint32_t per = ((nrows + ranges - 1) / ranges + (uint32_t)kWaves - 1) / kWaves * kWaves;   // whole blocks
     for (int b = 0; b < batch; ++b)
-        for (uint32_t r = 0; r < nrows; r += per)
-            launch((uint32_t)b, 1, r, nrows - r < per ? nrows : r + per);
+        for (uint32_t r = 0; r < nrows; r += per) {
+            Bracket e;
+            if (b == 0 && r == 0) e.start = br.start;
+            if (b == batch - 1 && nrows - r <= per) e.stop = br.stop;
+            launch((uint32_t)b, 1, r, nrows - r < per ? nrows : r + per, e);
+        }
+}
+
+// An ordinary launch, or, with timing events, the launch form that stamps them itself.
+template <typename K, typename... Args>
+static void launch_timed(K kernel, dim3 grid, dim3 block, hipStream_t st, Bracket e, Args... args) {
+    if (e.start || e.stop) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, e.start, e.stop, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
 }
 
 void launch_accumulate(const float *g, float *u, float *v, uint32_t n, int batch, uint64_t stride,
-                       float momentum, bool vec, hipStream_t st) {
+                       float momentum, bool vec, hipStream_t st, Bracket br) {
     const uint32_t nrows = (n + kRow - 1) / kRow;
-    for_each_share(nrows, batch, [&](uint32_t node0, int nodes, uint32_t r0, uint32_t r1) {
+    for_each_share(nrows, batch, br, [&](uint32_t node0, int nodes, uint32_t r0, uint32_t r1, Bracket e) {
         // a share is passed as shifted pointers and its own length (row ranges keep 16-byte alignment)
         const size_t off = (size_t)node0 * stride + (size_t)r0 * kRow;
         const uint32_t len = (r1 == nrows ? n : r1 * (uint32_t)kRow) - r0 * (uint32_t)kRow;
         dim3 grid((r1 - r0 + kWaves - 1) / kWaves, nodes);
-        if (vec) hipLaunchKernelGGL(k_accumulate<true>, grid, dim3(kBlock), 0, st, g + off, u + off, v + off, len, stride, momentum);
-        else hipLaunchKernelGGL(k_accumulate<false>, grid, dim3(kBlock), 0, st, g + off, u + off, v + off, len, stride, momentum);
+        if (vec) launch_timed(k_accumulate<true>, grid, dim3(kBlock), st, e, g + off, u + off, v + off, len, stride, momentum);
+        else launch_timed(k_accumulate<false>, grid, dim3(kBlock), st, e, g + off, u + off, v + off, len, stride, momentum);
     });
 }
 
@@ -199,14 +218,14 @@ __global__ __launch_bounds__(kBlock) void k_candidates(SelArgs a) {
     }
 }
 
-void launch_candidates(const SelArgs &args, int batch, bool fused, bool vec, hipStream_t st) {
+void launch_candidates(const SelArgs &args, int batch, bool fused, bool vec, hipStream_t st, Bracket br) {
     const uint32_t nrows = (args.n + kRow - 1) / kRow;
     const bool seg = args.seg_t != nullptr;
-    for_each_share(nrows, batch, [&](uint32_t node0, int nodes, uint32_t r0, uint32_t r1) {
+    for_each_share(nrows, batch, br, [&](uint32_t node0, int nodes, uint32_t r0, uint32_t r1, Bracket e) {
         SelArgs a = args;
         a.node0 = node0; a.row_begin = r0; a.row_end = r1;
         dim3 grid((r1 - r0 + kWaves - 1) / kWaves, nodes);
-#define LGC_CAND(F, V, S) hipLaunchKernelGGL((k_candidates<F, V, S>), grid, dim3(kBlock), 0, st, a)
+#define LGC_CAND(F, V, S) launch_timed(k_candidates<F, V, S>, grid, dim3(kBlock), st, e, a)
         if (seg) {
             if (fused) { if (vec) LGC_CAND(true, true, true); else LGC_CAND(true, false, true); }
             else       { if (vec) LGC_CAND(false, true, true); else LGC_CAND(false, false, true); }

@@ -212,3 +212,28 @@ def test_two_steps_in_a_hip_graph_replay_like_eager_calls(B, oracle):
                 ovals, oidx = oracle.topk(hv[b], hu[b], k)
     assert (graphed["idx"][K - 1].cpu().numpy().astype(np.uint32) == oidx).all() and same_bits(graphed["vals"][K - 1], ovals)
     ctx_e.close(); ctx_g.close(); ae.close()
+
+
+def test_timing_of_the_streaming_launches(B):
+    """LGC_OPT_PROFILE: the streaming launches of a call are timed by events that the launches stamp themselves;
+    lgc_profile_read returns their summed duration and count and starts over."""
+    n, k, K = 3_000_000, 3000, 2
+    ctx = B.Context(n, k, K)
+    g = torch.randn((K, n), device="cuda") * 1e-3
+    u = torch.zeros((K, n), device="cuda"); v = torch.zeros((K, n), device="cuda")
+    vals = torch.zeros((K, k), device="cuda"); idx = torch.zeros((K, k), device="cuda", dtype=torch.int32)
+    B.lgc_accumulate_topk(ctx, g, u, v, 0.9, k, vals, idx)          # not timed: the option is off
+    assert B.lgc_profile_read(ctx) == (0.0, 0)
+    B.lgc_set_option(ctx, B.LGC_OPT_PROFILE, 1)
+    B.lgc_accumulate(ctx, g, u, v, 0.9)
+    B.lgc_topk(ctx, v, u, k, vals, idx)
+    B.lgc_accumulate_topk(ctx, g, u, v, 0.9, k, vals, idx)
+    ms, calls = B.lgc_profile_read(ctx)
+    # 24 MB read and 48 MB read + written per pass: between a few microseconds and a few milliseconds in all
+    assert calls == 3 and 0.005 < ms < 20.0, (ms, calls)
+    assert B.lgc_profile_read(ctx) == (0.0, 0)
+    B.lgc_set_option(ctx, B.LGC_OPT_PROFILE, 0)
+    B.lgc_accumulate(ctx, g, u, v, 0.9)
+    assert B.lgc_profile_read(ctx) == (0.0, 0)
+    assert B.lgc_stats(ctx)[2] == 0
+    ctx.close()
