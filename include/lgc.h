@@ -343,9 +343,10 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
  * and reaching the exact path through the failed fast path costs more than
  * taking it outright (4 nodes x 25.6 M elements of seven distinct values:
  * 1.31 ms against 0.96 ms per accumulate + top-k).
- * LGC_OPT_PROFILE: 1 = bracket the streaming kernel launches of lgc_accumulate /
+ * LGC_OPT_PROFILE: 1 = time the streaming kernel launches of lgc_accumulate /
  * lgc_topk / lgc_accumulate_topk, their per-layer forms and lgc_accumulate_gather
- * with HIP events (read by lgc_profile_read).
+ * with HIP events (read by lgc_profile_read): the first launch of a call stamps
+ * a start event, the last one a stop event; no other packet enters the queue.
  * LGC_OPT_CARRY_THRESHOLD (default 1): the fast path of lgc_topk /
  * lgc_accumulate_topk needs a threshold with a few more than k elements above
  * it before its pass over the vector.  It samples the vector for one; with this
