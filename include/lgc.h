@@ -348,17 +348,20 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
  * with HIP events (read by lgc_profile_read): the first launch of a call stamps
  * a start event, the last one a stop event; no other packet enters the queue.
  * LGC_OPT_CARRY_THRESHOLD (default 1): the fast path of lgc_topk /
- * lgc_accumulate_topk needs a threshold with a few more than k elements above
- * it before its pass over the vector.  It samples the vector for one; with this
+ * lgc_accumulate_topk (and, layer by layer, of their per-layer forms, for the
+ * layers long enough to be sampled) needs a threshold with a few more than k
+ * elements above it before its pass over the vector.  It samples the vector for one; with this
  * option on it may instead take one worked out on the device from the exact
  * k-th magnitudes of the context's last selections (Alg. 1 / Alg. 2 run
  * every iteration on the same residuals, whose k-th magnitude moves smoothly):
- * their trend continued by one step, lowered by the margin that the last
+ * their trend continued by one step, lowered by a margin: what the last
  * selection's own candidate count says holds half as many candidates again as
- * k.  That threshold is offered only after selections whose k-th magnitudes
- * each lay close (a third of the margin) to what the two before them
- * predicted, and only to the next selection of the context with the same n
- * and k.  Results do
+ * k (per layer: twice k_l), or three times the recent distance between the
+ * k-th magnitudes and what the two selections before them predicted, if that
+ * is more.  The threshold is offered only if the margin is expected to flag
+ * no more candidates than the list has room for, after four selections in a
+ * row, and only to the next selection of the context with the same n and k
+ * (per layer: the same plan).  Results do
  * not depend on it: a threshold that turns out too high or too low sends that
  * node to the exact path, as after a bad sample, and doubles the number of
  * selections in a row (4 at first, 128 at most) that must be on record before

@@ -40,8 +40,13 @@ struct lgc_ctx {
     uint32_t *seg_t = nullptr, *seg_cand = nullptr, *seg_row_prefix = nullptr;
     size_t seg_t_words = 0, seg_cand_words = 0;
     int opt_path = 0, opt_profile = 0, opt_carry = 1;
-    // Thresholds carried from one selection to the next (one record per node, device memory, see Carry)
+    // Thresholds carried from one selection to the next (one record per node, device memory, see Carry); for the
+    // per-layer selection one record per layer and node, sized with the rest of its scratch by lgc_reserve
     Carry *carry = nullptr;
+    Carry *seg_carry = nullptr;
+    size_t seg_carry_records = 0;
+    const lgc_segments *last_seg = nullptr;   // the plan of the previous selection, if that was a per-layer one
+    uint64_t last_seg_k = 0;
     // Automatic path choice: a selection stores its call number to one of two pinned host words (fell back /
     // served by the fast path); the host looks at them (an ordinary read, no synchronisation) when it queues the
     // next selection, and after fall-backs takes the exact path outright for a while before it tries the fast path again.
@@ -298,7 +303,12 @@ lgc_status run_select(lgc_ctx *ctx, const float *g, float *u, float *v, uint64_t
     {   // a carried threshold aims at 1.5 k candidates, or at what a sample would give where that is fewer (large k)
         const double sampled = expected_candidates((double)n, (double)k) / (double)k;
         a.carry_target = (float)log2(sampled < 1.5 ? sampled : 1.5);
+        // and is offered only if it is expected to flag no more than 2.2 k, and no more than the list holds with
+        // a third of the margin to spare (log scale)
+        const double room = 0.75 * log2((double)ctx->cap / (double)k);
+        a.carry_most = (float)(room < log2(2.2) ? room : log2(2.2));
     }
+    ctx->last_seg = nullptr;
     bool fast = ctx->opt_path != 1 && n >= kMinFastN;
     if (fast) {
         a.rank = choose_rank((uint32_t)n, (uint32_t)k);
@@ -412,6 +422,7 @@ extern "C" void lgc_destroy(lgc_ctx *ctx) {
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     if (ctx->act[0]) (void)hipFree(ctx->act[0]);
     if (ctx->seg_t) (void)hipFree(ctx->seg_t);
+    if (ctx->seg_carry) (void)hipFree(ctx->seg_carry);
     if (ctx->seg_cand) (void)hipFree(ctx->seg_cand);
     if (ctx->seg_row_prefix) (void)hipFree(ctx->seg_row_prefix);
     if (ctx->scratch) (void)hipFree(ctx->scratch);
@@ -1070,6 +1081,7 @@ extern "C" uint64_t lgc_segments_total_k(const lgc_segments *seg) { return seg ?
 
 static bool seg_scratch_fits(const lgc_ctx *ctx, const lgc_segments *seg) {
     return (size_t)ctx->max_batch * seg->n_seg <= ctx->seg_t_words && ctx->seg_row_prefix &&
+           (size_t)ctx->max_batch * seg->n_seg <= ctx->seg_carry_records &&
            2 * (size_t)ctx->max_batch * seg->cap <= ctx->seg_cand_words;
 }
 
@@ -1083,6 +1095,13 @@ static lgc_status ensure_seg_scratch(lgc_ctx *ctx, const lgc_segments *seg) {
     }
     if (!ctx->seg_row_prefix)
         HIP_TRY(ctx, hipMalloc((void **)&ctx->seg_row_prefix, (size_t)ctx->max_batch * ctx->rows * 4));
+    if (t_words > ctx->seg_carry_records) {
+        if (ctx->seg_carry) { HIP_TRY(ctx, hipDeviceSynchronize()); HIP_TRY(ctx, hipFree(ctx->seg_carry)); ctx->seg_carry = nullptr; ctx->seg_carry_records = 0; }
+        HIP_TRY(ctx, hipMalloc((void **)&ctx->seg_carry, t_words * sizeof(Carry)));
+        ctx->seg_carry_records = t_words;
+        HIP_TRY(ctx, hipMemset(ctx->seg_carry, 0, t_words * sizeof(Carry)));
+        ctx->last_seg = nullptr;
+    }
     const size_t c_words = 2 * (size_t)ctx->max_batch * seg->cap;
     if (c_words > ctx->seg_cand_words) {
         if (ctx->seg_cand) { HIP_TRY(ctx, hipDeviceSynchronize()); HIP_TRY(ctx, hipFree(ctx->seg_cand)); ctx->seg_cand = nullptr; ctx->seg_cand_words = 0; }
@@ -1120,6 +1139,14 @@ static lgc_status run_segmented(lgc_ctx *ctx, const lgc_segments *seg, const flo
     a.row_seg = seg->row_seg; a.seg_t = ctx->seg_t; a.row_prefix = ctx->seg_row_prefix;
     a.cap = seg->cap;
     a.cand_idx = ctx->seg_cand; a.cand_val = ctx->seg_cand + (size_t)ctx->max_batch * seg->cap;
+    // per-layer thresholds carried from the previous selection, if that was one with this plan (a layer's record also
+    // names its length and k); the list holds 4.5 k candidates in all (a layer's sample flags 3 k_l), a carried
+    // threshold aims at 2 k_l and may be expected to flag 3.2 k_l at most, or k_l + 256 in a layer of few
+    a.seg_carry = ctx->opt_carry && !ctx->single_state ? ctx->seg_carry : nullptr;
+    a.carry_fresh = !(ctx->last_seg == seg && ctx->last_seg_k == seg->total_k);
+    a.carry_target = (float)log2(2.0);
+    a.carry_most = (float)log2(3.2);
+    ctx->last_seg = seg; ctx->last_seg_k = seg->total_k;
     ctx->cur ^= 1;  // this call uses the clean set and cleans the other one for the next call
     if (seg->n_sampled) {
         launch_seg_estimate(a, batch, fused, vec, st);   // also clears the next call's state set
@@ -1245,6 +1272,8 @@ extern "C" lgc_status lgc_set_option(lgc_ctx *ctx, lgc_option opt, int64_t value
                 if (!guard.ok) return fail(ctx, LGC_EHIP, "cannot select device %d", ctx->device);
                 HIP_TRY(ctx, hipDeviceSynchronize());
                 HIP_TRY(ctx, hipMemset(ctx->carry, 0, (size_t)ctx->max_batch * sizeof(Carry)));
+                if (ctx->seg_carry) HIP_TRY(ctx, hipMemset(ctx->seg_carry, 0, ctx->seg_carry_records * sizeof(Carry)));
+                ctx->last_seg = nullptr;
             }
             return LGC_OK;
     }

@@ -77,7 +77,7 @@ struct Stats {
 // writing it, on the device: the fast path its outcome, the exact path and the per-layer selection "nothing on
 // record" (len = 0, no offer); so the record is always the previous selection's, also in a replayed HIP graph.
 struct Carry {
-    uint32_t unused;
+    uint32_t carried_now; // per-layer selection: the layer's threshold of the call under way was taken from this record
     uint32_t n, k;        // its vector length and k: the record only serves a selection of the same shape
     uint32_t len;         // fast-path selections in a row so far (counted up to 255; 0: none)
     float log2_t[3];      // log2 |T*| of the last min(len, 3) selections, latest first
@@ -113,6 +113,9 @@ struct SelArgs {
     uint32_t notify_value;
     Carry *carry;             // [batch] thresholds carried from selection to selection (null: always sample)
     float carry_target;       // log2 of (candidates aimed at by a carried threshold) / k
+    float carry_most;         // log2 of (most candidates a carried threshold may be expected to flag) / k
+    Carry *seg_carry;         // per-layer selection: [batch][n_seg] records, one per layer and node (null: always sample)
+    uint32_t carry_fresh;     // per-layer selection: the records are not the previous selection's
     // current state set
     Sel *sel;
     Ctr *ctr;

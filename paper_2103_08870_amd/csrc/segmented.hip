@@ -18,6 +18,7 @@
 // kept values in index order.  No communication
 // between blocks, no waiting.
 
+#include "carry.h"
 #include "device_helpers.h"
 
 namespace lgc {
@@ -101,6 +102,16 @@ __global__ __launch_bounds__(1024) void k_seg_estimate(SelArgs a) {
     if (packed == 0) { if (tid == 0) *out = 0xffffffffu; return; }
     const uint32_t rank = packed & 0xffffu, threads = packed >> 16;   // 16 keys per sampling thread
     const uint32_t lo = a.seg_off[l], hi = a.seg_off[l + 1];
+    if (a.seg_carry) {   // the layer's threshold offered by its previous selection (carry.h), if there is one
+        Carry *c = a.seg_carry + (size_t)node * a.n_seg + l;
+        const uint32_t t = a.carry_fresh ? 0u : c->next_t_est;
+        const bool take = t != 0 && c->n == hi - lo && c->k == a.seg_k[l];   // the same for the whole block
+        if (tid == 0) {
+            c->carried_now = take;
+            if (take) { *out = t; atomicAdd(&a.stats->carried, 1u); }
+        }
+        if (take) return;
+    }
     // clusters of 32 elements (one 128-byte line per array) on 32-element boundaries of the vector,
     // inside the segment, one at a jittered place in each of threads/2 equal strata; two
     // neighbouring threads read the two halves of a cluster
@@ -179,7 +190,7 @@ constexpr int kSelThreads = 512;          // most segments and candidate runs ar
 // SMALL: the source spans at most kSelKeep rounds (16 K entries from begin & ~3 on): it is read once
 // and kept in registers for all four sweeps (the layers' candidate runs and the small layers).
 template <bool ALIGNED, bool DENSE, bool SMALL>
-__device__ __forceinline__ void select_in_block(const uint32_t *__restrict__ bits, const uint32_t *__restrict__ pos,
+__device__ __forceinline__ uint32_t select_in_block(const uint32_t *__restrict__ bits, const uint32_t *__restrict__ pos,
                                                 const uint32_t begin, const uint32_t end, const uint32_t k,
                                                 float *__restrict__ v, float *__restrict__ u,
                                                 uint32_t *__restrict__ oidx, float *__restrict__ oval,
@@ -298,6 +309,7 @@ __device__ __forceinline__ void select_in_block(const uint32_t *__restrict__ bit
     }
     // every thread holds the block's totals: the selection must add up to k
     if (tid == 0 && run_g + (run_e < quota ? run_e : quota) != k) atomicAdd(&stats->errors, 1u);
+    return thr;   // the exact k-th largest key
 }
 
 // One block per (segment, node).
@@ -356,16 +368,25 @@ __global__ __launch_bounds__(kSelThreads) void k_seg_select(SelArgs a) {
         if (threadIdx.x == 0) atomicAdd(from_list ? &a.stats->fast : &a.stats->fallback, 1u);
     }
     constexpr uint32_t kSmall = (uint32_t)kSelKeep * kSelThreads * 4u;
+    uint32_t thr;
     if (from_list) {
         if (p1 - (p0 & ~3u) <= kSmall)
-            select_in_block<true, false, true>(cval, cidx, p0, p1, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+            thr = select_in_block<true, false, true>(cval, cidx, p0, p1, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
         else
-            select_in_block<true, false, false>(cval, cidx, p0, p1, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+            thr = select_in_block<true, false, false>(cval, cidx, p0, p1, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
     } else {
         if (hi - (lo & ~3u) <= kSmall)
-            select_in_block<VEC, false, true>((const uint32_t *)v, nullptr, lo, hi, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+            thr = select_in_block<VEC, false, true>((const uint32_t *)v, nullptr, lo, hi, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
         else
-            select_in_block<VEC, false, false>((const uint32_t *)v, nullptr, lo, hi, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+            thr = select_in_block<VEC, false, false>((const uint32_t *)v, nullptr, lo, hi, k, v, u, oidx, oval, nullptr, a.stats, hist, wave_tmp, res, sh_g, sh_e);
+    }
+    // sampled layers: the record of this layer's exact thresholds, and its offer to the next selection
+    if (a.seg_carry && a.seg_rank[l] != 0 && threadIdx.x == 0) {
+        Carry *c = a.seg_carry + (size_t)node * a.n_seg + l;
+        // a layer that keeps few values may flag k + 256: what its k-th magnitude does is noisy, and the candidates cost nothing
+        const float most = fmaxf(a.carry_most, log2f((float)(k + 256u) / (float)k));
+        carry_update(c, hi - lo, k, a.carry_fresh != 0, from_list, c->carried_now != 0, thr,
+                     a.seg_t[(size_t)node * a.n_seg + l], p1 - p0, a.carry_target, most);
     }
 }
 

@@ -24,6 +24,7 @@
 //  the phases out through tickets when it is the fast path's fall-back, five launches of many blocks when it
 //  is chosen outright for a long input.
 
+#include "carry.h"
 #include "device_helpers.h"
 
 namespace lgc {
@@ -381,16 +382,7 @@ __device__ __forceinline__ void count_candidates(const uint32_t *cval, uint32_t 
 // ------------------------------------------------------------------ exact k-th key among the candidates
 
 // What the one thread that knows a selection's outcome on the fast path leaves behind: the node's state for the
-// kernels after it, the statistics, the word the host polls, and the record of carried thresholds.
-// The record: log2 |T*| of up to three selections in a row.  With three, T* of the next selection is predicted on
-// the line through the last two; the distance kept below the prediction is the one that would have put half as
-// many candidates again as k (or as many as a sample would give, if that is fewer) above this selection's T*
-// (from this selection's own count: the candidates above
-// t_est were `total`, so log(count) falls by log(total / k) over log2 T* - log2 t_est).  The threshold is offered
-// only if the recent selections' T* (this one's, and with fading weight those before it) each lay within a third of
-// that distance from what the two selections before them predicted;
-// a wrong offer costs the next selection its fast path (too few candidates, or too many for the list), never
-// its result, and doubles the number of fast-path selections in a row that the next offer waits for (4, 8, ... 128).
+// kernels after it, the statistics, the word the host polls, and the record of carried thresholds (carry.h).
 __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node, Sel *s, const bool ok, const uint32_t thr,
                                                const uint32_t quota, const uint32_t total, const uint32_t t_est) {
     s->fast_ok = ok;
@@ -398,37 +390,7 @@ __device__ __forceinline__ void report_outcome(const SelArgs &a, const int node,
     atomicAdd(ok ? &a.stats->fast : &a.stats->fallback, 1u);
     // the host sees the outcome without synchronising; a carried threshold that failed says nothing about the data
     if (a.notify && (ok || !s->carried)) st_system32(a.notify + (ok ? 1 : 0), a.notify_value);
-    if (!a.carry) return;
-    Carry *c = a.carry + node;
-    const bool same = c->n == a.n && c->k == a.k;           // the record is the previous selection's, of this shape
-    const bool follows = same && c->len > 0;
-    const float l1 = c->log2_t[0], l2 = c->log2_t[1];
-    uint32_t len = 0, next = 0, fails = same ? c->fails : 0u, held = same ? c->held : 0u;
-    if (s->carried) {
-        if (!ok) { fails = fails < 5 ? fails + 1 : 5u; held = 0; }
-        else if (++held >= 64) { fails = fails ? fails - 1 : 0u; held = 0; }
-    }
-    float l0 = 0.f, miss = 0.f;
-    constexpr uint32_t kMinNormal = 0x00800000u, kInf = 0x7f800000u;
-    if (ok && thr >= kMinNormal && thr < kInf && t_est >= kMinNormal && t_est < thr) {
-        l0 = log2f(__uint_as_float(thr));
-        len = follows ? (c->len < 255 ? c->len + 1 : 255u) : 1u;
-        if (len >= 3) miss = fmaxf(fabsf(l0 - (2.f * l1 - l2)), len > 3 ? 0.75f * c->miss : 0.f);
-        const float ratio = log2f((float)total / (float)a.k);   // > 0: total >= k
-        // two misses on record at least (four selections), more after offers that failed
-        if (len >= (4u << fails) && ratio >= 0.05f) {
-            const float used = l0 - log2f(__uint_as_float(t_est));
-            float gap = used * (a.carry_target / ratio);
-            gap = fminf(fmaxf(gap, 0.25f * used), 4.f * used);
-            if (used > 0.f && gap <= 0.25f && 3.f * miss <= gap) {
-                const uint32_t t = __float_as_uint(exp2f(2.f * l0 - l1 - gap));
-                if (t >= kMinNormal && t < kInf) next = t;
-            }
-        }
-    }
-    c->n = a.n; c->k = a.k; c->len = len;
-    c->log2_t[0] = l0; c->log2_t[1] = l1; c->log2_t[2] = l2;
-    c->next_t_est = next; c->fails = fails; c->held = held; c->miss = miss;
+    if (a.carry) carry_update(a.carry + node, a.n, a.k, false, ok, s->carried != 0, thr, t_est, total, a.carry_target, a.carry_most);
 }
 
 
