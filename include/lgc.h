@@ -356,7 +356,7 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
  * every iteration on the same residuals, whose k-th magnitude moves smoothly):
  * their trend continued by one step, lowered by a margin: what the last
  * selection's own candidate count says holds half as many candidates again as
- * k (per layer: twice k_l), or three times the recent distance between the
+ * k (per layer: twice k_l), or four times the recent distance between the
  * k-th magnitudes and what the two selections before them predicted, if that
  * is more.  The threshold is offered only if the margin is expected to flag
  * no more candidates than the list has room for, after four selections in a

@@ -6,8 +6,8 @@
 // prediction by a margin, the larger of
 //   * the distance that holds `target` times k candidates, from the slope that this selection measured itself:
 //     its candidates above t_est were `total`, so log2(count) falls by log2(total / k) over log2 T* - log2 t_est;
-//   * three times the recent miss: how far T* lay from what the two selections before it predicted, the largest
-//     of the recent selections (each selection's own, or three quarters of the value before).
+//   * four times the recent miss: how far T* lay from what the two selections before it predicted, the largest
+//     of the recent selections (each selection's own, or 0.85 of the value before).
 // The offer is made only if that margin is expected to hold no more than `most` times k candidates, after four
 // selections in a row (two misses on record), and after offers that failed only after twice as many each time
 // (8, 16, ... 128).  A wrong offer costs the next selection its fast path (too few candidates, or too many for
@@ -36,12 +36,12 @@ __device__ __forceinline__ void carry_update(Carry *c, const uint32_t n, const u
     if (ok && thr >= kMinNormal && thr < kInf && t_est >= kMinNormal && t_est < thr) {
         l0 = log2f(__uint_as_float(thr));
         len = follows ? (c->len < 255 ? c->len + 1 : 255u) : 1u;
-        if (len >= 3) miss = fmaxf(fabsf(l0 - (2.f * l1 - l2)), len > 3 ? 0.75f * c->miss : 0.f);
+        if (len >= 3) miss = fmaxf(fabsf(l0 - (2.f * l1 - l2)), len > 3 ? 0.85f * c->miss : 0.f);
         const float ratio = total > k ? log2f((float)total / (float)k) : 0.f;
         const float used = l0 - log2f(__uint_as_float(t_est));
         if (len >= (4u << fails) && ratio >= 0.05f && used > 0.f) {
             const float slope = ratio / used;                // log2(count) per log2(threshold)
-            const float gap = fmaxf(fminf(fmaxf(target / slope, 0.25f * used), 4.f * used), 3.f * miss);
+            const float gap = fmaxf(fminf(fmaxf(target / slope, 0.25f * used), 4.f * used), 4.f * miss);
             if (gap <= 0.25f && gap * slope <= most) {
                 const uint32_t t = __float_as_uint(exp2f(2.f * l0 - l1 - gap));
                 if (t >= kMinNormal && t < kInf) next = t;

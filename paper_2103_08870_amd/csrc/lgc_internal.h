@@ -86,7 +86,7 @@ struct Carry {
                           // selections in a row required before the next offer, 64 carried selections that held take one off
     uint32_t held;        // carried selections that held since `fails` last changed
     float miss;           // how far T* lay from the trend of the two selections before it (log2), largest of the
-                          // recent selections: each selection's own miss, or three quarters of the value before
+                          // recent selections: each selection's own miss, or 0.85 of the value before
     uint32_t pad[5];
 };
 static_assert(sizeof(Carry) == 64, "Carry is one 64-byte record");
