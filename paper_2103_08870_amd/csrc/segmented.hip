@@ -5,7 +5,7 @@
 // magnitudes (same key and tie rule as the flat selection), and the kept values of all segments
 // are concatenated in segment order.
 //
-// How: segments of at least 16 K elements with a small k_l / n_l are "sampled": one block per
+// How: segments of at least 8 K elements with a small k_l / n_l are "sampled": one block per
 // (segment, node) reads about n_l / 64 keys (whole 128-byte lines at jittered places, at most 16 K
 // keys), finds an order statistic of them in LDS and publishes it as the segment's candidate
 // threshold; the streaming candidate pass and
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(1024) void k_seg_estimate(SelArgs a) {
     // neighbouring threads read the two halves of a cluster
     const uint32_t c0 = (lo + 31u) >> 5, c1 = hi >> 5;
     const uint32_t clusters = threads >> 1;
-    const uint32_t stratum = (c1 - c0) / clusters;           // >= 1: a sampled segment has >= 16 K elements
+    const uint32_t stratum = (c1 - c0) / clusters;           // >= 3: a sampled segment has >= 8 K elements, i.e. 255 whole clusters for at most 64
     const bool active = tid < threads;
     const uint32_t ci = tid >> 1;
     const uint32_t cl = c0 + ci * stratum + seg_mix(ci * 0x9E3779B9u + l * 0x85EBCA6Bu + (uint32_t)node) % stratum;

@@ -82,8 +82,8 @@ def test_small_segments_selected_from_v(B, oracle, n, n_seg, batch, pad):
 def mixed_layout():
     """Sampled and direct segments side by side, boundaries at odd places (rows of 1024 elements
     that hold several segments, segments that start and end inside a row)."""
-    sizes = [100, 70_001, 5, 200_000, 65_536, 999_999, 3_000, 64, 64, 64, 300_000, 1, 131_073, 450_000, 16_383, 777,
-             16_384, 33]
+    sizes = [100, 70_001, 5, 200_000, 65_536, 999_999, 3_000, 64, 64, 64, 300_000, 1, 131_073, 450_000, 8_191, 777,
+             8_192, 33]
     off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
     ks = [max(1, s // 1000) for s in sizes]
     ks[2] = 5            # whole segment
@@ -123,7 +123,7 @@ def test_mixed_segments(B, oracle, fused, aligned_base):
         assert (oidx[0].cpu().numpy().astype(np.uint32) == idx).all() and same_bits(ovals[0], vals)
         assert same_bits(dv[1:], v1) and same_bits(du[1:], u1)
         batch = 1
-    # sampled: 70 001, 200 000, 65 536, 999 999, 131 073, 450 000, 16 384 (not the dense one, not 16 383)
+    # sampled: 70 001, 200 000, 65 536, 999 999, 131 073, 450 000, 8 192 (not the dense one, not 8 191)
     assert fast == 7 * batch and fallback == 0
     seg.close(); ctx.close()
 
@@ -192,7 +192,7 @@ def test_full_size_resnet50_layers(B, oracle):
     w = synth.workload(2)
     off, ks = synth.layer_plan(w)
     K = sum(ks)
-    sampled = sum(1 for a, b in zip(off, off[1:]) if b - a >= 16_384)
+    sampled = sum(1 for a, b in zip(off, off[1:]) if b - a >= 8_192)
     ctx = B.Context(w.n, K, w.nodes)
     seg = B.Segments(off, ks)
     B.lgc_reserve(ctx, seg=seg)
@@ -220,7 +220,7 @@ def test_layer_thresholds_carried_at_full_size(B, oracle):
     w = synth.workload(2)
     off, ks = synth.layer_plan(w)
     K = sum(ks)
-    sampled = sum(1 for a, b in zip(off, off[1:]) if b - a >= 16_384)
+    sampled = sum(1 for a, b in zip(off, off[1:]) if b - a >= 8_192)
     ctx = B.Context(w.n, K, w.nodes)
     seg = B.Segments(off, ks)
     B.lgc_reserve(ctx, seg=seg)
