@@ -347,6 +347,7 @@ lgc_status lgc_reserve(lgc_ctx *ctx, const lgc_ae *ae /* nullable */, uint64_t k
  * lgc_topk / lgc_accumulate_topk, their per-layer forms and lgc_accumulate_gather
  * with HIP events (read by lgc_profile_read): the first launch of a call stamps
  * a start event, the last one a stop event; no other packet enters the queue.
+ * Leave it off while a stream is being captured into a HIP graph.
  * LGC_OPT_CARRY_THRESHOLD (default 1): the fast path of lgc_topk /
  * lgc_accumulate_topk (and, layer by layer, of their per-layer forms, for the
  * layers long enough to be sampled) needs a threshold with a few more than k
